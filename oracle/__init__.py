@@ -1,0 +1,24 @@
+"""CPU oracle for the paged-attention decode + KV swapping path.
+
+TEST INFRASTRUCTURE ONLY.  This package is a plain, slow, float64 statement of
+what the path computes.  Only the test-suite, the smoke check and the
+benchmark's `cpu_baseline` leg may import it; the product (the HIP library and
+its Python binding) never does, and this package imports nothing of the
+product.
+
+Pinned by (see tests/test_oracle_*.py):
+  attention.paged_attention_decode  - brute-force dense softmax attention on
+      tiny inputs, closed forms (ctx = 1, constant V, equal keys, peaked
+      softmax, key-shift invariance), GQA == MHA with repeated heads, a library
+      cross-check, residency independence.
+  pool_model.PoolModel              - conservation invariants, byte-identical
+      swap round trips, brute-force dictionary bookkeeping.
+  expansion.*                       - the worked example's printed 1.28 (= 9/7),
+      the buffered form on the same example, the 800 KB-per-token figure.
+  controller_sim.AdaptiveExpansion  - the closed-form fixed point of the
+      transparency condition, the worked example's m = 4, start-at-zero,
+      shrink-after-slowdown, spike tolerance, plateau.
+  fifo_sim.simulate                 - the worked example's four-layer trace,
+      queue length and residence time.
+Absolute throughput numbers: parity unpinned (the paper prints none for this path).
+"""
