@@ -1,0 +1,273 @@
+/*
+ * pie.h - C ABI of the MI355X paged-attention decode path with
+ * performance-transparent KV-cache swapping.
+ *
+ * The path follows the paper "Pie: Pooling CPU Memory for LLM Inference":
+ *   - Section 3.2 (architecture, mapping table, two-phase update, presence
+ *     check before a layer is computed),
+ *   - Section 3.3 (prefetch of the data the next layer needs behind the current
+ *     layer's computation),
+ *   - Section 3.4.2 and Section 1 (adaptive expansion and its three growth
+ *     conditions),
+ *   - Section 4.1 (block manager: free list, base pointer + unchanged offset).
+ * The unit of residency is a KV block (16 tokens of one layer, all KV heads,
+ * keys and values) instead of a whole layer: a logical block, named by a
+ * handle, is homed in the same slot of every layer of either the GPU pool or
+ * the pinned-host pool.
+ *
+ * Conventions
+ *   - Every function returns 0 (PIE_OK) or a negative error code; nothing
+ *     throws or aborts across this boundary.  On error no state has changed
+ *     unless stated otherwise.
+ *   - Pointers named d_* are device pointers, h_* host pointers.  `stream`
+ *     arguments are hipStream_t passed as void*; NULL is the default stream.
+ *   - No function blocks the host unless its name ends in _sync.
+ *   - Ownership: the caller allocates the device buffer, the pinned host buffer
+ *     and the streams, and frees them after pie_pool_destroy.  The library
+ *     allocates no device memory at any time.
+ *   - One pool is driven by one host thread; attention / append calls of one
+ *     pool go to one compute stream at a time.
+ *   - Block layout (both pools): [layer][slot][K|V][kv_head][token][head_dim],
+ *     row-major, element type as in pie_config.dtype.  In the device buffer a
+ *     layer holds n_gpu_blocks resident slots, then staging region 0, then
+ *     staging region 1 (n_stage_blocks each).
+ *   - Handles are int32 in [0, n_gpu_blocks + n_host_blocks); -1 marks an
+ *     unused block-table entry.
+ */
+#ifndef PIE_H
+#define PIE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define PIE_OK      0
+#define PIE_EINVAL (-1)  /* bad argument */
+#define PIE_ENOMEM (-2)  /* pool, staging region or buffer too small */
+#define PIE_ESTATE (-3)  /* operation not valid for the block's / pool's state */
+#define PIE_EHIP   (-4)  /* HIP runtime error; see pie_last_hip_error */
+
+#define PIE_DTYPE_F32  0
+#define PIE_DTYPE_F16  1
+#define PIE_DTYPE_BF16 2
+
+#define PIE_WHERE_GPU  0
+#define PIE_WHERE_HOST 1
+
+/* swap paths (pie_set_swap_path) */
+#define PIE_SWAP_AUTO   0  /* copy engine for few long runs, kernel otherwise */
+#define PIE_SWAP_DMA    1  /* one hipMemcpyAsync per contiguous run of slots */
+#define PIE_SWAP_KERNEL 2  /* gather / scatter kernel reading or writing pinned host memory directly */
+
+typedef struct pie_pool pie_pool;
+typedef struct pie_controller pie_controller;
+
+typedef struct {
+  int32_t n_layers;
+  int32_t n_q_heads;
+  int32_t n_kv_heads;        /* divides n_q_heads */
+  int32_t head_dim;          /* 64 or 128 */
+  int32_t block_tokens;      /* 16 */
+  int32_t dtype;             /* PIE_DTYPE_* */
+  int32_t n_gpu_blocks;      /* resident slots per layer */
+  int32_t n_stage_blocks;    /* slots per staging region (there are two) */
+  int32_t n_host_blocks;     /* host slots per layer */
+  int32_t max_batch;         /* sizes the split-context workspace */
+  int32_t max_blocks_per_seq;/* likewise; also the largest block-table width accepted */
+  float   softmax_scale;     /* 0 => 1/sqrt(head_dim) */
+} pie_config;
+
+/* Filled by pie_get_stats; times in milliseconds, from HIP events of the last pie_step. */
+typedef struct {
+  int32_t n_layers;
+  int32_t host_blocks_in_use;   /* handles currently homed on the host */
+  int32_t gpu_blocks_in_use;
+  float   host_fraction;        /* host / (host + gpu) blocks in use */
+  float   expansion_simple;     /* 1 / (1 - f): Section 3.1 */
+  float   expansion_staged;     /* L / (L (1 - f) + 2 f): Section 3.3's buffer-corrected ratio, block form */
+  float   step_ms;              /* first layer's start to last layer's end on the compute stream */
+  float   attn_ms;              /* sum over layers of append + attention time */
+  float   swap_in_ms;           /* sum over layers */
+  float   swap_out_ms;
+  float   stall_ms;             /* sum over layers of time the compute stream idled before a layer */
+  uint64_t bytes_in;            /* host -> GPU bytes moved by the last pie_step */
+  uint64_t bytes_out;
+  uint32_t device_error_flags;  /* PIE_DEVERR_* collected by pie_check_errors_sync calls so far */
+} pie_stats;
+
+#define PIE_DEVERR_BAD_HANDLE   1u  /* a block-table entry outside [0, n_handles) inside a sequence's context */
+#define PIE_DEVERR_NOT_PRESENT  2u  /* a block that is neither GPU-homed nor staged for this layer */
+
+/* ---- pool (Section 4.1 block manager; Section 3.2 mapping table) -------- */
+
+/* Bytes the caller must provide: device buffer (KV slots incl. staging, handle maps, split workspace)
+ * and pinned host buffer (host slots).  PIE_EINVAL for an unsupported config. */
+int pie_pool_bytes_required(const pie_config* cfg, size_t* d_bytes, size_t* h_bytes);
+
+/* Creates a pool over caller-owned memory.  d_base: device memory, 256-byte aligned, >= d_bytes required.
+ * h_pinned_base: page-locked host memory the GPU can address (hipHostMalloc / torch pin_memory), >= h_bytes
+ * required; may be NULL when n_host_blocks == 0.  Passing d_base == NULL creates a bookkeeping-only pool
+ * (allocator, residency, tables; any call that would touch the device returns PIE_ESTATE) - used to test
+ * host logic without a GPU.  Neither buffer is cleared.  PIE_ENOMEM if a buffer is too small. */
+int pie_pool_init(const pie_config* cfg, void* d_base, size_t d_bytes,
+                  void* h_pinned_base, size_t h_bytes, pie_pool** out);
+
+/* Waits for the pool's outstanding work, destroys its events, frees its host bookkeeping.  Caller buffers
+ * are untouched. */
+int pie_pool_destroy(pie_pool* pool);
+
+/* Takes n blocks from pool `where`: the n lowest free handles paired, ascending, with the n lowest free
+ * slots.  All or nothing: PIE_ENOMEM if fewer than n slots (or handles) are free. */
+int pie_block_alloc(pie_pool* pool, int32_t where, int32_t n, int32_t* out_handles);
+
+/* Returns blocks to their free lists.  PIE_EINVAL for a handle out of range, PIE_ESTATE for one that is not
+ * allocated or is repeated; all or nothing.  The caller must not free blocks that enqueued work still reads. */
+int pie_block_free(pie_pool* pool, int32_t n, const int32_t* handles);
+
+/* Home of each handle: out_where[i] = PIE_WHERE_* or -1 if unallocated, out_slot[i] = slot in that pool. */
+int pie_block_where(pie_pool* pool, int32_t n, const int32_t* handles, int32_t* out_where, int32_t* out_slot);
+
+/* Staged copy of each handle in staging region `region` (0/1): out_stage_slot[i] = slot in the device pool
+ * (n_gpu_blocks + region * n_stage_blocks + rank) or -1; out_state[i] = 0 not staged, 1 copy in flight,
+ * 2 present (the region's swap-in event has completed - the second phase of the mapping-table update). */
+int pie_block_staged(pie_pool* pool, int32_t region, int32_t n, const int32_t* handles,
+                     int32_t* out_stage_slot, int32_t* out_state);
+
+/* Number of free slots in a pool. */
+int pie_pool_free_count(pie_pool* pool, int32_t where, int32_t* out_n);
+
+/* Device / host address of a block's bytes for one layer (slot in the device pool, staging included, or in
+ * the host pool), for callers that fill or inspect the cache directly. */
+int pie_block_address(pie_pool* pool, int32_t where, int32_t layer, int32_t slot, void** out_ptr);
+
+/* ---- swaps (Section 3.2 two-phase update; Section 3.3) ------------------ */
+
+/* Prefetch: copies layer `layer` of the n host-homed blocks into staging region (layer & 1); handles[i] lands
+ * in staging slot i, replacing whatever the region held.  Asynchronous on `stream`; the stream first waits
+ * for earlier readers and write-backs of the region.  The block becomes "present" when the copy's event
+ * completes; pie_attn_decode / pie_kv_append of that layer wait for it on their stream.
+ * PIE_ENOMEM if n > n_stage_blocks; PIE_ESTATE if a handle is not allocated, not host-homed or repeated. */
+int pie_swap_in(pie_pool* pool, int32_t layer, int32_t n, const int32_t* handles, void* stream);
+
+/* Write-back: copies the staged copies of `layer` for the n handles to their host slots.  The handles must
+ * be staged in region (layer & 1) and the region must hold `layer` (PIE_ESTATE otherwise).  Asynchronous on
+ * `stream`, after the compute stream's work on that layer enqueued so far. */
+int pie_swap_out(pie_pool* pool, int32_t layer, int32_t n, const int32_t* handles, void* stream);
+
+/* Re-homes blocks, all layers, in pool `to_where` (lowest free slots, in list order); handles already there
+ * are skipped; staged copies of moved blocks are dropped.  Asynchronous on `stream`, ordered after compute
+ * work enqueued so far; later compute work waits for it.  PIE_ENOMEM (nothing moved) if the target lacks slots. */
+int pie_migrate(pie_pool* pool, int32_t n, const int32_t* handles, int32_t to_where, void* stream);
+
+/* Fixed-fraction mode (the paper's fixed expansion): of the n handles in `order`, the first
+ * floor(f*n + 0.5) are homed on the host and the rest on the GPU (blocks coming back move first).  The caller
+ * supplies the order (e.g. a seeded permutation) so that host sets are nested as f grows.  out_n_host may be
+ * NULL. */
+int pie_set_host_fraction(pie_pool* pool, float f, int32_t n, const int32_t* order, void* stream,
+                          int32_t* out_n_host);
+
+/* Chooses how swaps move bytes (PIE_SWAP_*). */
+int pie_set_swap_path(pie_pool* pool, int32_t path);
+
+/* Tokens of one sequence handled by one attention workgroup (rounded up to a multiple of 64, clamped to
+ * [256, 4096]); longer contexts are split and reduced.  Default 512. */
+int pie_set_attn_partition(pie_pool* pool, int32_t tokens);
+
+/* Workgroups the gather / scatter kernel may occupy (1..1024, default 64): it is bound by the host link,
+ * so few are enough and the rest of the GPU stays free for attention. */
+int pie_set_swap_workgroups(pie_pool* pool, int32_t n);
+
+/* ---- per-layer operations ------------------------------------------------ */
+
+/* Appends this step's key and value rows.  d_k, d_v: [batch][n_kv_heads][head_dim] in the pool's dtype.
+ * For sequence b the rows go to token position ctx_lens[b] - 1, i.e. block d_block_table[b][(ctx-1)/T], row
+ * (ctx-1)%T, in the block's GPU home or, for a host-homed block, its staged copy for this layer (the block
+ * is then dirty until pie_swap_out).  A host-homed block that is not staged raises PIE_DEVERR_NOT_PRESENT on
+ * the device and is skipped.  d_block_table: int32 [batch][max_blocks] of handles. */
+int pie_kv_append(pie_pool* pool, int32_t layer, const void* d_k, const void* d_v,
+                  const int32_t* d_block_table, int32_t max_blocks,
+                  const int32_t* d_ctx_lens, int32_t batch, void* stream);
+
+/* Decode attention for one layer: for sequence b and query head h (KV head h / (n_q_heads / n_kv_heads))
+ *   out[b][h] = sum_t softmax_t(scale * <q[b][h], K[b][g][t]>) V[b][g][t],  t < ctx_lens[b],
+ * reading K and V through the block table (Section 2.3's paged KV cache; the per-layer access of Section
+ * 3.2).  d_q, d_out: [batch][n_q_heads][head_dim] in the pool's dtype; accumulation is fp32.  ctx 0 gives
+ * zeros.  The stream first waits until the layer's staged blocks are present (the presence check).
+ * PIE_EINVAL if batch > max_batch or max_blocks > max_blocks_per_seq. */
+int pie_attn_decode(pie_pool* pool, int32_t layer, const void* d_q,
+                    const int32_t* d_block_table, int32_t max_blocks,
+                    const int32_t* d_ctx_lens, int32_t batch,
+                    void* d_out, void* stream);
+
+/* ---- the pipeline ---------------------------------------------------------- */
+
+/* One decode step over all layers.  h_prefetch: the n_prefetch host-homed handles this batch touches, in
+ * (sequence, logical block) order - the host cannot read the device block table, so the caller names them
+ * (pie_prefetch_list computes it from a host copy of the table).  h_dirty: the n_dirty of those that receive
+ * this step's token (host-homed tail blocks).  For l = 0..L-1: layer l+1's blocks are prefetched on
+ * swap_in_stream while layer l runs (append, then attention) on compute_stream; layer l's dirty blocks are
+ * written back on swap_out_stream afterwards.
+ * d_q_all, d_out_all: [L][batch][n_q_heads][head_dim]; d_k_new, d_v_new: [L][batch][n_kv_heads][head_dim]
+ * (NULL skips the append). */
+int pie_step(pie_pool* pool, const void* d_q_all, const void* d_k_new, const void* d_v_new,
+             const int32_t* d_block_table, int32_t max_blocks, const int32_t* d_ctx_lens, int32_t batch,
+             int32_t n_prefetch, const int32_t* h_prefetch, int32_t n_dirty, const int32_t* h_dirty,
+             void* d_out_all, void* compute_stream, void* swap_in_stream, void* swap_out_stream);
+
+/* Host-homed handles among h_block_table[b][j], j < ceil(ctx/T), in (b, j) order without repeats; and of
+ * those the tail blocks (entry (ctx-1)/T).  out arrays need room for batch*max_blocks and batch entries. */
+int pie_prefetch_list(pie_pool* pool, const int32_t* h_block_table, int32_t max_blocks,
+                      const int32_t* h_ctx_lens, int32_t batch,
+                      int32_t* out_prefetch, int32_t* out_n_prefetch, int32_t* out_dirty, int32_t* out_n_dirty);
+
+/* Turns per-layer event timing in pie_step on (1) or off (0, default). */
+int pie_set_timing(pie_pool* pool, int32_t on);
+
+/* Waits for everything the pool has enqueued on the streams it has seen. */
+int pie_pool_sync(pie_pool* pool);
+
+/* Summary of the last pie_step (timing must be on and the step complete: call after pie_pool_sync). */
+int pie_get_stats(pie_pool* pool, pie_stats* out);
+
+/* Per-layer times in ms of the last pie_step; each array has n_layers entries (NULL to skip one). */
+int pie_get_layer_times(pie_pool* pool, float* t_attn, float* t_in, float* t_out, float* t_stall);
+
+/* Reads and clears the device error flags after synchronising the pool. */
+int pie_check_errors_sync(pie_pool* pool, uint32_t* out_flags);
+
+/* ---- adaptive expansion (Section 3.4.2; growth conditions of Section 1) ---- */
+
+/* A controller over integer levels k in [0, k_max]; host fraction = k / units.  Starts at k = 0. */
+int pie_controller_create(int32_t units, int32_t k_max, pie_controller** out);
+int pie_controller_destroy(pie_controller* ctl);
+
+/* rho: growth keeps the predicted swap-in time within rho x compute; k_up good steps before growing;
+ * k_down consecutive bad steps before shrinking; probe_period steps before a ceiling is retried;
+ * plateau_eps: minimum relative throughput gain for a level to count as scaling; util_max: link
+ * utilisation at or above which growth stops; stall_eps: summed waits above this share of summed compute
+ * make a step bad. */
+int pie_controller_config(pie_controller* ctl, double rho, int32_t k_up, int32_t k_down, int32_t probe_period,
+                          double plateau_eps, double util_max, double stall_eps);
+
+/* Feeds one decode step's measurements (per-layer arrays of n_layers entries, any consistent time unit)
+ * and returns the level to use for the next step. */
+int pie_controller_observe(pie_controller* ctl, int32_t n_layers, const double* t_attn, const double* t_in,
+                           const double* t_stall, double link_util, double throughput, int32_t* out_level);
+
+int pie_controller_level(pie_controller* ctl, int32_t* out_level, int32_t* out_ceiling /* -1 = none */);
+
+/* Convenience: feeds the pool's last-step timings (timing on, step complete) to the controller. */
+int pie_controller_update(pie_pool* pool, pie_controller* ctl, double throughput, float* out_host_fraction);
+
+/* ---- diagnostics -------------------------------------------------------------- */
+int pie_last_hip_error(void);            /* hipError_t of the last PIE_EHIP on this thread, 0 if none */
+const char* pie_strerror(int code);      /* static string for a PIE_* code */
+int pie_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PIE_H */

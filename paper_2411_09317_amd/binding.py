@@ -1,0 +1,324 @@
+"""ctypes binding of libpie.so: argument marshalling only.
+
+Every step of the path (allocator, residency, swaps, attention, pipeline,
+controller) runs inside the native library; this module converts Python
+arguments to C ones, owns the torch tensors that back the pools, and raises
+`PieError` for negative return codes.  There is no fallback: if the library has
+not been built (`python -m paper_2411_09317_amd.build`) importing fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpie.so")
+
+OK, EINVAL, ENOMEM, ESTATE, EHIP = 0, -1, -2, -3, -4
+GPU, HOST = 0, 1
+SWAP_AUTO, SWAP_DMA, SWAP_KERNEL = 0, 1, 2
+DEVERR_BAD_HANDLE, DEVERR_NOT_PRESENT = 1, 2
+
+# every symbol include/pie.h declares
+SYMBOLS = [
+    "pie_pool_bytes_required", "pie_pool_init", "pie_pool_destroy", "pie_block_alloc", "pie_block_free",
+    "pie_block_where", "pie_block_staged", "pie_pool_free_count", "pie_block_address", "pie_swap_in", "pie_swap_out",
+    "pie_migrate", "pie_set_host_fraction", "pie_set_swap_path", "pie_set_attn_partition", "pie_set_swap_workgroups",
+    "pie_kv_append", "pie_attn_decode",
+    "pie_step", "pie_prefetch_list", "pie_set_timing", "pie_pool_sync", "pie_get_stats", "pie_get_layer_times",
+    "pie_check_errors_sync", "pie_controller_create", "pie_controller_destroy", "pie_controller_config",
+    "pie_controller_observe", "pie_controller_level", "pie_controller_update", "pie_last_hip_error", "pie_strerror",
+    "pie_version",
+]
+
+
+class PieError(RuntimeError):
+    def __init__(self, code: int, what: str = ""):
+        self.code = code
+        msg = _lib.pie_strerror(code).decode() if _lib is not None else str(code)
+        if code == EHIP and _lib is not None:
+            msg += f" (hipError {_lib.pie_last_hip_error()})"
+        super().__init__(f"{what}: {msg} [{code}]")
+
+
+class PieConfig(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in (
+        "n_layers", "n_q_heads", "n_kv_heads", "head_dim", "block_tokens", "dtype", "n_gpu_blocks", "n_stage_blocks",
+        "n_host_blocks", "max_batch", "max_blocks_per_seq")] + [("softmax_scale", C.c_float)]
+
+
+class PieStats(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("host_blocks_in_use", C.c_int32), ("gpu_blocks_in_use", C.c_int32),
+                ("host_fraction", C.c_float), ("expansion_simple", C.c_float), ("expansion_staged", C.c_float),
+                ("step_ms", C.c_float), ("attn_ms", C.c_float), ("swap_in_ms", C.c_float), ("swap_out_ms", C.c_float),
+                ("stall_ms", C.c_float), ("bytes_in", C.c_uint64), ("bytes_out", C.c_uint64),
+                ("device_error_flags", C.c_uint32)]
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2411_09317_amd.build` "
+                           "(there is no fallback path)")
+    # PyTorch owns the device memory and the streams handed to the library, so both must talk to the same
+    # HIP runtime: torch's wheel carries its own libamdhip64 (same soname as the system one); importing torch
+    # first makes the dynamic loader resolve the library's dependency to that already-loaded copy.
+    import torch  # noqa: F401
+    lib = C.CDLL(LIB_PATH)
+    lib.pie_strerror.restype = C.c_char_p
+    lib.pie_strerror.argtypes = [C.c_int]
+    return lib
+
+
+_lib = None
+_lib = _load()
+
+
+def lib():
+    return _lib
+
+
+def _i32(seq) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(seq, dtype=np.int32).ravel())
+
+
+def _ptr(a: np.ndarray):
+    return a.ctypes.data_as(C.POINTER(C.c_int32))
+
+
+def _check(code: int, what: str):
+    if code != OK:
+        raise PieError(code, what)
+
+
+def _stream_ptr(stream) -> C.c_void_p:
+    if stream is None:
+        return C.c_void_p(0)
+    if isinstance(stream, int):
+        return C.c_void_p(stream)
+    return C.c_void_p(stream.cuda_stream)
+
+
+def _dptr(t) -> C.c_void_p:
+    if t is None:
+        return C.c_void_p(0)
+    return C.c_void_p(t.data_ptr())
+
+
+class Pool:
+    """A KV pool over torch-owned memory.  device=None makes a bookkeeping-only pool (no GPU needed)."""
+
+    def __init__(self, n_layers, n_q_heads, n_kv_heads, head_dim, block_tokens, dtype, n_gpu_blocks, n_stage_blocks,
+                 n_host_blocks, max_batch=1, max_blocks_per_seq=1, softmax_scale=0.0, device: Optional[str] = "cuda:0"):
+        self.cfg = PieConfig(n_layers, n_q_heads, n_kv_heads, head_dim, block_tokens, dtype, n_gpu_blocks,
+                             n_stage_blocks, n_host_blocks, max_batch, max_blocks_per_seq, softmax_scale)
+        self._h = C.c_void_p(0)
+        self.device = device
+        d_bytes, h_bytes = C.c_size_t(0), C.c_size_t(0)
+        _check(_lib.pie_pool_bytes_required(C.byref(self.cfg), C.byref(d_bytes), C.byref(h_bytes)), "bytes_required")
+        self.d_bytes, self.h_bytes = d_bytes.value, h_bytes.value
+        self.elem_bytes = 4 if dtype == 0 else 2
+        self.block_bytes = 2 * n_kv_heads * block_tokens * head_dim * self.elem_bytes
+        self.n_slots = n_gpu_blocks + 2 * n_stage_blocks
+        self.d_buf = self.h_buf = None
+        if device is not None:
+            import torch
+            self.d_buf = torch.empty(self.d_bytes + 256, dtype=torch.uint8, device=device)
+            off = (-self.d_buf.data_ptr()) % 256
+            self._d_base = self.d_buf.data_ptr() + off
+            self._d_off = off
+            if self.h_bytes:
+                self.h_buf = torch.empty(self.h_bytes, dtype=torch.uint8, pin_memory=True)
+            h_ptr = self.h_buf.data_ptr() if self.h_buf is not None else 0
+            _check(_lib.pie_pool_init(C.byref(self.cfg), C.c_void_p(self._d_base), C.c_size_t(self.d_bytes),
+                                      C.c_void_p(h_ptr), C.c_size_t(self.h_bytes), C.byref(self._h)), "pool_init")
+        else:
+            _check(_lib.pie_pool_init(C.byref(self.cfg), C.c_void_p(0), C.c_size_t(0), C.c_void_p(0), C.c_size_t(0),
+                                      C.byref(self._h)), "pool_init")
+
+    def close(self):
+        if self._h:
+            _lib.pie_pool_destroy(self._h)
+            self._h = C.c_void_p(0)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # ---- views of the pools (plumbing for tests and benchmarks) ------------------
+    def gpu_image(self):
+        """uint8 view [L][n_gpu + 2*n_stage][block_bytes] of the device pool."""
+        n = self.cfg.n_layers * self.n_slots * self.block_bytes
+        return self.d_buf[self._d_off:self._d_off + n].view(self.cfg.n_layers, self.n_slots, self.block_bytes)
+
+    def host_image(self):
+        """uint8 view [L][n_host][block_bytes] of the pinned host pool."""
+        return self.h_buf.view(self.cfg.n_layers, self.cfg.n_host_blocks, self.block_bytes)
+
+    # ---- allocator ------------------------------------------------------------------
+    def block_alloc(self, where: int, n: int) -> List[int]:
+        out = np.empty(max(n, 1), dtype=np.int32)
+        _check(_lib.pie_block_alloc(self._h, C.c_int32(where), C.c_int32(n), _ptr(out)), "block_alloc")
+        return out[:n].tolist()
+
+    def block_free(self, handles: Sequence[int]):
+        h = _i32(handles)
+        _check(_lib.pie_block_free(self._h, C.c_int32(len(h)), _ptr(h)), "block_free")
+
+    def block_where(self, handles: Sequence[int]) -> Tuple[List[int], List[int]]:
+        h = _i32(handles)
+        w, s = np.empty(max(len(h), 1), np.int32), np.empty(max(len(h), 1), np.int32)
+        _check(_lib.pie_block_where(self._h, C.c_int32(len(h)), _ptr(h), _ptr(w), _ptr(s)), "block_where")
+        return w[:len(h)].tolist(), s[:len(h)].tolist()
+
+    def block_staged(self, region: int, handles: Sequence[int]):
+        h = _i32(handles)
+        a, b = np.empty(max(len(h), 1), np.int32), np.empty(max(len(h), 1), np.int32)
+        _check(_lib.pie_block_staged(self._h, C.c_int32(region), C.c_int32(len(h)), _ptr(h), _ptr(a), _ptr(b)),
+               "block_staged")
+        return a[:len(h)].tolist(), b[:len(h)].tolist()
+
+    def n_free(self, where: int) -> int:
+        n = C.c_int32(0)
+        _check(_lib.pie_pool_free_count(self._h, C.c_int32(where), C.byref(n)), "free_count")
+        return n.value
+
+    def block_address(self, where: int, layer: int, slot: int) -> int:
+        p = C.c_void_p(0)
+        _check(_lib.pie_block_address(self._h, C.c_int32(where), C.c_int32(layer), C.c_int32(slot), C.byref(p)),
+               "block_address")
+        return p.value or 0
+
+    # ---- swaps ------------------------------------------------------------------------
+    def swap_in(self, layer: int, handles: Sequence[int], stream=None):
+        h = _i32(handles)
+        _check(_lib.pie_swap_in(self._h, C.c_int32(layer), C.c_int32(len(h)), _ptr(h), _stream_ptr(stream)), "swap_in")
+
+    def swap_out(self, layer: int, handles: Sequence[int], stream=None):
+        h = _i32(handles)
+        _check(_lib.pie_swap_out(self._h, C.c_int32(layer), C.c_int32(len(h)), _ptr(h), _stream_ptr(stream)),
+               "swap_out")
+
+    def migrate(self, handles: Sequence[int], to_where: int, stream=None):
+        h = _i32(handles)
+        _check(_lib.pie_migrate(self._h, C.c_int32(len(h)), _ptr(h), C.c_int32(to_where), _stream_ptr(stream)),
+               "migrate")
+
+    def set_host_fraction(self, f: float, order: Sequence[int], stream=None) -> int:
+        h = _i32(order)
+        k = C.c_int32(0)
+        _check(_lib.pie_set_host_fraction(self._h, C.c_float(f), C.c_int32(len(h)), _ptr(h), _stream_ptr(stream),
+                                          C.byref(k)), "set_host_fraction")
+        return k.value
+
+    def set_swap_path(self, path: int):
+        _check(_lib.pie_set_swap_path(self._h, C.c_int32(path)), "set_swap_path")
+
+    def set_attn_partition(self, tokens: int):
+        _check(_lib.pie_set_attn_partition(self._h, C.c_int32(tokens)), "set_attn_partition")
+
+    def set_swap_workgroups(self, n: int):
+        _check(_lib.pie_set_swap_workgroups(self._h, C.c_int32(n)), "set_swap_workgroups")
+
+    # ---- per-layer operations (tensors are torch device tensors) --------------------------
+    def kv_append(self, layer, k, v, block_table, ctx_lens, stream=None):
+        B, mb = block_table.shape
+        _check(_lib.pie_kv_append(self._h, C.c_int32(layer), _dptr(k), _dptr(v), _dptr(block_table), C.c_int32(mb),
+                                  _dptr(ctx_lens), C.c_int32(B), _stream_ptr(stream)), "kv_append")
+
+    def attn_decode(self, layer, q, block_table, ctx_lens, out, stream=None):
+        B, mb = block_table.shape
+        _check(_lib.pie_attn_decode(self._h, C.c_int32(layer), _dptr(q), _dptr(block_table), C.c_int32(mb),
+                                    _dptr(ctx_lens), C.c_int32(B), _dptr(out), _stream_ptr(stream)), "attn_decode")
+
+    def prefetch_list(self, block_table_host: np.ndarray, ctx_lens_host: np.ndarray):
+        t = np.ascontiguousarray(block_table_host, dtype=np.int32)
+        c = np.ascontiguousarray(ctx_lens_host, dtype=np.int32)
+        B, mb = t.shape
+        pf, dirty = np.empty(max(B * mb, 1), np.int32), np.empty(max(B, 1), np.int32)
+        npf, nd = C.c_int32(0), C.c_int32(0)
+        _check(_lib.pie_prefetch_list(self._h, _ptr(t), C.c_int32(mb), _ptr(c), C.c_int32(B), _ptr(pf), C.byref(npf),
+                                      _ptr(dirty), C.byref(nd)), "prefetch_list")
+        return pf[:npf.value].copy(), dirty[:nd.value].copy()
+
+    def step(self, q_all, k_new, v_new, block_table, ctx_lens, prefetch, dirty, out_all, compute_stream=None,
+             swap_in_stream=None, swap_out_stream=None):
+        B, mb = block_table.shape
+        pf, dt = _i32(prefetch), _i32(dirty)
+        _check(_lib.pie_step(self._h, _dptr(q_all), _dptr(k_new), _dptr(v_new), _dptr(block_table), C.c_int32(mb),
+                             _dptr(ctx_lens), C.c_int32(B), C.c_int32(len(pf)), _ptr(pf), C.c_int32(len(dt)), _ptr(dt),
+                             _dptr(out_all), _stream_ptr(compute_stream), _stream_ptr(swap_in_stream),
+                             _stream_ptr(swap_out_stream)), "step")
+
+    # ---- control ---------------------------------------------------------------------------
+    def set_timing(self, on: bool):
+        _check(_lib.pie_set_timing(self._h, C.c_int32(1 if on else 0)), "set_timing")
+
+    def sync(self):
+        _check(_lib.pie_pool_sync(self._h), "pool_sync")
+
+    def stats(self) -> PieStats:
+        s = PieStats()
+        _check(_lib.pie_get_stats(self._h, C.byref(s)), "get_stats")
+        return s
+
+    def layer_times(self):
+        L = self.cfg.n_layers
+        arrs = [np.zeros(L, dtype=np.float32) for _ in range(4)]
+        ps = [a.ctypes.data_as(C.POINTER(C.c_float)) for a in arrs]
+        _check(_lib.pie_get_layer_times(self._h, *ps), "get_layer_times")
+        return dict(zip(("attn", "swap_in", "swap_out", "stall"), arrs))
+
+    def check_errors(self) -> int:
+        f = C.c_uint32(0)
+        _check(_lib.pie_check_errors_sync(self._h, C.byref(f)), "check_errors_sync")
+        return f.value
+
+
+class Controller:
+    """Adaptive-expansion controller (pure host logic inside the library)."""
+
+    def __init__(self, units: int, k_max: int, rho=0.9, k_up=4, k_down=2, probe_period=64, plateau_eps=0.01,
+                 util_max=0.9, stall_eps=0.01):
+        self._h = C.c_void_p(0)
+        self.units = units
+        _check(_lib.pie_controller_create(C.c_int32(units), C.c_int32(k_max), C.byref(self._h)), "controller_create")
+        _check(_lib.pie_controller_config(self._h, C.c_double(rho), C.c_int32(k_up), C.c_int32(k_down),
+                                          C.c_int32(probe_period), C.c_double(plateau_eps), C.c_double(util_max),
+                                          C.c_double(stall_eps)), "controller_config")
+
+    def observe(self, t_attn, t_in, t_stall, link_util: float, throughput: float) -> int:
+        a = np.ascontiguousarray(t_attn, dtype=np.float64)
+        i = np.ascontiguousarray(t_in, dtype=np.float64)
+        s = np.ascontiguousarray(t_stall, dtype=np.float64)
+        dp = C.POINTER(C.c_double)
+        lvl = C.c_int32(0)
+        _check(_lib.pie_controller_observe(self._h, C.c_int32(len(a)), a.ctypes.data_as(dp), i.ctypes.data_as(dp),
+                                           s.ctypes.data_as(dp), C.c_double(link_util), C.c_double(throughput),
+                                           C.byref(lvl)), "controller_observe")
+        return lvl.value
+
+    def level(self) -> Tuple[int, int]:
+        k, c = C.c_int32(0), C.c_int32(0)
+        _check(_lib.pie_controller_level(self._h, C.byref(k), C.byref(c)), "controller_level")
+        return k.value, c.value
+
+    def update_from_pool(self, pool: Pool, throughput: float) -> float:
+        f = C.c_float(0)
+        _check(_lib.pie_controller_update(pool._h, self._h, C.c_double(throughput), C.byref(f)), "controller_update")
+        return f.value
+
+    def close(self):
+        if self._h:
+            _lib.pie_controller_destroy(self._h)
+            self._h = C.c_void_p(0)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

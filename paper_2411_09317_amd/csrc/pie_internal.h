@@ -1,0 +1,141 @@
+// Internal declarations shared by the library's translation units (not part of the ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <set>
+#include <vector>
+
+#include "pie.h"
+
+namespace pie {
+
+extern thread_local int g_last_hip_error;
+
+#define PIE_HIP(call)                                  \
+  do {                                                 \
+    hipError_t e_ = (call);                            \
+    if (e_ != hipSuccess) {                            \
+      ::pie::g_last_hip_error = (int)e_;               \
+      (void)hipGetLastError();                         \
+      return PIE_EHIP;                                 \
+    }                                                  \
+  } while (0)
+
+constexpr int kMapPatchPairs = 448;   // (handle, slot) pairs passed by value per patch launch
+constexpr int kSwapPairs = 448;       // (src slot, dst slot) pairs passed by value per gather launch
+constexpr uint32_t kAlign = 256;
+
+struct Home {
+  int32_t where = -1;  // PIE_WHERE_* or -1 = unallocated
+  int32_t slot = -1;
+};
+
+struct LayerEvents {
+  hipEvent_t attn_start, attn_end, in_start, in_end, out_start, out_end;
+  bool in_used = false, out_used = false;
+};
+
+struct MapPatch {  // by-value kernel argument
+  int32_t n;
+  int32_t handle[kMapPatchPairs];
+  int32_t slot[kMapPatchPairs];
+};
+
+struct SwapPairs {  // by-value kernel argument
+  int32_t n;
+  int32_t src[kSwapPairs];
+  int32_t dst[kSwapPairs];
+};
+
+}  // namespace pie
+
+struct pie_pool {
+  pie_config cfg;
+  bool device = false;          // false: bookkeeping only
+  int32_t n_handles = 0;
+  int32_t elem_bytes = 0;
+  size_t block_bytes = 0;       // one layer of one block
+  size_t d_layer_stride = 0;    // bytes between layers in the device pool
+  size_t h_layer_stride = 0;
+  float scale_log2e = 0.f;
+
+  char* d_kv = nullptr;         // device pool base
+  int32_t* d_map[2] = {nullptr, nullptr};   // per staging region: handle -> device slot, or -1
+  float* d_ws = nullptr;        // split-context partials
+  size_t ws_floats = 0;
+  uint32_t* d_err = nullptr;    // device error flags
+  char* h_kv = nullptr;         // host pool base (host address)
+  char* h_kv_dev = nullptr;     // same memory as seen from the device
+
+  // allocator and residency
+  std::set<int32_t> free_handles;
+  std::set<int32_t> free_slots[2];
+  std::vector<pie::Home> home;
+  int32_t n_in_use[2] = {0, 0};
+
+  // staging regions
+  std::vector<int32_t> stage_rank[2];       // handle -> rank in the region's list, or -1
+  std::vector<int32_t> stage_list[2];       // the region's current list
+  int32_t region_layer[2] = {-1, -1};
+
+  // host mirror of the device maps and what still has to be sent
+  std::vector<int32_t> map_mirror[2];
+  std::vector<int32_t> map_dirty[2];        // handles whose device entry is stale
+  std::vector<uint8_t> map_dirty_flag[2];
+
+  // ordering between streams
+  hipEvent_t ev_in[2] = {nullptr, nullptr};       // last swap-in into region r
+  hipEvent_t ev_read[2] = {nullptr, nullptr};     // last compute work that may touch region r
+  hipEvent_t ev_out[2] = {nullptr, nullptr};      // last write-back from region r
+  hipEvent_t ev_compute = nullptr;                // last compute work
+  hipEvent_t ev_migrate = nullptr;                // last migration
+  bool ev_in_rec[2] = {false, false}, ev_read_rec[2] = {false, false}, ev_out_rec[2] = {false, false};
+  bool ev_compute_rec = false, ev_migrate_rec = false, migrate_pending = false;
+  std::vector<hipStream_t> streams_seen;
+
+  // options
+  int32_t swap_path = PIE_SWAP_AUTO;
+  int32_t attn_partition = 512;   // tokens per workgroup
+  int32_t swap_wgs = 64;          // workgroups of the gather / scatter kernel
+  bool timing = false;
+  uint32_t last_err_flags = 0;    // device error flags seen by pie_check_errors_sync so far
+
+  // timing of the last step
+  std::vector<pie::LayerEvents> lev;
+  hipEvent_t ev_step_start = nullptr;
+  bool step_timed = false;
+  uint64_t bytes_in = 0, bytes_out = 0;
+};
+
+namespace pie {
+
+// host-side pieces used across files
+int note_stream(pie_pool* p, hipStream_t s);
+int flush_map(pie_pool* p, hipStream_t s);
+void map_set(pie_pool* p, int region, int32_t handle, int32_t slot);
+inline int32_t stage_slot(const pie_pool* p, int region, int32_t rank) {
+  return p->cfg.n_gpu_blocks + region * p->cfg.n_stage_blocks + rank;
+}
+inline char* d_block(const pie_pool* p, int32_t layer, int32_t slot) {
+  return p->d_kv + (size_t)layer * p->d_layer_stride + (size_t)slot * p->block_bytes;
+}
+inline char* h_block(const pie_pool* p, int32_t layer, int32_t slot) {
+  return p->h_kv + (size_t)layer * p->h_layer_stride + (size_t)slot * p->block_bytes;
+}
+
+// kernel launchers (pie_kernels.hip)
+int launch_map_fill(int32_t* d_map, int32_t n, int32_t value, hipStream_t s);
+int launch_map_patch(int32_t* d_map, const MapPatch& patch, hipStream_t s);
+int launch_zero_u32(uint32_t* d, int32_t n, hipStream_t s);
+int launch_swap_copy(char* dst_layer_base, const char* src_layer_base, size_t block_bytes, const SwapPairs& pairs,
+                     int n_wgs, hipStream_t s);
+int launch_kv_append(const pie_pool* p, int32_t layer, const void* d_k, const void* d_v, const int32_t* d_table,
+                     int32_t max_blocks, const int32_t* d_ctx, int32_t batch, bool stage_valid, hipStream_t s);
+int launch_attn_decode(const pie_pool* p, int32_t layer, const void* d_q, const int32_t* d_table, int32_t max_blocks,
+                       const int32_t* d_ctx, int32_t batch, void* d_out, bool stage_valid, hipStream_t s);
+size_t attn_workspace_floats(const pie_config& c);
+bool attn_config_supported(const pie_config& c);
+
+}  // namespace pie

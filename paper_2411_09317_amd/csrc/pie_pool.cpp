@@ -1,0 +1,856 @@
+// Pool: block allocator, residency (the mapping table), staging regions, swaps, and the per-layer
+// pipeline.  Host logic only; kernels live in pie_kernels.hip.
+//
+// Paper passages: Section 3.2 (mapping table, two-phase update, presence check), Section 3.3 (prefetch
+// behind the current layer), Section 4.1 (block manager, base pointer + offset addressing).
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <new>
+
+#include "pie_internal.h"
+
+namespace pie {
+
+thread_local int g_last_hip_error = 0;
+
+static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+static int elem_bytes_of(int32_t dtype) {
+  switch (dtype) {
+    case PIE_DTYPE_F32: return 4;
+    case PIE_DTYPE_F16: return 2;
+    case PIE_DTYPE_BF16: return 2;
+    default: return 0;
+  }
+}
+
+static bool config_ok(const pie_config* c) {
+  if (!c) return false;
+  if (c->n_layers <= 0 || c->n_q_heads <= 0 || c->n_kv_heads <= 0 || c->head_dim <= 0 || c->block_tokens <= 0)
+    return false;
+  if (c->n_q_heads % c->n_kv_heads) return false;
+  if (c->n_gpu_blocks < 0 || c->n_stage_blocks < 0 || c->n_host_blocks < 0) return false;
+  if (c->max_batch < 0 || c->max_blocks_per_seq < 0) return false;
+  if (!elem_bytes_of(c->dtype)) return false;
+  if ((int64_t)c->n_gpu_blocks + c->n_host_blocks > (int64_t)1 << 30) return false;
+  return true;
+}
+
+struct Layout {
+  size_t block_bytes, d_layer_stride, h_layer_stride;
+  size_t off_map0, off_map1, off_ws, off_err, d_total, h_total;
+  size_t ws_floats;
+};
+
+static Layout layout_of(const pie_config& c) {
+  Layout l;
+  const int e = elem_bytes_of(c.dtype);
+  l.block_bytes = (size_t)2 * c.n_kv_heads * c.block_tokens * c.head_dim * e;
+  l.d_layer_stride = ((size_t)c.n_gpu_blocks + 2 * (size_t)c.n_stage_blocks) * l.block_bytes;
+  l.h_layer_stride = (size_t)c.n_host_blocks * l.block_bytes;
+  const size_t n_handles = (size_t)c.n_gpu_blocks + c.n_host_blocks;
+  size_t off = align_up(l.d_layer_stride * c.n_layers, kAlign);
+  l.off_map0 = off; off = align_up(off + n_handles * 4, kAlign);
+  l.off_map1 = off; off = align_up(off + n_handles * 4, kAlign);
+  l.ws_floats = attn_workspace_floats(c);
+  l.off_ws = off; off = align_up(off + l.ws_floats * 4, kAlign);
+  l.off_err = off; off += kAlign;
+  l.d_total = off;
+  l.h_total = l.h_layer_stride * c.n_layers;
+  return l;
+}
+
+int note_stream(pie_pool* p, hipStream_t s) {
+  for (hipStream_t t : p->streams_seen)
+    if (t == s) return PIE_OK;
+  p->streams_seen.push_back(s);
+  return PIE_OK;
+}
+
+void map_set(pie_pool* p, int region, int32_t handle, int32_t slot) {
+  if (p->map_mirror[region][handle] == slot) return;
+  p->map_mirror[region][handle] = slot;
+  if (!p->map_dirty_flag[region][handle]) {
+    p->map_dirty_flag[region][handle] = 1;
+    p->map_dirty[region].push_back(handle);
+  }
+}
+
+// Sends stale map entries to the device on stream s, as by-value kernel arguments so that neither a
+// staging buffer nor a later change of the mirror can race with the copy.
+int flush_map(pie_pool* p, hipStream_t s) {
+  if (!p->device) return PIE_OK;
+  for (int r = 0; r < 2; ++r) {
+    std::vector<int32_t>& dirty = p->map_dirty[r];
+    if (dirty.empty()) continue;
+    MapPatch patch;
+    size_t i = 0;
+    while (i < dirty.size()) {
+      patch.n = 0;
+      while (i < dirty.size() && patch.n < kMapPatchPairs) {
+        const int32_t h = dirty[i++];
+        patch.handle[patch.n] = h;
+        patch.slot[patch.n] = p->map_mirror[r][h];
+        p->map_dirty_flag[r][h] = 0;
+        ++patch.n;
+      }
+      int rc = launch_map_patch(p->d_map[r], patch, s);
+      if (rc) return rc;
+    }
+    dirty.clear();
+  }
+  return PIE_OK;
+}
+
+static int check_handles(const pie_pool* p, int32_t n, const int32_t* handles, int need_where,
+                         std::vector<uint8_t>& seen) {
+  if (n < 0 || (n > 0 && !handles)) return PIE_EINVAL;
+  seen.assign(p->n_handles, 0);
+  for (int32_t i = 0; i < n; ++i) {
+    const int32_t h = handles[i];
+    if (h < 0 || h >= p->n_handles) return PIE_EINVAL;
+  }
+  for (int32_t i = 0; i < n; ++i) {
+    const int32_t h = handles[i];
+    if (p->home[h].where < 0 || seen[h]) return PIE_ESTATE;
+    if (need_where >= 0 && p->home[h].where != need_where) return PIE_ESTATE;
+    seen[h] = 1;
+  }
+  return PIE_OK;
+}
+
+static void drop_staged(pie_pool* p, int32_t h) {
+  for (int r = 0; r < 2; ++r) {
+    if (p->stage_rank[r][h] >= 0) {
+      p->stage_list[r][p->stage_rank[r][h]] = -1;
+      p->stage_rank[r][h] = -1;
+    }
+  }
+}
+
+// Moves n (src slot -> dst slot) block copies of one layer between the pools or within the device pool.
+// kind: 0 host->device, 1 device->host.  Chooses the copy engine for long contiguous runs and the
+// gather / scatter kernel otherwise.
+static int copy_blocks(pie_pool* p, int kind, int32_t layer, const std::vector<int32_t>& src,
+                       const std::vector<int32_t>& dst, hipStream_t s) {
+  const size_t n = src.size();
+  if (!n) return PIE_OK;
+  // contiguous runs
+  struct Run { int32_t src, dst, len; };
+  std::vector<Run> runs;
+  for (size_t i = 0; i < n; ++i) {
+    if (!runs.empty() && runs.back().src + runs.back().len == src[i] && runs.back().dst + runs.back().len == dst[i])
+      ++runs.back().len;
+    else
+      runs.push_back({src[i], dst[i], 1});
+  }
+  int path = p->swap_path;
+  if (path == PIE_SWAP_AUTO) {
+    // the copy engine pays a fixed cost per call; use it when runs are long on average
+    const size_t avg_bytes = n * p->block_bytes / runs.size();
+    path = (runs.size() <= 64 && avg_bytes >= ((size_t)1 << 20)) ? PIE_SWAP_DMA : PIE_SWAP_KERNEL;
+  }
+  if (path == PIE_SWAP_DMA) {
+    for (const Run& r : runs) {
+      const size_t bytes = (size_t)r.len * p->block_bytes;
+      if (kind == 0)
+        PIE_HIP(hipMemcpyAsync(d_block(p, layer, r.dst), h_block(p, layer, r.src), bytes, hipMemcpyHostToDevice, s));
+      else
+        PIE_HIP(hipMemcpyAsync(h_block(p, layer, r.dst), d_block(p, layer, r.src), bytes, hipMemcpyDeviceToHost, s));
+    }
+    return PIE_OK;
+  }
+  char* dst_base = kind == 0 ? p->d_kv + (size_t)layer * p->d_layer_stride
+                             : p->h_kv_dev + (size_t)layer * p->h_layer_stride;
+  const char* src_base = kind == 0 ? p->h_kv_dev + (size_t)layer * p->h_layer_stride
+                                   : p->d_kv + (size_t)layer * p->d_layer_stride;
+  SwapPairs pairs;
+  size_t i = 0;
+  while (i < n) {
+    pairs.n = 0;
+    while (i < n && pairs.n < kSwapPairs) {
+      pairs.src[pairs.n] = src[i];
+      pairs.dst[pairs.n] = dst[i];
+      ++pairs.n;
+      ++i;
+    }
+    int rc = launch_swap_copy(dst_base, src_base, p->block_bytes, pairs, p->swap_wgs, s);
+    if (rc) return rc;
+  }
+  return PIE_OK;
+}
+
+static int wait_if(hipStream_t s, hipEvent_t ev, bool recorded) {
+  if (recorded) PIE_HIP(hipStreamWaitEvent(s, ev, 0));
+  return PIE_OK;
+}
+
+// ---- internals of the public swap / compute calls (also used by pie_step) ------------------------------
+
+static int swap_in_impl(pie_pool* p, int32_t layer, int32_t n, const int32_t* handles, hipStream_t s,
+                        bool validated, hipEvent_t t0, hipEvent_t t1) {
+  const int r = layer & 1;
+  if (!validated) {
+    if (layer < 0 || layer >= p->cfg.n_layers) return PIE_EINVAL;
+    if (n < 0 || (n > 0 && !handles)) return PIE_EINVAL;
+    if (n > p->cfg.n_stage_blocks) return PIE_ENOMEM;
+    std::vector<uint8_t> seen;
+    int rc = check_handles(p, n, handles, PIE_WHERE_HOST, seen);
+    if (rc) return rc;
+  }
+  if (!p->device) return PIE_ESTATE;
+  note_stream(p, s);
+  // phase one: publish where the copies will be
+  bool same = (int32_t)p->stage_list[r].size() == n;
+  for (int32_t i = 0; same && i < n; ++i) same = p->stage_list[r][i] == handles[i];
+  if (!same) {
+    for (int32_t h : p->stage_list[r])
+      if (h >= 0) {
+        p->stage_rank[r][h] = -1;
+        map_set(p, r, h, -1);
+      }
+    p->stage_list[r].assign(handles, handles + n);
+    for (int32_t i = 0; i < n; ++i) {
+      p->stage_rank[r][handles[i]] = i;
+      map_set(p, r, handles[i], stage_slot(p, r, i));
+    }
+  }
+  p->region_layer[r] = layer;
+  // the region may still be read by compute or written back
+  int rc;
+  if ((rc = wait_if(s, p->ev_read[r], p->ev_read_rec[r]))) return rc;
+  if ((rc = wait_if(s, p->ev_out[r], p->ev_out_rec[r]))) return rc;
+  if ((rc = wait_if(s, p->ev_migrate, p->ev_migrate_rec))) return rc;
+  if (t0) PIE_HIP(hipEventRecord(t0, s));
+  std::vector<int32_t> src(n), dst(n);
+  for (int32_t i = 0; i < n; ++i) {
+    src[i] = p->home[handles[i]].slot;
+    dst[i] = stage_slot(p, r, i);
+  }
+  if ((rc = copy_blocks(p, 0, layer, src, dst, s))) return rc;
+  if (t1) PIE_HIP(hipEventRecord(t1, s));
+  // phase two happens when this event completes
+  PIE_HIP(hipEventRecord(p->ev_in[r], s));
+  p->ev_in_rec[r] = true;
+  p->bytes_in += (uint64_t)n * p->block_bytes;
+  return PIE_OK;
+}
+
+static int swap_out_impl(pie_pool* p, int32_t layer, int32_t n, const int32_t* handles, hipStream_t s,
+                         hipEvent_t t0, hipEvent_t t1) {
+  if (layer < 0 || layer >= p->cfg.n_layers) return PIE_EINVAL;
+  std::vector<uint8_t> seen;
+  int rc = check_handles(p, n, handles, PIE_WHERE_HOST, seen);
+  if (rc) return rc;
+  const int r = layer & 1;
+  if (n > 0 && p->region_layer[r] != layer) return PIE_ESTATE;
+  for (int32_t i = 0; i < n; ++i)
+    if (p->stage_rank[r][handles[i]] < 0) return PIE_ESTATE;
+  if (!p->device) return PIE_ESTATE;
+  note_stream(p, s);
+  if ((rc = wait_if(s, p->ev_in[r], p->ev_in_rec[r]))) return rc;
+  if ((rc = wait_if(s, p->ev_read[r], p->ev_read_rec[r]))) return rc;
+  if (t0) PIE_HIP(hipEventRecord(t0, s));
+  std::vector<int32_t> src(n), dst(n);
+  for (int32_t i = 0; i < n; ++i) {
+    src[i] = stage_slot(p, r, p->stage_rank[r][handles[i]]);
+    dst[i] = p->home[handles[i]].slot;
+  }
+  if ((rc = copy_blocks(p, 1, layer, src, dst, s))) return rc;
+  if (t1) PIE_HIP(hipEventRecord(t1, s));
+  PIE_HIP(hipEventRecord(p->ev_out[r], s));
+  p->ev_out_rec[r] = true;
+  p->bytes_out += (uint64_t)n * p->block_bytes;
+  return PIE_OK;
+}
+
+// Everything a compute-stream kernel of `layer` must wait for: the presence check.
+static int compute_prologue(pie_pool* p, int32_t layer, hipStream_t s, bool* stage_valid) {
+  const int r = layer & 1;
+  note_stream(p, s);
+  int rc;
+  if ((rc = wait_if(s, p->ev_migrate, p->ev_migrate_rec))) return rc;
+  *stage_valid = p->region_layer[r] == layer;
+  if (*stage_valid && (rc = wait_if(s, p->ev_in[r], p->ev_in_rec[r]))) return rc;
+  return flush_map(p, s);
+}
+
+static int compute_epilogue(pie_pool* p, int32_t layer, hipStream_t s) {
+  const int r = layer & 1;
+  PIE_HIP(hipEventRecord(p->ev_read[r], s));
+  p->ev_read_rec[r] = true;
+  PIE_HIP(hipEventRecord(p->ev_compute, s));
+  p->ev_compute_rec = true;
+  return PIE_OK;
+}
+
+static int check_batch_args(const pie_pool* p, int32_t layer, const void* a, const int32_t* table,
+                            int32_t max_blocks, const int32_t* ctx, int32_t batch) {
+  if (layer < 0 || layer >= p->cfg.n_layers) return PIE_EINVAL;
+  if (batch < 0 || max_blocks < 0) return PIE_EINVAL;
+  if (batch > 0 && (!a || !table || !ctx)) return PIE_EINVAL;
+  if (batch > p->cfg.max_batch || max_blocks > p->cfg.max_blocks_per_seq) return PIE_EINVAL;
+  return PIE_OK;
+}
+
+}  // namespace pie
+
+using namespace pie;
+
+extern "C" {
+
+int pie_pool_bytes_required(const pie_config* cfg, size_t* d_bytes, size_t* h_bytes) {
+  if (!config_ok(cfg)) return PIE_EINVAL;
+  const Layout l = layout_of(*cfg);
+  if (d_bytes) *d_bytes = l.d_total;
+  if (h_bytes) *h_bytes = l.h_total;
+  return PIE_OK;
+}
+
+int pie_pool_init(const pie_config* cfg, void* d_base, size_t d_bytes, void* h_pinned_base, size_t h_bytes,
+                  pie_pool** out) {
+  if (!out || !config_ok(cfg)) return PIE_EINVAL;
+  *out = nullptr;
+  const Layout l = layout_of(*cfg);
+  const bool device = d_base != nullptr;
+  if (device) {
+    if (!attn_config_supported(*cfg)) return PIE_EINVAL;
+    if ((uintptr_t)d_base % kAlign) return PIE_EINVAL;
+    if (d_bytes < l.d_total) return PIE_ENOMEM;
+    if (cfg->n_host_blocks > 0) {
+      if (!h_pinned_base) return PIE_EINVAL;
+      if ((uintptr_t)h_pinned_base % 16) return PIE_EINVAL;
+      if (h_bytes < l.h_total) return PIE_ENOMEM;
+    }
+  }
+  pie_pool* p = new (std::nothrow) pie_pool();
+  if (!p) return PIE_ENOMEM;
+  p->cfg = *cfg;
+  p->device = device;
+  p->n_handles = cfg->n_gpu_blocks + cfg->n_host_blocks;
+  p->elem_bytes = elem_bytes_of(cfg->dtype);
+  p->block_bytes = l.block_bytes;
+  p->d_layer_stride = l.d_layer_stride;
+  p->h_layer_stride = l.h_layer_stride;
+  const float scale = cfg->softmax_scale != 0.f ? cfg->softmax_scale : 1.0f / std::sqrt((float)cfg->head_dim);
+  p->scale_log2e = scale * 1.4426950408889634f;
+  for (int32_t h = 0; h < p->n_handles; ++h) p->free_handles.insert(h);
+  for (int32_t s = 0; s < cfg->n_gpu_blocks; ++s) p->free_slots[0].insert(s);
+  for (int32_t s = 0; s < cfg->n_host_blocks; ++s) p->free_slots[1].insert(s);
+  p->home.assign(p->n_handles, Home());
+  for (int r = 0; r < 2; ++r) {
+    p->stage_rank[r].assign(p->n_handles, -1);
+    p->map_mirror[r].assign(p->n_handles, -1);
+    p->map_dirty_flag[r].assign(p->n_handles, 0);
+  }
+  p->h_kv = (char*)h_pinned_base;
+  if (device) {
+    char* base = (char*)d_base;
+    p->d_kv = base;
+    p->d_map[0] = (int32_t*)(base + l.off_map0);
+    p->d_map[1] = (int32_t*)(base + l.off_map1);
+    p->d_ws = (float*)(base + l.off_ws);
+    p->ws_floats = l.ws_floats;
+    p->d_err = (uint32_t*)(base + l.off_err);
+    int rc = PIE_OK;
+    auto fail = [&](int code) { pie_pool_destroy(p); return code; };
+    if (cfg->n_host_blocks > 0) {
+      void* dev_ptr = nullptr;
+      hipError_t e = hipHostGetDevicePointer(&dev_ptr, h_pinned_base, 0);
+      if (e != hipSuccess) { g_last_hip_error = (int)e; (void)hipGetLastError(); return fail(PIE_EHIP); }
+      p->h_kv_dev = (char*)dev_ptr;
+    }
+    hipEvent_t* evs[] = {&p->ev_in[0], &p->ev_in[1], &p->ev_read[0], &p->ev_read[1], &p->ev_out[0], &p->ev_out[1],
+                         &p->ev_compute, &p->ev_migrate};
+    for (hipEvent_t* e : evs) {
+      hipError_t err = hipEventCreateWithFlags(e, hipEventDisableTiming);
+      if (err != hipSuccess) { g_last_hip_error = (int)err; (void)hipGetLastError(); return fail(PIE_EHIP); }
+    }
+    hipError_t err = hipEventCreate(&p->ev_step_start);
+    if (err != hipSuccess) { g_last_hip_error = (int)err; return fail(PIE_EHIP); }
+    p->lev.resize(cfg->n_layers);
+    for (auto& le : p->lev) {
+      hipEvent_t* tev[] = {&le.attn_start, &le.attn_end, &le.in_start, &le.in_end, &le.out_start, &le.out_end};
+      for (hipEvent_t* e : tev) {
+        *e = nullptr;
+        err = hipEventCreate(e);
+        if (err != hipSuccess) { g_last_hip_error = (int)err; return fail(PIE_EHIP); }
+      }
+    }
+    // maps start empty, error flags clear (default stream; synchronised before returning)
+    if ((rc = launch_map_fill(p->d_map[0], p->n_handles, -1, nullptr))) return fail(rc);
+    if ((rc = launch_map_fill(p->d_map[1], p->n_handles, -1, nullptr))) return fail(rc);
+    if ((rc = launch_zero_u32(p->d_err, kAlign / 4, nullptr))) return fail(rc);
+    err = hipStreamSynchronize(nullptr);
+    if (err != hipSuccess) { g_last_hip_error = (int)err; return fail(PIE_EHIP); }
+  }
+  *out = p;
+  return PIE_OK;
+}
+
+int pie_pool_sync(pie_pool* p) {
+  if (!p) return PIE_EINVAL;
+  if (!p->device) return PIE_OK;
+  for (hipStream_t s : p->streams_seen) PIE_HIP(hipStreamSynchronize(s));
+  return PIE_OK;
+}
+
+int pie_pool_destroy(pie_pool* p) {
+  if (!p) return PIE_EINVAL;
+  if (p->device) {
+    for (hipStream_t s : p->streams_seen) (void)hipStreamSynchronize(s);
+    hipEvent_t evs[] = {p->ev_in[0], p->ev_in[1], p->ev_read[0], p->ev_read[1], p->ev_out[0], p->ev_out[1],
+                        p->ev_compute, p->ev_migrate, p->ev_step_start};
+    for (hipEvent_t e : evs)
+      if (e) (void)hipEventDestroy(e);
+    for (auto& le : p->lev) {
+      hipEvent_t tev[] = {le.attn_start, le.attn_end, le.in_start, le.in_end, le.out_start, le.out_end};
+      for (hipEvent_t e : tev)
+        if (e) (void)hipEventDestroy(e);
+    }
+  }
+  delete p;
+  return PIE_OK;
+}
+
+int pie_block_alloc(pie_pool* p, int32_t where, int32_t n, int32_t* out_handles) {
+  if (!p || (where != PIE_WHERE_GPU && where != PIE_WHERE_HOST) || n < 0 || (n > 0 && !out_handles))
+    return PIE_EINVAL;
+  if ((size_t)n > p->free_slots[where].size() || (size_t)n > p->free_handles.size()) return PIE_ENOMEM;
+  for (int32_t i = 0; i < n; ++i) {
+    const int32_t h = *p->free_handles.begin();
+    const int32_t s = *p->free_slots[where].begin();
+    p->free_handles.erase(p->free_handles.begin());
+    p->free_slots[where].erase(p->free_slots[where].begin());
+    p->home[h] = {where, s};
+    out_handles[i] = h;
+    const int32_t dev_slot = where == PIE_WHERE_GPU ? s : -1;
+    map_set(p, 0, h, dev_slot);
+    map_set(p, 1, h, dev_slot);
+  }
+  p->n_in_use[where] += n;
+  return PIE_OK;
+}
+
+int pie_block_free(pie_pool* p, int32_t n, const int32_t* handles) {
+  if (!p) return PIE_EINVAL;
+  std::vector<uint8_t> seen;
+  int rc = check_handles(p, n, handles, -1, seen);
+  if (rc) return rc;
+  for (int32_t i = 0; i < n; ++i) {
+    const int32_t h = handles[i];
+    const Home hm = p->home[h];
+    p->free_slots[hm.where].insert(hm.slot);
+    p->free_handles.insert(h);
+    --p->n_in_use[hm.where];
+    p->home[h] = Home();
+    drop_staged(p, h);
+    map_set(p, 0, h, -1);
+    map_set(p, 1, h, -1);
+  }
+  return PIE_OK;
+}
+
+int pie_block_where(pie_pool* p, int32_t n, const int32_t* handles, int32_t* out_where, int32_t* out_slot) {
+  if (!p || n < 0 || (n > 0 && (!handles || !out_where || !out_slot))) return PIE_EINVAL;
+  for (int32_t i = 0; i < n; ++i)
+    if (handles[i] < 0 || handles[i] >= p->n_handles) return PIE_EINVAL;
+  for (int32_t i = 0; i < n; ++i) {
+    out_where[i] = p->home[handles[i]].where;
+    out_slot[i] = p->home[handles[i]].slot;
+  }
+  return PIE_OK;
+}
+
+int pie_block_staged(pie_pool* p, int32_t region, int32_t n, const int32_t* handles, int32_t* out_stage_slot,
+                     int32_t* out_state) {
+  if (!p || (region != 0 && region != 1) || n < 0 || (n > 0 && (!handles || !out_stage_slot || !out_state)))
+    return PIE_EINVAL;
+  for (int32_t i = 0; i < n; ++i)
+    if (handles[i] < 0 || handles[i] >= p->n_handles) return PIE_EINVAL;
+  bool done = true;
+  if (p->device && p->ev_in_rec[region]) {
+    hipError_t e = hipEventQuery(p->ev_in[region]);
+    if (e == hipErrorNotReady) {
+      done = false;
+      (void)hipGetLastError();
+    } else if (e != hipSuccess) {
+      g_last_hip_error = (int)e;
+      return PIE_EHIP;
+    }
+  }
+  for (int32_t i = 0; i < n; ++i) {
+    const int32_t rank = p->stage_rank[region][handles[i]];
+    out_stage_slot[i] = rank < 0 ? -1 : stage_slot(p, region, rank);
+    out_state[i] = rank < 0 ? 0 : (done ? 2 : 1);
+  }
+  return PIE_OK;
+}
+
+int pie_pool_free_count(pie_pool* p, int32_t where, int32_t* out_n) {
+  if (!p || !out_n || (where != 0 && where != 1)) return PIE_EINVAL;
+  *out_n = (int32_t)p->free_slots[where].size();
+  return PIE_OK;
+}
+
+int pie_block_address(pie_pool* p, int32_t where, int32_t layer, int32_t slot, void** out_ptr) {
+  if (!p || !out_ptr || layer < 0 || layer >= p->cfg.n_layers || slot < 0) return PIE_EINVAL;
+  if (where == PIE_WHERE_GPU) {
+    if (slot >= p->cfg.n_gpu_blocks + 2 * p->cfg.n_stage_blocks) return PIE_EINVAL;
+    if (!p->device) return PIE_ESTATE;
+    *out_ptr = d_block(p, layer, slot);
+  } else if (where == PIE_WHERE_HOST) {
+    if (slot >= p->cfg.n_host_blocks) return PIE_EINVAL;
+    if (!p->h_kv) return PIE_ESTATE;
+    *out_ptr = h_block(p, layer, slot);
+  } else {
+    return PIE_EINVAL;
+  }
+  return PIE_OK;
+}
+
+int pie_swap_in(pie_pool* p, int32_t layer, int32_t n, const int32_t* handles, void* stream) {
+  if (!p) return PIE_EINVAL;
+  return swap_in_impl(p, layer, n, handles, (hipStream_t)stream, false, nullptr, nullptr);
+}
+
+int pie_swap_out(pie_pool* p, int32_t layer, int32_t n, const int32_t* handles, void* stream) {
+  if (!p) return PIE_EINVAL;
+  return swap_out_impl(p, layer, n, handles, (hipStream_t)stream, nullptr, nullptr);
+}
+
+int pie_migrate(pie_pool* p, int32_t n, const int32_t* handles, int32_t to_where, void* stream) {
+  if (!p || (to_where != PIE_WHERE_GPU && to_where != PIE_WHERE_HOST)) return PIE_EINVAL;
+  std::vector<uint8_t> seen;
+  int rc = check_handles(p, n, handles, -1, seen);
+  if (rc) return rc;
+  std::vector<int32_t> movers;
+  for (int32_t i = 0; i < n; ++i)
+    if (p->home[handles[i]].where != to_where) movers.push_back(handles[i]);
+  if (movers.size() > p->free_slots[to_where].size()) return PIE_ENOMEM;
+  if (movers.empty()) return PIE_OK;
+  hipStream_t s = (hipStream_t)stream;
+  if (p->device) {
+    note_stream(p, s);
+    if ((rc = wait_if(s, p->ev_compute, p->ev_compute_rec))) return rc;
+    for (int r = 0; r < 2; ++r) {
+      if ((rc = wait_if(s, p->ev_in[r], p->ev_in_rec[r]))) return rc;
+      if ((rc = wait_if(s, p->ev_out[r], p->ev_out_rec[r]))) return rc;
+    }
+  }
+  std::vector<int32_t> src(movers.size()), dst(movers.size());
+  const int from = 1 - to_where;
+  for (size_t i = 0; i < movers.size(); ++i) {
+    const int32_t h = movers[i];
+    const int32_t t = *p->free_slots[to_where].begin();
+    p->free_slots[to_where].erase(p->free_slots[to_where].begin());
+    src[i] = p->home[h].slot;
+    dst[i] = t;
+  }
+  for (size_t i = 0; i < movers.size(); ++i) {
+    const int32_t h = movers[i];
+    p->free_slots[from].insert(src[i]);
+    p->home[h] = {to_where, dst[i]};
+    drop_staged(p, h);
+    const int32_t dev_slot = to_where == PIE_WHERE_GPU ? dst[i] : -1;
+    map_set(p, 0, h, dev_slot);
+    map_set(p, 1, h, dev_slot);
+  }
+  p->n_in_use[from] -= (int32_t)movers.size();
+  p->n_in_use[to_where] += (int32_t)movers.size();
+  if (p->device) {
+    for (int32_t layer = 0; layer < p->cfg.n_layers; ++layer)
+      if ((rc = copy_blocks(p, to_where == PIE_WHERE_GPU ? 0 : 1, layer, src, dst, s))) return rc;
+    PIE_HIP(hipEventRecord(p->ev_migrate, s));
+    p->ev_migrate_rec = true;
+  }
+  return PIE_OK;
+}
+
+int pie_set_host_fraction(pie_pool* p, float f, int32_t n, const int32_t* order, void* stream,
+                          int32_t* out_n_host) {
+  if (!p || !(f >= 0.f && f <= 1.f)) return PIE_EINVAL;
+  std::vector<uint8_t> seen;
+  int rc = check_handles(p, n, order, -1, seen);
+  if (rc) return rc;
+  const int32_t k = (int32_t)std::floor((double)f * n + 0.5);
+  // capacity check for both moves before anything changes
+  int32_t to_gpu = 0, to_host = 0;
+  for (int32_t i = 0; i < n; ++i) {
+    const int w = p->home[order[i]].where;
+    if (i < k && w == PIE_WHERE_GPU) ++to_host;
+    if (i >= k && w == PIE_WHERE_HOST) ++to_gpu;
+  }
+  if ((size_t)to_gpu > p->free_slots[0].size()) return PIE_ENOMEM;
+  if ((size_t)to_host > p->free_slots[1].size() + (size_t)to_gpu) return PIE_ENOMEM;
+  if ((rc = pie_migrate(p, n - k, order + k, PIE_WHERE_GPU, stream))) return rc;
+  if ((rc = pie_migrate(p, k, order, PIE_WHERE_HOST, stream))) return rc;
+  if (out_n_host) *out_n_host = k;
+  return PIE_OK;
+}
+
+int pie_set_swap_path(pie_pool* p, int32_t path) {
+  if (!p || path < PIE_SWAP_AUTO || path > PIE_SWAP_KERNEL) return PIE_EINVAL;
+  p->swap_path = path;
+  return PIE_OK;
+}
+
+int pie_set_attn_partition(pie_pool* p, int32_t tokens) {
+  if (!p || tokens <= 0) return PIE_EINVAL;
+  p->attn_partition = tokens;
+  return PIE_OK;
+}
+
+int pie_set_swap_workgroups(pie_pool* p, int32_t n) {
+  if (!p || n < 1 || n > 1024) return PIE_EINVAL;
+  p->swap_wgs = n;
+  return PIE_OK;
+}
+
+int pie_kv_append(pie_pool* p, int32_t layer, const void* d_k, const void* d_v, const int32_t* d_block_table,
+                  int32_t max_blocks, const int32_t* d_ctx_lens, int32_t batch, void* stream) {
+  if (!p) return PIE_EINVAL;
+  int rc = check_batch_args(p, layer, d_k, d_block_table, max_blocks, d_ctx_lens, batch);
+  if (rc) return rc;
+  if (batch > 0 && !d_v) return PIE_EINVAL;
+  if (!p->device) return PIE_ESTATE;
+  if (batch == 0) return PIE_OK;
+  hipStream_t s = (hipStream_t)stream;
+  bool stage_valid = false;
+  if ((rc = compute_prologue(p, layer, s, &stage_valid))) return rc;
+  if ((rc = launch_kv_append(p, layer, d_k, d_v, d_block_table, max_blocks, d_ctx_lens, batch, stage_valid, s)))
+    return rc;
+  return compute_epilogue(p, layer, s);
+}
+
+int pie_attn_decode(pie_pool* p, int32_t layer, const void* d_q, const int32_t* d_block_table, int32_t max_blocks,
+                    const int32_t* d_ctx_lens, int32_t batch, void* d_out, void* stream) {
+  if (!p) return PIE_EINVAL;
+  int rc = check_batch_args(p, layer, d_q, d_block_table, max_blocks, d_ctx_lens, batch);
+  if (rc) return rc;
+  if (batch > 0 && !d_out) return PIE_EINVAL;
+  if (!p->device) return PIE_ESTATE;
+  if (batch == 0) return PIE_OK;
+  hipStream_t s = (hipStream_t)stream;
+  bool stage_valid = false;
+  if ((rc = compute_prologue(p, layer, s, &stage_valid))) return rc;
+  if ((rc = launch_attn_decode(p, layer, d_q, d_block_table, max_blocks, d_ctx_lens, batch, d_out, stage_valid, s)))
+    return rc;
+  return compute_epilogue(p, layer, s);
+}
+
+int pie_prefetch_list(pie_pool* p, const int32_t* h_block_table, int32_t max_blocks, const int32_t* h_ctx_lens,
+                      int32_t batch, int32_t* out_prefetch, int32_t* out_n_prefetch, int32_t* out_dirty,
+                      int32_t* out_n_dirty) {
+  if (!p || batch < 0 || max_blocks < 0 || !out_n_prefetch || !out_n_dirty) return PIE_EINVAL;
+  if (batch > 0 && (!h_block_table || !h_ctx_lens || !out_prefetch || !out_dirty)) return PIE_EINVAL;
+  const int32_t T = p->cfg.block_tokens;
+  std::vector<uint8_t> seen(p->n_handles, 0), seen_dirty(p->n_handles, 0);
+  int32_t np = 0, nd = 0;
+  for (int32_t b = 0; b < batch; ++b) {
+    const int32_t ctx = h_ctx_lens[b];
+    if (ctx <= 0) continue;
+    const int32_t nb = (ctx + T - 1) / T;
+    if (nb > max_blocks) return PIE_EINVAL;
+    for (int32_t j = 0; j < nb; ++j) {
+      const int32_t h = h_block_table[(size_t)b * max_blocks + j];
+      if (h < 0 || h >= p->n_handles) return PIE_EINVAL;
+      if (p->home[h].where != PIE_WHERE_HOST) continue;
+      if (!seen[h]) {
+        seen[h] = 1;
+        out_prefetch[np++] = h;
+      }
+      if (j == (ctx - 1) / T && !seen_dirty[h]) {
+        seen_dirty[h] = 1;
+        out_dirty[nd++] = h;
+      }
+    }
+  }
+  *out_n_prefetch = np;
+  *out_n_dirty = nd;
+  return PIE_OK;
+}
+
+int pie_step(pie_pool* p, const void* d_q_all, const void* d_k_new, const void* d_v_new,
+             const int32_t* d_block_table, int32_t max_blocks, const int32_t* d_ctx_lens, int32_t batch,
+             int32_t n_prefetch, const int32_t* h_prefetch, int32_t n_dirty, const int32_t* h_dirty,
+             void* d_out_all, void* compute_stream, void* swap_in_stream, void* swap_out_stream) {
+  if (!p) return PIE_EINVAL;
+  int rc = check_batch_args(p, 0, d_q_all, d_block_table, max_blocks, d_ctx_lens, batch);
+  if (rc) return rc;
+  if (batch > 0 && !d_out_all) return PIE_EINVAL;
+  if ((d_k_new == nullptr) != (d_v_new == nullptr)) return PIE_EINVAL;
+  if (n_prefetch < 0 || n_dirty < 0) return PIE_EINVAL;
+  if (n_prefetch > p->cfg.n_stage_blocks) return PIE_ENOMEM;
+  std::vector<uint8_t> seen;
+  if ((rc = check_handles(p, n_prefetch, h_prefetch, PIE_WHERE_HOST, seen))) return rc;
+  {
+    std::vector<uint8_t> seen_d;
+    if ((rc = check_handles(p, n_dirty, h_dirty, PIE_WHERE_HOST, seen_d))) return rc;
+    for (int32_t i = 0; i < n_dirty; ++i)
+      if (!seen[h_dirty[i]]) return PIE_ESTATE;  // a dirty block must be among the prefetched ones
+  }
+  if (!p->device) return PIE_ESTATE;
+  if (batch == 0) return PIE_OK;
+  hipStream_t cs = (hipStream_t)compute_stream, is = (hipStream_t)swap_in_stream, os = (hipStream_t)swap_out_stream;
+  const int32_t L = p->cfg.n_layers;
+  const size_t q_stride = (size_t)batch * p->cfg.n_q_heads * p->cfg.head_dim * p->elem_bytes;
+  const size_t kv_stride = (size_t)batch * p->cfg.n_kv_heads * p->cfg.head_dim * p->elem_bytes;
+  const bool timed = p->timing;
+  p->bytes_in = p->bytes_out = 0;
+  p->step_timed = false;
+  note_stream(p, cs);
+  if (timed) {
+    PIE_HIP(hipEventRecord(p->ev_step_start, cs));
+    for (auto& le : p->lev) le.in_used = le.out_used = false;
+  }
+  // layer 0's blocks have no earlier layer to hide behind
+  if (n_prefetch > 0) {
+    if ((rc = swap_in_impl(p, 0, n_prefetch, h_prefetch, is, true, timed ? p->lev[0].in_start : nullptr,
+                           timed ? p->lev[0].in_end : nullptr)))
+      return rc;
+    p->lev[0].in_used = timed;
+  }
+  for (int32_t l = 0; l < L; ++l) {
+    if (l + 1 < L && n_prefetch > 0) {
+      // enqueue the next layer's prefetch before this layer's compute so the two overlap
+      if ((rc = swap_in_impl(p, l + 1, n_prefetch, h_prefetch, is, true, timed ? p->lev[l + 1].in_start : nullptr,
+                             timed ? p->lev[l + 1].in_end : nullptr)))
+        return rc;
+      p->lev[l + 1].in_used = timed;
+    }
+    bool stage_valid = false;
+    if ((rc = compute_prologue(p, l, cs, &stage_valid))) return rc;
+    if (timed) PIE_HIP(hipEventRecord(p->lev[l].attn_start, cs));
+    if (d_k_new) {
+      if ((rc = launch_kv_append(p, l, (const char*)d_k_new + l * kv_stride, (const char*)d_v_new + l * kv_stride,
+                                 d_block_table, max_blocks, d_ctx_lens, batch, stage_valid, cs)))
+        return rc;
+    }
+    if ((rc = launch_attn_decode(p, l, (const char*)d_q_all + l * q_stride, d_block_table, max_blocks, d_ctx_lens,
+                                 batch, (char*)d_out_all + l * q_stride, stage_valid, cs)))
+      return rc;
+    if (timed) PIE_HIP(hipEventRecord(p->lev[l].attn_end, cs));
+    if ((rc = compute_epilogue(p, l, cs))) return rc;
+    if (n_dirty > 0 && d_k_new) {
+      if ((rc = swap_out_impl(p, l, n_dirty, h_dirty, os, timed ? p->lev[l].out_start : nullptr,
+                              timed ? p->lev[l].out_end : nullptr)))
+        return rc;
+      p->lev[l].out_used = timed;
+    }
+  }
+  p->step_timed = timed;
+  return PIE_OK;
+}
+
+int pie_set_timing(pie_pool* p, int32_t on) {
+  if (!p) return PIE_EINVAL;
+  p->timing = on != 0;
+  return PIE_OK;
+}
+
+static int elapsed(hipEvent_t a, hipEvent_t b, float* ms) {
+  hipError_t e = hipEventElapsedTime(ms, a, b);
+  if (e != hipSuccess) {
+    g_last_hip_error = (int)e;
+    (void)hipGetLastError();
+    return PIE_EHIP;
+  }
+  return PIE_OK;
+}
+
+int pie_get_layer_times(pie_pool* p, float* t_attn, float* t_in, float* t_out, float* t_stall) {
+  if (!p) return PIE_EINVAL;
+  if (!p->device || !p->step_timed) return PIE_ESTATE;
+  const int32_t L = p->cfg.n_layers;
+  int rc;
+  for (int32_t l = 0; l < L; ++l) {
+    float ms = 0.f;
+    if (t_attn) {
+      if ((rc = elapsed(p->lev[l].attn_start, p->lev[l].attn_end, &ms))) return rc;
+      t_attn[l] = ms;
+    }
+    if (t_in) {
+      ms = 0.f;
+      if (p->lev[l].in_used && (rc = elapsed(p->lev[l].in_start, p->lev[l].in_end, &ms))) return rc;
+      t_in[l] = ms;
+    }
+    if (t_out) {
+      ms = 0.f;
+      if (p->lev[l].out_used && (rc = elapsed(p->lev[l].out_start, p->lev[l].out_end, &ms))) return rc;
+      t_out[l] = ms;
+    }
+    if (t_stall) {
+      // idle time of the compute stream before this layer: from the previous layer's end (or the step's
+      // start) to this layer's start
+      if ((rc = elapsed(l == 0 ? p->ev_step_start : p->lev[l - 1].attn_end, p->lev[l].attn_start, &ms))) return rc;
+      t_stall[l] = ms > 0.f ? ms : 0.f;
+    }
+  }
+  return PIE_OK;
+}
+
+int pie_get_stats(pie_pool* p, pie_stats* out) {
+  if (!p || !out) return PIE_EINVAL;
+  std::memset(out, 0, sizeof(*out));
+  out->n_layers = p->cfg.n_layers;
+  out->host_blocks_in_use = p->n_in_use[1];
+  out->gpu_blocks_in_use = p->n_in_use[0];
+  const int32_t tot = p->n_in_use[0] + p->n_in_use[1];
+  const float f = tot ? (float)p->n_in_use[1] / (float)tot : 0.f;
+  out->host_fraction = f;
+  out->expansion_simple = f < 1.f ? 1.f / (1.f - f) : INFINITY;
+  const float L = (float)p->cfg.n_layers;
+  out->expansion_staged = L / (L * (1.f - f) + 2.f * f);
+  out->bytes_in = p->bytes_in;
+  out->bytes_out = p->bytes_out;
+  if (p->device && p->step_timed) {
+    const int32_t n = p->cfg.n_layers;
+    std::vector<float> a(n), i(n), o(n), s(n);
+    int rc = pie_get_layer_times(p, a.data(), i.data(), o.data(), s.data());
+    if (rc) return rc;
+    for (int32_t l = 0; l < n; ++l) {
+      out->attn_ms += a[l];
+      out->swap_in_ms += i[l];
+      out->swap_out_ms += o[l];
+      out->stall_ms += s[l];
+    }
+    if ((rc = elapsed(p->ev_step_start, p->lev[n - 1].attn_end, &out->step_ms))) return rc;
+  }
+  out->device_error_flags = p->last_err_flags;
+  return PIE_OK;
+}
+
+int pie_check_errors_sync(pie_pool* p, uint32_t* out_flags) {
+  if (!p || !out_flags) return PIE_EINVAL;
+  *out_flags = 0;
+  if (!p->device) return PIE_OK;
+  int rc = pie_pool_sync(p);
+  if (rc) return rc;
+  PIE_HIP(hipMemcpy(out_flags, p->d_err, sizeof(uint32_t), hipMemcpyDeviceToHost));
+  p->last_err_flags |= *out_flags;
+  if (*out_flags) {
+    if ((rc = launch_zero_u32(p->d_err, 1, nullptr))) return rc;
+    PIE_HIP(hipStreamSynchronize(nullptr));
+  }
+  return PIE_OK;
+}
+
+int pie_last_hip_error(void) { return g_last_hip_error; }
+
+const char* pie_strerror(int code) {
+  switch (code) {
+    case PIE_OK: return "ok";
+    case PIE_EINVAL: return "invalid argument";
+    case PIE_ENOMEM: return "pool, staging region or buffer too small";
+    case PIE_ESTATE: return "operation not valid in this state";
+    case PIE_EHIP: return "HIP runtime error";
+    default: return "unknown error";
+  }
+}
+
+int pie_version(void) { return 1; }
+
+}  // extern "C"

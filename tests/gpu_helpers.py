@@ -1,0 +1,78 @@
+"""Plumbing for the GPU parity tests: put a synthetic case into a library pool
+and into the oracle's pool model with identical placement."""
+import numpy as np
+import torch
+
+import helpers as H
+from oracle.pool_model import PoolModel
+from paper_2411_09317_amd import binding as B
+from paper_2411_09317_amd import inputs as I
+
+DEV = "cuda:0"
+TORCH_DT = {I.DTYPE_F32: torch.float32, I.DTYPE_F16: torch.float16, I.DTYPE_BF16: torch.bfloat16}
+
+
+def to_dev(arr: np.ndarray, dtype: int):
+    """Storage array -> device tensor (bf16 travels as its 16-bit patterns)."""
+    if dtype == I.DTYPE_BF16:
+        return torch.from_numpy(arr.view(np.int16).copy()).to(DEV).view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(arr)).to(DEV)
+
+
+def from_dev(t, dtype: int) -> np.ndarray:
+    """Device tensor -> float64 numpy (exact for all three storage types)."""
+    return t.detach().to("cpu").to(torch.float64).numpy()
+
+
+def make_pools(case, n_gpu, n_stage, n_host, order_seed=0, upto_ctx=None, fill=None, scale=0.0, max_blocks=None):
+    w = case.w
+    mb = max_blocks or max(1, case.max_blocks)
+    lib = B.Pool(w.n_layers, w.n_q_heads, w.n_kv_heads, w.head_dim, w.block_tokens, w.dtype, n_gpu, n_stage, n_host,
+                 max_batch=w.batch, max_blocks_per_seq=mb, softmax_scale=scale, device=DEV)
+    mod = PoolModel(w.n_layers, w.n_q_heads, w.n_kv_heads, w.head_dim, w.block_tokens, w.dtype, n_gpu, n_stage, n_host,
+                    softmax_scale=scale)
+    plan = H.plan_allocation(case, order_seed)
+    table = H.allocate(lib, case, plan)
+    table_m = H.allocate(mod, case, plan)
+    assert np.array_equal(table, table_m)
+    if mb > table.shape[1]:
+        table = np.concatenate([table, np.full((w.batch, mb - table.shape[1]), -1, np.int32)], axis=1)
+    where, slot = H.home_maps(mod, table)
+    g, h = H.build_images(case, table, where, slot, n_gpu, n_host, upto_ctx=upto_ctx, fill=fill)
+    mod.gpu[:, :n_gpu] = g
+    mod.host[:] = h
+    if fill is not None:
+        mod.gpu[:, n_gpu:] = fill
+    load_images(lib, mod)
+    return lib, mod, table
+
+
+def load_images(lib, mod):
+    """Copy the model's pool images (staging included) into the library's pools."""
+    L = mod.L
+    gi = torch.from_numpy(mod.gpu.reshape(L, mod.gpu.shape[1], -1).view(np.uint8).copy())
+    lib.gpu_image().copy_(gi.to(DEV))
+    if mod.n_host:
+        hi = torch.from_numpy(mod.host.reshape(L, mod.n_host, -1).view(np.uint8).copy())
+        lib.host_image().copy_(hi)
+    torch.cuda.synchronize()
+
+
+def images_of(lib):
+    torch.cuda.synchronize()
+    g = lib.gpu_image().cpu().numpy()
+    h = lib.host_image().cpu().numpy() if lib.h_buf is not None else None
+    return g, h
+
+
+def model_bytes(mod):
+    L = mod.L
+    return (mod.gpu.reshape(L, mod.gpu.shape[1], -1).view(np.uint8), mod.host.reshape(L, mod.n_host, -1).view(np.uint8))
+
+
+def rowwise_rel_err(got: np.ndarray, ref: np.ndarray) -> float:
+    """max over rows (last axis) of |got-ref|_inf / |ref|_inf."""
+    num = np.abs(got - ref).max(axis=-1)
+    den = np.abs(ref).max(axis=-1)
+    den = np.where(den == 0, 1.0, den)
+    return float((num / den).max())
