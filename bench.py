@@ -1,0 +1,243 @@
+#!/usr/bin/env python3
+"""Benchmark of the decode hot path on one MI355X.
+
+A step is one pass of the whole path over one synthetic batch: for every layer,
+append the new token's K/V and run paged-attention decode (and, in the swap leg,
+prefetch the next layer's host-resident blocks behind it and write dirty blocks
+back).  The headline number is decode tokens/s on the Llama-2-7B-shaped fp16
+workload with all KV resident (inputs already in HBM).  The same line carries
+the roofline of the attention kernel, the float64 oracle timed on the host's
+cores on a sample, and the swap leg: 30 % of every sequence's blocks in pinned
+host memory, reporting host-link GB/s, kernel-latency inflation and stall.
+
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+LINK_PEAK_GBS = 63.0           # PCIe Gen5 x16, per direction, before protocol overhead
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg4", "cfg5"])
+    ap.add_argument("--layers", type=int, default=None, help="override the number of layers (diagnostics only)")
+    ap.add_argument("--partition", type=int, default=0, help="attention partition size in tokens (0 = library default)")
+    ap.add_argument("--swap-fraction", type=float, default=0.30)
+    ap.add_argument("--swap-steps", type=int, default=3)
+    ap.add_argument("--swap-path", type=int, default=0)
+    ap.add_argument("--no-swap", action="store_true")
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--cpu-seqs", type=int, default=64)
+    ap.add_argument("--cpu-layers", type=int, default=6)
+    ap.add_argument("--calib-copy-mib", type=int, default=0,
+                    help="also run a plain elementwise copy of this many MiB (a known-size reference for HBM counters)")
+    return ap.parse_args()
+
+
+def timed_steps(dw, streams, n, pf, dirty):
+    import torch
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(n):
+        dw.pool.step(dw.q, dw.k_new, dw.v_new, dw.d_table, dw.d_ctx, pf, dirty, dw.out, *streams)
+    dw.pool.sync()
+    torch.cuda.synchronize()
+    return time.perf_counter() - t0
+
+
+def layer_profile(dw, streams, pf, dirty, reps=3):
+    """Per-layer event times (ms), median over a few timed steps."""
+    acc = {}
+    dw.pool.set_timing(True)
+    for _ in range(reps):
+        dw.pool.step(dw.q, dw.k_new, dw.v_new, dw.d_table, dw.d_ctx, pf, dirty, dw.out, *streams)
+        dw.pool.sync()
+        lt = dw.pool.layer_times()
+        st = dw.pool.stats()
+        for k, v in lt.items():
+            acc.setdefault(k, []).append(v.copy())
+        acc.setdefault("step_ms", []).append(st.step_ms)
+        acc.setdefault("bytes_in", []).append(st.bytes_in)
+        acc.setdefault("bytes_out", []).append(st.bytes_out)
+    dw.pool.set_timing(False)
+    out = {k: np.median(np.stack(v), axis=0) for k, v in acc.items() if k not in ("step_ms", "bytes_in", "bytes_out")}
+    out["step_ms"] = float(np.median(acc["step_ms"]))
+    out["bytes_in"] = int(acc["bytes_in"][-1])
+    out["bytes_out"] = int(acc["bytes_out"][-1])
+    return out
+
+
+def traffic_from_profile(name):
+    """HBM bytes per launch measured with rocprofv3 counters, if a summary has been committed."""
+    path = os.path.join(ROOT, "profiles", name)
+    if not os.path.exists(path):
+        return None
+    for line in open(path):
+        if line.startswith("traffic_bytes_per_launch"):
+            return float(line.split("=")[1].split()[0])
+    return None
+
+
+def cpu_baseline(dw, n_seqs, n_layers):
+    """The float64 oracle on a sample: the first n_layers layers of the first n_seqs sequences, with the very
+    bytes the GPU holds.  Also checks the GPU's output for those sequences against it."""
+    import torch
+    from threadpoolctl import threadpool_info
+    from oracle.pool_model import PoolModel
+    w = dw.w
+    n_seqs = min(n_seqs, w.batch)
+    nb = dw.n_blocks[:n_seqs]
+    total = int(nb.sum())
+    n_layers = min(n_layers, w.n_layers)
+    mod = PoolModel(n_layers, w.n_q_heads, w.n_kv_heads, w.head_dim, w.block_tokens, w.dtype, total, 0, 0)
+    handles = mod.block_alloc(0, total)
+    table = np.full((n_seqs, int(nb.max())), -1, dtype=np.int32)
+    where, slots = dw.pool.block_where(dw.table[:n_seqs][dw.table[:n_seqs] >= 0])
+    assert all(x == 0 for x in where)
+    src = torch.as_tensor(np.asarray(slots, dtype=np.int64), device=dw.q.device)
+    sd = mod.gpu.dtype
+    for l in range(n_layers):
+        blocks = dw.pool.gpu_image()[l].index_select(0, src).cpu().numpy()       # [total][block_bytes]
+        mod.gpu[l, :total] = blocks.view(sd).reshape((total,) + mod.gpu.shape[2:])
+    i = 0
+    for b in range(n_seqs):
+        for j in range(int(nb[b])):
+            table[b, j] = handles[i]
+            i += 1
+    q_dev = dw.q[:n_layers, :n_seqs]
+    q = q_dev.view(torch.int16).cpu().numpy().view(np.uint16) if w.dtype == 2 else q_dev.cpu().numpy()
+    dt, rel = 0.0, 0.0
+    for l in range(n_layers):
+        t0 = time.perf_counter()
+        ref = mod.attn_decode(l, q[l], table, dw.ctx_lens[:n_seqs])
+        dt += time.perf_counter() - t0
+        got = dw.out[l, :n_seqs].to(torch.float64).cpu().numpy()
+        num = np.abs(got - ref).max(axis=-1)
+        den = np.abs(ref).max(axis=-1)
+        rel = max(rel, float((num / np.where(den == 0, 1, den)).max()))
+    threads = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    tokens_per_s = n_seqs / (dt * w.n_layers / n_layers)     # n_layers timed; a step has w.n_layers of them
+    return {"value": tokens_per_s, "unit": "tokens/s", "cores": int(threads), "kind": "oracle",
+            "sample": f"float64 oracle, first {n_layers} of {w.n_layers} layers, first {n_seqs} of {w.batch} sequences "
+                      f"({int(dw.ctx_lens[:n_seqs].sum())} context tokens per layer), {dt:.2f} s; scaled by "
+                      f"{w.n_layers}/{n_layers} layers to a whole step", "host_cpus": os.cpu_count(),
+            "gpu_vs_oracle_rowwise_rel_err": rel}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print(f"bench.py measures one GPU; --gpus {args.gpus} is not supported in this build "
+              "(the path shards by sequence with no exchange step; see DESIGN.md)", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2411_09317_amd import binding as B
+    from paper_2411_09317_amd import inputs as I
+    from paper_2411_09317_amd import workload as WL
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    w = I.CONFIGS[args.workload]
+    swap_leg = not args.no_swap and args.swap_fraction > 0
+    t_build = time.perf_counter()
+    dw = WL.build(w, host_capacity_fraction=(args.swap_fraction + 0.02) if swap_leg else 0.0, n_layers=args.layers)
+    w = dw.w
+    t_build = time.perf_counter() - t_build
+    if args.partition:
+        dw.pool.set_attn_partition(args.partition)
+    dw.pool.set_swap_path(args.swap_path)
+    streams = (torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream())
+    none = np.zeros(0, dtype=np.int32)
+
+    if args.calib_copy_mib:
+        n = args.calib_copy_mib * (1 << 20) // 4
+        src = torch.ones(n, dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1.0, out=dst)          # reads n*4 bytes, writes n*4 bytes
+        torch.cuda.synchronize()
+        del src, dst
+
+    # ---- all-resident: the headline ---------------------------------------------------------------
+    timed_steps(dw, streams, args.warmup, none, none)
+    total_s = timed_steps(dw, streams, args.steps, none, none)
+    ms_per_step = total_s / args.steps * 1e3
+    tokens_per_s = w.batch / (total_s / args.steps)
+    prof = layer_profile(dw, streams, none, none)
+    assert dw.pool.check_errors() == 0
+    k_ms = float(np.mean(prof["kernel"]))
+    bytes_layer = dw.kv_bytes_per_layer
+    achieved = bytes_layer / (k_ms * 1e-3) / 1e9
+    elem = {0: "f32", 1: "f16", 2: "bf16"}[w.dtype]
+    result = {
+        "metric": "decode tokens/s", "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": elem, "data": "synthetic",
+        "config": {"workload": f"{w.name}: {w.n_layers} layers, batch {w.batch}, {w.n_q_heads} q heads / "
+                               f"{w.n_kv_heads} kv heads, head_dim {w.head_dim}, block 16, ctx {w.ctx_dist} "
+                               f"[{w.ctx_lo},{w.ctx_hi}], all KV GPU-resident",
+                   "context_tokens": int(dw.ctx_lens.sum()), "kv_bytes_per_layer": bytes_layer,
+                   "kv_blocks_per_layer": dw.total_blocks, "attn_partition_tokens": args.partition or 512,
+                   "build_s": round(t_build, 1)},
+        "roofline": {"bound": "hbm", "kernel": "k_attn_decode", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": traffic_from_profile(f"attn_decode_{w.name}_pmc.txt"),
+                     "kernel_ms": k_ms, "algorithmic_bytes_per_launch": bytes_layer},
+        "per_layer_ms": {"attn_total": float(np.mean(prof["attn"])), "attn_kernel": k_ms,
+                         "step_ms_events": prof["step_ms"]},
+    }
+    base_kernel_ms = prof["kernel"].copy()
+    base_step_ms = ms_per_step
+
+    # ---- the oracle on the host's cores -----------------------------------------------------------------
+    if not args.no_cpu:
+        result["cpu_baseline"] = cpu_baseline(dw, args.cpu_seqs, args.cpu_layers)
+
+    # ---- swap leg: a fraction of every sequence's blocks in pinned host memory ------------------------------
+    if swap_leg:
+        hs = WL.per_sequence_host_order(dw, args.swap_fraction, I.CONFIGS.get("cfg3") if w.name == "cfg2" else None)
+        t0 = time.perf_counter()
+        dw.pool.migrate(hs, B.HOST, streams[1])
+        dw.pool.sync()
+        t_mig = time.perf_counter() - t0
+        pf, dirty = dw.pool.prefetch_list(dw.table, dw.ctx_lens)
+        timed_steps(dw, streams, 1, pf, dirty)
+        s_total = timed_steps(dw, streams, args.swap_steps, pf, dirty)
+        sp = layer_profile(dw, streams, pf, dirty, reps=2)
+        assert dw.pool.check_errors() == 0
+        st = dw.pool.stats()
+        in_gbs = sp["bytes_in"] / w.n_layers / (float(np.mean(sp["swap_in"])) * 1e-3) / 1e9
+        result["swap"] = {
+            "host_fraction": st.host_fraction, "host_blocks": st.host_blocks_in_use,
+            "expansion_simple": st.expansion_simple, "expansion_staged": st.expansion_staged,
+            "tokens_per_s": w.batch / (s_total / args.swap_steps), "ms_per_step": s_total / args.swap_steps * 1e3,
+            "bytes_in_per_layer": sp["bytes_in"] // w.n_layers, "bytes_out_per_layer": sp["bytes_out"] // w.n_layers,
+            "swap_in_ms_per_layer": float(np.mean(sp["swap_in"])), "swap_out_ms_per_layer": float(np.mean(sp["swap_out"])),
+            "host_link_GBps": in_gbs, "host_link_peak_GBps": LINK_PEAK_GBS, "host_link_frac": in_gbs / LINK_PEAK_GBS,
+            "attn_kernel_ms_per_layer": float(np.mean(sp["kernel"])),
+            "inflation_kernel": float(np.median(sp["kernel"]) / np.median(base_kernel_ms) - 1.0),
+            "stall_ms_per_step": float(np.sum(sp["stall"])),
+            "inflation_e2e": (s_total / args.swap_steps * 1e3) / base_step_ms - 1.0,
+            "transparent_fraction_bound": in_gbs / achieved, "migrate_s": round(t_mig, 2),
+            "swap_path": args.swap_path,
+        }
+    dw.pool.close()
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

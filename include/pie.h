@@ -232,8 +232,10 @@ int pie_pool_sync(pie_pool* pool);
 /* Summary of the last pie_step (timing must be on and the step complete: call after pie_pool_sync). */
 int pie_get_stats(pie_pool* pool, pie_stats* out);
 
-/* Per-layer times in ms of the last pie_step; each array has n_layers entries (NULL to skip one). */
-int pie_get_layer_times(pie_pool* pool, float* t_attn, float* t_in, float* t_out, float* t_stall);
+/* Per-layer times in ms of the last pie_step; each array has n_layers entries (NULL to skip one).
+ * t_attn: append + attention + reduction; t_kernel: the attention decode kernel alone; t_in / t_out: the
+ * layer's prefetch / write-back; t_stall: idle time of the compute stream before the layer. */
+int pie_get_layer_times(pie_pool* pool, float* t_attn, float* t_kernel, float* t_in, float* t_out, float* t_stall);
 
 /* Reads and clears the device error flags after synchronising the pool. */
 int pie_check_errors_sync(pie_pool* pool, uint32_t* out_flags);

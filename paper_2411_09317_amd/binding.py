@@ -268,10 +268,10 @@ class Pool:
 
     def layer_times(self):
         L = self.cfg.n_layers
-        arrs = [np.zeros(L, dtype=np.float32) for _ in range(4)]
+        arrs = [np.zeros(L, dtype=np.float32) for _ in range(5)]
         ps = [a.ctypes.data_as(C.POINTER(C.c_float)) for a in arrs]
         _check(_lib.pie_get_layer_times(self._h, *ps), "get_layer_times")
-        return dict(zip(("attn", "swap_in", "swap_out", "stall"), arrs))
+        return dict(zip(("attn", "kernel", "swap_in", "swap_out", "stall"), arrs))
 
     def check_errors(self) -> int:
         f = C.c_uint32(0)

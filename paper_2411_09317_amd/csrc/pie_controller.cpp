@@ -145,7 +145,7 @@ int pie_controller_update(pie_pool* p, pie_controller* c, double throughput, flo
   if (!p || !c || !out_host_fraction) return PIE_EINVAL;
   const int32_t L = p->cfg.n_layers;
   std::vector<float> a(L), i(L), s(L);
-  int rc = pie_get_layer_times(p, a.data(), i.data(), nullptr, s.data());
+  int rc = pie_get_layer_times(p, a.data(), nullptr, i.data(), nullptr, s.data());
   if (rc) return rc;
   std::vector<double> ad(a.begin(), a.end()), id(i.begin(), i.end()), sd(s.begin(), s.end());
   double in_sum = 0.0, span = 0.0;

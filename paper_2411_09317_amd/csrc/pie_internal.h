@@ -33,7 +33,8 @@ struct Home {
 };
 
 struct LayerEvents {
-  hipEvent_t attn_start, attn_end, in_start, in_end, out_start, out_end;
+  hipEvent_t attn_start = nullptr, attn_end = nullptr, k_start = nullptr, k_end = nullptr, in_start = nullptr,
+             in_end = nullptr, out_start = nullptr, out_end = nullptr;
   bool in_used = false, out_used = false;
 };
 
@@ -134,7 +135,8 @@ int launch_swap_copy(char* dst_layer_base, const char* src_layer_base, size_t bl
 int launch_kv_append(const pie_pool* p, int32_t layer, const void* d_k, const void* d_v, const int32_t* d_table,
                      int32_t max_blocks, const int32_t* d_ctx, int32_t batch, bool stage_valid, hipStream_t s);
 int launch_attn_decode(const pie_pool* p, int32_t layer, const void* d_q, const int32_t* d_table, int32_t max_blocks,
-                       const int32_t* d_ctx, int32_t batch, void* d_out, bool stage_valid, hipStream_t s);
+                       const int32_t* d_ctx, int32_t batch, void* d_out, bool stage_valid, hipStream_t s,
+                       hipEvent_t k_start = nullptr, hipEvent_t k_end = nullptr);
 size_t attn_workspace_floats(const pie_config& c);
 bool attn_config_supported(const pie_config& c);
 

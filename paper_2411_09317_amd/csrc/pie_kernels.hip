@@ -512,9 +512,12 @@ size_t attn_workspace_floats(const pie_config& c) {
 }
 
 template <typename E, int HD, int G>
-static int launch_typed(const AttnArgs& a, int32_t batch, int32_t n_q_heads, hipStream_t s) {
+static int launch_typed(const AttnArgs& a, int32_t batch, int32_t n_q_heads, hipStream_t s, hipEvent_t e0,
+                        hipEvent_t e1) {
+  if (e0) PIE_HIP(hipEventRecord(e0, s));
   hipLaunchKernelGGL((k_attn_decode<E, HD, G>), dim3(a.n_parts, a.n_kv_heads, batch), dim3(kWaves * 64), 0, s, a);
   PIE_HIP(hipGetLastError());
+  if (e1) PIE_HIP(hipEventRecord(e1, s));
   if (a.n_parts > 1) {
     hipLaunchKernelGGL((k_attn_reduce<E, HD>), dim3(n_q_heads, batch), dim3(HD), 0, s, a, n_q_heads);
     PIE_HIP(hipGetLastError());
@@ -523,27 +526,30 @@ static int launch_typed(const AttnArgs& a, int32_t batch, int32_t n_q_heads, hip
 }
 
 template <typename E, int HD>
-static int launch_g(const AttnArgs& a, int32_t g, int32_t batch, int32_t nq, hipStream_t s) {
+static int launch_g(const AttnArgs& a, int32_t g, int32_t batch, int32_t nq, hipStream_t s, hipEvent_t e0,
+                    hipEvent_t e1) {
   switch (g) {
-    case 1: return launch_typed<E, HD, 1>(a, batch, nq, s);
-    case 2: return launch_typed<E, HD, 2>(a, batch, nq, s);
-    case 4: return launch_typed<E, HD, 4>(a, batch, nq, s);
-    case 8: return launch_typed<E, HD, 8>(a, batch, nq, s);
+    case 1: return launch_typed<E, HD, 1>(a, batch, nq, s, e0, e1);
+    case 2: return launch_typed<E, HD, 2>(a, batch, nq, s, e0, e1);
+    case 4: return launch_typed<E, HD, 4>(a, batch, nq, s, e0, e1);
+    case 8: return launch_typed<E, HD, 8>(a, batch, nq, s, e0, e1);
     default: return PIE_EINVAL;
   }
 }
 
 template <typename E>
-static int launch_hd(const AttnArgs& a, int32_t hd, int32_t g, int32_t batch, int32_t nq, hipStream_t s) {
+static int launch_hd(const AttnArgs& a, int32_t hd, int32_t g, int32_t batch, int32_t nq, hipStream_t s, hipEvent_t e0,
+                     hipEvent_t e1) {
   switch (hd) {
-    case 64: return launch_g<E, 64>(a, g, batch, nq, s);
-    case 128: return launch_g<E, 128>(a, g, batch, nq, s);
+    case 64: return launch_g<E, 64>(a, g, batch, nq, s, e0, e1);
+    case 128: return launch_g<E, 128>(a, g, batch, nq, s, e0, e1);
     default: return PIE_EINVAL;
   }
 }
 
 int launch_attn_decode(const pie_pool* p, int32_t layer, const void* d_q, const int32_t* d_table, int32_t max_blocks,
-                       const int32_t* d_ctx, int32_t batch, void* d_out, bool stage_valid, hipStream_t s) {
+                       const int32_t* d_ctx, int32_t batch, void* d_out, bool stage_valid, hipStream_t s,
+                       hipEvent_t k_start, hipEvent_t k_end) {
   const pie_config& c = p->cfg;
   if (((uintptr_t)d_q | (uintptr_t)d_out) % 16) return PIE_EINVAL;
   if (max_blocks <= 0) return PIE_EINVAL;
@@ -578,9 +584,9 @@ int launch_attn_decode(const pie_pool* p, int32_t layer, const void* d_q, const 
   a.n_parts = n_parts;
   a.stage_valid = stage_valid ? 1 : 0;
   switch (c.dtype) {
-    case PIE_DTYPE_F32: return launch_hd<F32>(a, c.head_dim, g, batch, c.n_q_heads, s);
-    case PIE_DTYPE_F16: return launch_hd<F16>(a, c.head_dim, g, batch, c.n_q_heads, s);
-    case PIE_DTYPE_BF16: return launch_hd<BF16>(a, c.head_dim, g, batch, c.n_q_heads, s);
+    case PIE_DTYPE_F32: return launch_hd<F32>(a, c.head_dim, g, batch, c.n_q_heads, s, k_start, k_end);
+    case PIE_DTYPE_F16: return launch_hd<F16>(a, c.head_dim, g, batch, c.n_q_heads, s, k_start, k_end);
+    case PIE_DTYPE_BF16: return launch_hd<BF16>(a, c.head_dim, g, batch, c.n_q_heads, s, k_start, k_end);
     default: return PIE_EINVAL;
   }
 }

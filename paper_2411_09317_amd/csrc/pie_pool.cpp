@@ -372,7 +372,8 @@ int pie_pool_init(const pie_config* cfg, void* d_base, size_t d_bytes, void* h_p
     if (err != hipSuccess) { g_last_hip_error = (int)err; return fail(PIE_EHIP); }
     p->lev.resize(cfg->n_layers);
     for (auto& le : p->lev) {
-      hipEvent_t* tev[] = {&le.attn_start, &le.attn_end, &le.in_start, &le.in_end, &le.out_start, &le.out_end};
+      hipEvent_t* tev[] = {&le.attn_start, &le.attn_end, &le.k_start, &le.k_end,
+                           &le.in_start,   &le.in_end,   &le.out_start, &le.out_end};
       for (hipEvent_t* e : tev) {
         *e = nullptr;
         err = hipEventCreate(e);
@@ -406,7 +407,8 @@ int pie_pool_destroy(pie_pool* p) {
     for (hipEvent_t e : evs)
       if (e) (void)hipEventDestroy(e);
     for (auto& le : p->lev) {
-      hipEvent_t tev[] = {le.attn_start, le.attn_end, le.in_start, le.in_end, le.out_start, le.out_end};
+      hipEvent_t tev[] = {le.attn_start, le.attn_end, le.k_start, le.k_end,
+                          le.in_start,   le.in_end,   le.out_start, le.out_end};
       for (hipEvent_t e : tev)
         if (e) (void)hipEventDestroy(e);
     }
@@ -730,7 +732,8 @@ int pie_step(pie_pool* p, const void* d_q_all, const void* d_k_new, const void* 
         return rc;
     }
     if ((rc = launch_attn_decode(p, l, (const char*)d_q_all + l * q_stride, d_block_table, max_blocks, d_ctx_lens,
-                                 batch, (char*)d_out_all + l * q_stride, stage_valid, cs)))
+                                 batch, (char*)d_out_all + l * q_stride, stage_valid, cs,
+                                 timed ? p->lev[l].k_start : nullptr, timed ? p->lev[l].k_end : nullptr)))
       return rc;
     if (timed) PIE_HIP(hipEventRecord(p->lev[l].attn_end, cs));
     if ((rc = compute_epilogue(p, l, cs))) return rc;
@@ -761,7 +764,7 @@ static int elapsed(hipEvent_t a, hipEvent_t b, float* ms) {
   return PIE_OK;
 }
 
-int pie_get_layer_times(pie_pool* p, float* t_attn, float* t_in, float* t_out, float* t_stall) {
+int pie_get_layer_times(pie_pool* p, float* t_attn, float* t_kernel, float* t_in, float* t_out, float* t_stall) {
   if (!p) return PIE_EINVAL;
   if (!p->device || !p->step_timed) return PIE_ESTATE;
   const int32_t L = p->cfg.n_layers;
@@ -771,6 +774,10 @@ int pie_get_layer_times(pie_pool* p, float* t_attn, float* t_in, float* t_out, f
     if (t_attn) {
       if ((rc = elapsed(p->lev[l].attn_start, p->lev[l].attn_end, &ms))) return rc;
       t_attn[l] = ms;
+    }
+    if (t_kernel) {
+      if ((rc = elapsed(p->lev[l].k_start, p->lev[l].k_end, &ms))) return rc;
+      t_kernel[l] = ms;
     }
     if (t_in) {
       ms = 0.f;
@@ -809,7 +816,7 @@ int pie_get_stats(pie_pool* p, pie_stats* out) {
   if (p->device && p->step_timed) {
     const int32_t n = p->cfg.n_layers;
     std::vector<float> a(n), i(n), o(n), s(n);
-    int rc = pie_get_layer_times(p, a.data(), i.data(), o.data(), s.data());
+    int rc = pie_get_layer_times(p, a.data(), nullptr, i.data(), o.data(), s.data());
     if (rc) return rc;
     for (int32_t l = 0; l < n; ++l) {
       out->attn_ms += a[l];
