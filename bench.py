@@ -36,6 +36,7 @@ def parse():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg4", "cfg5"])
     ap.add_argument("--layers", type=int, default=None, help="override the number of layers (diagnostics only)")
+    ap.add_argument("--ctx-fixed", type=int, default=0, help="diagnostics: give every sequence this context length")
     ap.add_argument("--partition", type=int, default=0, help="attention partition size in tokens (0 = library default)")
     ap.add_argument("--swap-fraction", type=float, default=0.30)
     ap.add_argument("--swap-steps", type=int, default=3)
@@ -152,6 +153,8 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     w = I.CONFIGS[args.workload]
+    if args.ctx_fixed:
+        w = I.scaled(w, name=w.name + "-fixedctx", ctx_dist="fixed", ctx_lo=args.ctx_fixed, ctx_hi=args.ctx_fixed)
     swap_leg = not args.no_swap and args.swap_fraction > 0
     t_build = time.perf_counter()
     dw = WL.build(w, host_capacity_fraction=(args.swap_fraction + 0.02) if swap_leg else 0.0, n_layers=args.layers)
@@ -191,7 +194,7 @@ def main():
                                f"{w.n_kv_heads} kv heads, head_dim {w.head_dim}, block 16, ctx {w.ctx_dist} "
                                f"[{w.ctx_lo},{w.ctx_hi}], all KV GPU-resident",
                    "context_tokens": int(dw.ctx_lens.sum()), "kv_bytes_per_layer": bytes_layer,
-                   "kv_blocks_per_layer": dw.total_blocks, "attn_partition_tokens": args.partition or 512,
+                   "kv_blocks_per_layer": dw.total_blocks, "attn_partition_tokens": args.partition or 1024,
                    "build_s": round(t_build, 1)},
         "roofline": {"bound": "hbm", "kernel": "k_attn_decode", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,

@@ -23,12 +23,12 @@ FLAGS = [
 ]
 
 
-def build(verbose: bool = True) -> str:
+def build(verbose: bool = True, out: str = LIB, defines=()) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc] + FLAGS
+    cmd = [hipcc] + FLAGS + ["-D" + d for d in defines]
     for src in SOURCES:
         cmd += ["-x", "hip", os.path.join(CSRC, src)]
-    cmd += ["-o", LIB]
+    cmd += ["-o", out]
     if verbose:
         print(" ".join(cmd), flush=True)
     res = subprocess.run(cmd, capture_output=True, text=True)
@@ -39,7 +39,7 @@ def build(verbose: bool = True) -> str:
         raise RuntimeError("hipcc failed")
     if verbose and err.strip():
         sys.stderr.write(err + "\n")
-    return LIB
+    return out
 
 
 if __name__ == "__main__":

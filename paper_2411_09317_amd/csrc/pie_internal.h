@@ -98,7 +98,8 @@ struct pie_pool {
 
   // options
   int32_t swap_path = PIE_SWAP_AUTO;
-  int32_t attn_partition = 512;   // tokens per workgroup
+  int32_t attn_partition = 1024;  // tokens per workgroup
+  bool attn_nontemporal = true;   // non-temporal K/V loads in the attention kernel
   int32_t swap_wgs = 64;          // workgroups of the gather / scatter kernel
   bool timing = false;
   uint32_t last_err_flags = 0;    // device error flags seen by pie_check_errors_sync so far

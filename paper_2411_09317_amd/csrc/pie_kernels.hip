@@ -14,6 +14,8 @@
 #include <hip/hip_fp16.h>
 #include <hip/hip_runtime.h>
 
+#include <cstdlib>
+
 #include "pie_internal.h"
 
 namespace pie {
@@ -266,7 +268,10 @@ int launch_kv_append(const pie_pool* p, int32_t layer, const void* d_k, const vo
 // as (m, l, acc) for the reduction kernel.
 // ---------------------------------------------------------------------------------------------------
 
-constexpr int kWaves = 4;
+#ifndef PIE_KWAVES
+#define PIE_KWAVES 4
+#endif
+constexpr int kWaves = PIE_KWAVES;
 constexpr int kBlockTokens = 16;
 constexpr float kNegBig = -1.0e30f;   // finite stand-in for -inf as the initial running max
 
@@ -301,9 +306,20 @@ struct AttnArgs {
   float scale_log2e;
   int32_t max_blocks, n_handles, n_gpu_blocks, n_slots, n_kv_heads, part_tokens, n_parts;
   int32_t stage_valid;
+  int32_t nontemporal;       // stream K/V past the caches (each byte is read once)
+  int32_t exp_mode;          // TIMING EXPERIMENT ONLY
+#ifdef PIE_EXPERIMENT
+  unsigned long long* dbg;   // per-workgroup timestamps
+  int32_t dbg_cap;
+#endif
 };
 
-template <typename E, int HD, int G>
+__device__ __forceinline__ uint4 nt_load16(const char* p) {
+  const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+template <typename E, int HD, int G, bool NT>
 __global__ __launch_bounds__(kWaves * 64) void k_attn_decode(const AttnArgs a) {
   using EL = Elem<E>;
   constexpr int VEC = EL::kVec;
@@ -313,7 +329,12 @@ __global__ __launch_bounds__(kWaves * 64) void k_attn_decode(const AttnArgs a) {
   constexpr int TILE_BYTES = kBlockTokens * HD * (16 / VEC);
   static_assert(LPR >= 4 && LPR <= 64 && NLD >= 1, "unsupported head_dim / dtype");
 
-  const int32_t part = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+  // grid (kv head, sequence, partition): partitions are the slowest index, so the short last partitions of
+  // the sequences are dispatched at the end and even out the tail of the launch
+  const int32_t g = blockIdx.x, b = blockIdx.y, part = blockIdx.z;
+#ifdef PIE_EXPERIMENT
+  const unsigned long long t_entry = wall_clock64();
+#endif
   const int32_t ctx = a.ctx[b];
   const int32_t tok0 = part * a.part_tokens;
   const int32_t n_parts_b = ctx <= 0 ? 1 : (ctx + a.part_tokens - 1) / a.part_tokens;
@@ -358,26 +379,39 @@ __global__ __launch_bounds__(kWaves * 64) void k_attn_decode(const AttnArgs a) {
     if (j >= a.max_blocks) atomicOr(a.err, PIE_DEVERR_BAD_HANDLE);
   }
 
-  const size_t head_off = (size_t)g * TILE_BYTES;
-  const size_t v_off = a.block_bytes / 2;
+  // TIMING EXPERIMENT (exp_mode & 4): pretend K and V tiles of a head are adjacent (in-bounds, wrong data)
+  const size_t head_off = (a.exp_mode & 4) ? (size_t)g * 2 * TILE_BYTES : (size_t)g * TILE_BYTES;
+  const size_t v_off = (a.exp_mode & 4) ? (size_t)TILE_BYTES : a.block_bytes / 2;
 
-  uint4 kr[NLD], vr[NLD];
-  auto load_tile = [&](int32_t slot) {
+  // Two register sets: while one tile is consumed the next is already in flight (8 KiB per wave).
+  uint4 kA[NLD], vA[NLD], kB[NLD], vB[NLD];
+  auto load_tile = [&](uint4 (&kr)[NLD], uint4 (&vr)[NLD], int32_t it) {
+    int32_t slot = __shfl(my_slot, it, 64);
+    slot = slot < 0 ? 0 : slot;                                    // flagged blocks are masked below
     const char* kp = a.kv_layer + (size_t)slot * a.block_bytes + head_off + (size_t)lane * 16;
 #pragma unroll
-    for (int i = 0; i < NLD; ++i) kr[i] = *reinterpret_cast<const uint4*>(kp + (size_t)i * 1024);
+    for (int i = 0; i < NLD; ++i) kr[i] = NT ? nt_load16(kp + (size_t)i * 1024)
+                                             : *reinterpret_cast<const uint4*>(kp + (size_t)i * 1024);
 #pragma unroll
-    for (int i = 0; i < NLD; ++i) vr[i] = *reinterpret_cast<const uint4*>(kp + v_off + (size_t)i * 1024);
+    for (int i = 0; i < NLD; ++i) vr[i] = NT ? nt_load16(kp + v_off + (size_t)i * 1024)
+                                             : *reinterpret_cast<const uint4*>(kp + v_off + (size_t)i * 1024);
   };
-
-  for (int32_t it = 0; it < n_it; ++it) {
-    const int32_t slot = __shfl(my_slot, it, 64);
-    if (slot < 0) continue;                                        // flagged; treated as masked
-    load_tile(slot);
+  auto consume = [&](uint4 (&kr)[NLD], uint4 (&vr)[NLD], int32_t it) {
     const int32_t t_base = (jb0 + wave + kWaves * it) * kBlockTokens + rg;   // token of load 0
-    const bool tail = t_base - rg + kBlockTokens > tok1;
+    const bool present = __shfl(my_slot, it, 64) >= 0;
+    const int32_t limit = present ? tok1 : 0;                               // a missing block contributes nothing
+    const bool tail = t_base - rg + kBlockTokens > limit;
 
     float s[G][NLD];
+    if (a.exp_mode & 1) {
+      uint32_t x = 0;
+#pragma unroll
+      for (int i = 0; i < NLD; ++i) x ^= kr[i].x ^ kr[i].y ^ kr[i].z ^ kr[i].w;
+#pragma unroll
+      for (int i = 0; i < NLD; ++i)
+#pragma unroll
+        for (int h = 0; h < G; ++h) s[h][i] = (x == 0x12345u) ? 1.f : 0.f;
+    } else
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
       float kf[VEC];
@@ -393,7 +427,7 @@ __global__ __launch_bounds__(kWaves * 64) void k_attn_decode(const AttnArgs a) {
     if (tail) {
 #pragma unroll
       for (int i = 0; i < NLD; ++i) {
-        const bool valid = t_base + i * TPL < tok1;
+        const bool valid = t_base + i * TPL < limit;
 #pragma unroll
         for (int h = 0; h < G; ++h) s[h][i] = valid ? s[h][i] : -INFINITY;
         if (!valid) vr[i] = make_uint4(0, 0, 0, 0);                // garbage rows must not reach the sum
@@ -418,6 +452,12 @@ __global__ __launch_bounds__(kWaves * 64) void k_attn_decode(const AttnArgs a) {
 #pragma unroll
       for (int v = 0; v < VEC; ++v) acc[h][v] *= corr;
     }
+    if (a.exp_mode & 2) {
+      uint32_t x = 0;
+#pragma unroll
+      for (int i = 0; i < NLD; ++i) x ^= vr[i].x ^ vr[i].y ^ vr[i].z ^ vr[i].w;
+      acc[0][0] += (x == 0x12345u) ? p[0][0] : 0.f;
+    } else
 #pragma unroll
     for (int i = 0; i < NLD; ++i) {
       float vf[VEC];
@@ -427,8 +467,24 @@ __global__ __launch_bounds__(kWaves * 64) void k_attn_decode(const AttnArgs a) {
 #pragma unroll
         for (int v = 0; v < VEC; ++v) acc[h][v] = fmaf(p[h][i], vf[v], acc[h][v]);
     }
+  };
+
+#ifdef PIE_EXPERIMENT
+  const unsigned long long t_pro = wall_clock64();
+#endif
+  if (n_it > 0) load_tile(kA, vA, 0);
+  for (int32_t it = 0; it < n_it; it += 2) {
+    if (it + 1 < n_it) load_tile(kB, vB, it + 1);
+    consume(kA, vA, it);
+    if (it + 1 < n_it) {
+      if (it + 2 < n_it) load_tile(kA, vA, it + 2);
+      consume(kB, vB, it + 1);
+    }
   }
 
+#ifdef PIE_EXPERIMENT
+  const unsigned long long t_loop = wall_clock64();
+#endif
   // merge the kWaves * TPL partial states, one query head at a time to keep LDS small
   constexpr int NP = kWaves * TPL;
   __shared__ float s_m[NP], s_l[NP];
@@ -468,6 +524,19 @@ __global__ __launch_bounds__(kWaves * 64) void k_attn_decode(const AttnArgs a) {
       }
     }
   }
+#ifdef PIE_EXPERIMENT
+  if (a.dbg && lane == 0) {
+    const int wg = (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
+    if (wg < a.dbg_cap) {
+      unsigned long long* d = a.dbg + ((size_t)wg * kWaves + wave) * 6;
+      d[0] = t_entry; d[1] = t_pro; d[2] = t_loop; d[3] = wall_clock64();
+      d[4] = (unsigned long long)n_it;
+      unsigned hwid; asm volatile("s_getreg_b32 %0, hwreg(HW_REG_HW_ID)" : "=s"(hwid));
+      unsigned xcc; asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
+      d[5] = ((unsigned long long)xcc << 32) | hwid;
+    }
+  }
+#endif
 }
 
 // Reduction over the partitions of one (sequence, query head): out = sum_s 2^(m_s - M) acc_s / sum_s 2^(m_s - M) l_s.
@@ -515,7 +584,10 @@ template <typename E, int HD, int G>
 static int launch_typed(const AttnArgs& a, int32_t batch, int32_t n_q_heads, hipStream_t s, hipEvent_t e0,
                         hipEvent_t e1) {
   if (e0) PIE_HIP(hipEventRecord(e0, s));
-  hipLaunchKernelGGL((k_attn_decode<E, HD, G>), dim3(a.n_parts, a.n_kv_heads, batch), dim3(kWaves * 64), 0, s, a);
+  if (a.nontemporal)
+    hipLaunchKernelGGL((k_attn_decode<E, HD, G, true>), dim3(a.n_kv_heads, batch, a.n_parts), dim3(kWaves * 64), 0, s, a);
+  else
+    hipLaunchKernelGGL((k_attn_decode<E, HD, G, false>), dim3(a.n_kv_heads, batch, a.n_parts), dim3(kWaves * 64), 0, s, a);
   PIE_HIP(hipGetLastError());
   if (e1) PIE_HIP(hipEventRecord(e1, s));
   if (a.n_parts > 1) {
@@ -583,6 +655,13 @@ int launch_attn_decode(const pie_pool* p, int32_t layer, const void* d_q, const 
   a.part_tokens = part;
   a.n_parts = n_parts;
   a.stage_valid = stage_valid ? 1 : 0;
+  a.nontemporal = p->attn_nontemporal ? 1 : 0;
+  { const char* e = getenv("PIE_EXP_MODE"); a.exp_mode = e ? atoi(e) : 0; }
+#ifdef PIE_EXPERIMENT
+  { const char* e = getenv("PIE_DBG_PTR"); a.dbg = e ? (unsigned long long*)strtoull(e, nullptr, 10) : nullptr;
+    const char* c2 = getenv("PIE_DBG_CAP"); a.dbg_cap = c2 ? atoi(c2) : 0; }
+#endif
+  if (a.n_slots <= 0) return PIE_EINVAL;
   switch (c.dtype) {
     case PIE_DTYPE_F32: return launch_hd<F32>(a, c.head_dim, g, batch, c.n_q_heads, s, k_start, k_end);
     case PIE_DTYPE_F16: return launch_hd<F16>(a, c.head_dim, g, batch, c.n_q_heads, s, k_start, k_end);
