@@ -194,7 +194,7 @@ def main():
                                f"{w.n_kv_heads} kv heads, head_dim {w.head_dim}, block 16, ctx {w.ctx_dist} "
                                f"[{w.ctx_lo},{w.ctx_hi}], all KV GPU-resident",
                    "context_tokens": int(dw.ctx_lens.sum()), "kv_bytes_per_layer": bytes_layer,
-                   "kv_blocks_per_layer": dw.total_blocks, "attn_partition_tokens": args.partition or 1024,
+                   "kv_blocks_per_layer": dw.total_blocks, "attn_partition_tokens": args.partition or 512,
                    "build_s": round(t_build, 1)},
         "roofline": {"bound": "hbm", "kernel": "k_attn_decode", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,

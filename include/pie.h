@@ -173,7 +173,7 @@ int pie_set_host_fraction(pie_pool* pool, float f, int32_t n, const int32_t* ord
 int pie_set_swap_path(pie_pool* pool, int32_t path);
 
 /* Tokens of one sequence handled by one attention workgroup (rounded up to a multiple of 64, clamped to
- * [256, 4096]); longer contexts are split and reduced.  Default 1024. */
+ * [256, 4096]); longer contexts are split and reduced.  Default 512. */
 int pie_set_attn_partition(pie_pool* pool, int32_t tokens);
 
 /* Workgroups the gather / scatter kernel may occupy (1..1024, default 64): it is bound by the host link,

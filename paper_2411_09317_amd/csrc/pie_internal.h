@@ -66,6 +66,8 @@ struct pie_pool {
   int32_t* d_map[2] = {nullptr, nullptr};   // per staging region: handle -> device slot, or -1
   float* d_ws = nullptr;        // split-context partials
   size_t ws_floats = 0;
+  int32_t* d_plan = nullptr;    // attention planning state: header, ticket counters, items, resolved tables
+  int32_t n_cu = 256;           // compute units of the device
   uint32_t* d_err = nullptr;    // device error flags
   char* h_kv = nullptr;         // host pool base (host address)
   char* h_kv_dev = nullptr;     // same memory as seen from the device
@@ -98,7 +100,7 @@ struct pie_pool {
 
   // options
   int32_t swap_path = PIE_SWAP_AUTO;
-  int32_t attn_partition = 1024;  // tokens per workgroup
+  int32_t attn_partition = 512;   // tokens per work item (one workgroup)
   bool attn_nontemporal = true;   // non-temporal K/V loads in the attention kernel
   int32_t swap_wgs = 64;          // workgroups of the gather / scatter kernel
   bool timing = false;
@@ -135,9 +137,13 @@ int launch_swap_copy(char* dst_layer_base, const char* src_layer_base, size_t bl
                      int n_wgs, hipStream_t s);
 int launch_kv_append(const pie_pool* p, int32_t layer, const void* d_k, const void* d_v, const int32_t* d_table,
                      int32_t max_blocks, const int32_t* d_ctx, int32_t batch, bool stage_valid, hipStream_t s);
-int launch_attn_decode(const pie_pool* p, int32_t layer, const void* d_q, const int32_t* d_table, int32_t max_blocks,
-                       const int32_t* d_ctx, int32_t batch, void* d_out, bool stage_valid, hipStream_t s,
-                       hipEvent_t k_start = nullptr, hipEvent_t k_end = nullptr);
+int launch_attn_plan(const pie_pool* p, const int32_t* d_ctx, int32_t batch, int32_t max_blocks, hipStream_t s);
+int launch_attn_resolve(const pie_pool* p, const int32_t* d_table, const int32_t* d_ctx, int32_t batch,
+                        int32_t max_blocks, bool region0, bool valid0, bool region1, bool valid1, hipStream_t s);
+int launch_attn_decode(const pie_pool* p, int32_t layer, const void* d_q, int32_t max_blocks, const int32_t* d_ctx,
+                       int32_t batch, void* d_out, hipStream_t s, hipEvent_t k_start = nullptr,
+                       hipEvent_t k_end = nullptr);
+size_t attn_plan_ints(const pie_config& c);
 size_t attn_workspace_floats(const pie_config& c);
 bool attn_config_supported(const pie_config& c);
 

@@ -41,7 +41,7 @@ static bool config_ok(const pie_config* c) {
 
 struct Layout {
   size_t block_bytes, d_layer_stride, h_layer_stride;
-  size_t off_map0, off_map1, off_ws, off_err, d_total, h_total;
+  size_t off_map0, off_map1, off_ws, off_plan, off_err, d_total, h_total;
   size_t ws_floats;
 };
 
@@ -57,6 +57,7 @@ static Layout layout_of(const pie_config& c) {
   l.off_map1 = off; off = align_up(off + n_handles * 4, kAlign);
   l.ws_floats = attn_workspace_floats(c);
   l.off_ws = off; off = align_up(off + l.ws_floats * 4, kAlign);
+  l.off_plan = off; off = align_up(off + attn_plan_ints(c) * 4, kAlign);
   l.off_err = off; off += kAlign;
   l.d_total = off;
   l.h_total = l.h_layer_stride * c.n_layers;
@@ -190,6 +191,23 @@ static int wait_if(hipStream_t s, hipEvent_t ev, bool recorded) {
 
 // ---- internals of the public swap / compute calls (also used by pie_step) ------------------------------
 
+// Phase one of a swap-in: publish where the copies of the listed blocks will be (staging slot = rank).
+static void publish_stage_list(pie_pool* p, int r, int32_t n, const int32_t* handles) {
+  bool same = (int32_t)p->stage_list[r].size() == n;
+  for (int32_t i = 0; same && i < n; ++i) same = p->stage_list[r][i] == handles[i];
+  if (same) return;
+  for (int32_t h : p->stage_list[r])
+    if (h >= 0) {
+      p->stage_rank[r][h] = -1;
+      map_set(p, r, h, -1);
+    }
+  p->stage_list[r].assign(handles, handles + n);
+  for (int32_t i = 0; i < n; ++i) {
+    p->stage_rank[r][handles[i]] = i;
+    map_set(p, r, handles[i], stage_slot(p, r, i));
+  }
+}
+
 static int swap_in_impl(pie_pool* p, int32_t layer, int32_t n, const int32_t* handles, hipStream_t s,
                         bool validated, hipEvent_t t0, hipEvent_t t1) {
   const int r = layer & 1;
@@ -203,21 +221,7 @@ static int swap_in_impl(pie_pool* p, int32_t layer, int32_t n, const int32_t* ha
   }
   if (!p->device) return PIE_ESTATE;
   note_stream(p, s);
-  // phase one: publish where the copies will be
-  bool same = (int32_t)p->stage_list[r].size() == n;
-  for (int32_t i = 0; same && i < n; ++i) same = p->stage_list[r][i] == handles[i];
-  if (!same) {
-    for (int32_t h : p->stage_list[r])
-      if (h >= 0) {
-        p->stage_rank[r][h] = -1;
-        map_set(p, r, h, -1);
-      }
-    p->stage_list[r].assign(handles, handles + n);
-    for (int32_t i = 0; i < n; ++i) {
-      p->stage_rank[r][handles[i]] = i;
-      map_set(p, r, handles[i], stage_slot(p, r, i));
-    }
-  }
+  publish_stage_list(p, r, n, handles);
   p->region_layer[r] = layer;
   // the region may still be read by compute or written back
   int rc;
@@ -357,8 +361,17 @@ int pie_pool_init(const pie_config* cfg, void* d_base, size_t d_bytes, void* h_p
     p->d_map[1] = (int32_t*)(base + l.off_map1);
     p->d_ws = (float*)(base + l.off_ws);
     p->ws_floats = l.ws_floats;
+    p->d_plan = (int32_t*)(base + l.off_plan);
     p->d_err = (uint32_t*)(base + l.off_err);
     int rc = PIE_OK;
+    {
+      int dev = 0, n_cu = 0;
+      if (hipGetDevice(&dev) == hipSuccess &&
+          hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n_cu > 0)
+        p->n_cu = n_cu;
+      else
+        (void)hipGetLastError();
+    }
     auto fail = [&](int code) { pie_pool_destroy(p); return code; };
     if (cfg->n_host_blocks > 0) {
       void* dev_ptr = nullptr;
@@ -642,8 +655,12 @@ int pie_attn_decode(pie_pool* p, int32_t layer, const void* d_q, const int32_t* 
   hipStream_t s = (hipStream_t)stream;
   bool stage_valid = false;
   if ((rc = compute_prologue(p, layer, s, &stage_valid))) return rc;
-  if ((rc = launch_attn_decode(p, layer, d_q, d_block_table, max_blocks, d_ctx_lens, batch, d_out, stage_valid, s)))
+  const int r = layer & 1;
+  if ((rc = launch_attn_plan(p, d_ctx_lens, batch, max_blocks, s))) return rc;
+  if ((rc = launch_attn_resolve(p, d_block_table, d_ctx_lens, batch, max_blocks, r == 0, stage_valid, r == 1,
+                                stage_valid, s)))
     return rc;
+  if ((rc = launch_attn_decode(p, layer, d_q, max_blocks, d_ctx_lens, batch, d_out, s))) return rc;
   return compute_epilogue(p, layer, s);
 }
 
@@ -712,6 +729,15 @@ int pie_step(pie_pool* p, const void* d_q_all, const void* d_k_new, const void* 
     PIE_HIP(hipEventRecord(p->ev_step_start, cs));
     for (auto& le : p->lev) le.in_used = le.out_used = false;
   }
+  // The prefetch list is the same for every layer, so both staging regions' slot assignments are known now:
+  // publish them, send the map changes, and plan the attention work once for the whole step.
+  publish_stage_list(p, 0, n_prefetch, h_prefetch);
+  if (L > 1) publish_stage_list(p, 1, n_prefetch, h_prefetch);
+  if ((rc = wait_if(cs, p->ev_migrate, p->ev_migrate_rec))) return rc;
+  if ((rc = flush_map(p, cs))) return rc;
+  if ((rc = launch_attn_plan(p, d_ctx_lens, batch, max_blocks, cs))) return rc;
+  if ((rc = launch_attn_resolve(p, d_block_table, d_ctx_lens, batch, max_blocks, true, true, L > 1, true, cs)))
+    return rc;
   // layer 0's blocks have no earlier layer to hide behind
   if (n_prefetch > 0) {
     if ((rc = swap_in_impl(p, 0, n_prefetch, h_prefetch, is, true, timed ? p->lev[0].in_start : nullptr,
@@ -735,9 +761,9 @@ int pie_step(pie_pool* p, const void* d_q_all, const void* d_k_new, const void* 
                                  d_block_table, max_blocks, d_ctx_lens, batch, stage_valid, cs)))
         return rc;
     }
-    if ((rc = launch_attn_decode(p, l, (const char*)d_q_all + l * q_stride, d_block_table, max_blocks, d_ctx_lens,
-                                 batch, (char*)d_out_all + l * q_stride, stage_valid, cs,
-                                 timed ? p->lev[l].k_start : nullptr, timed ? p->lev[l].k_end : nullptr)))
+    if ((rc = launch_attn_decode(p, l, (const char*)d_q_all + l * q_stride, max_blocks, d_ctx_lens, batch,
+                                 (char*)d_out_all + l * q_stride, cs, timed ? p->lev[l].k_start : nullptr,
+                                 timed ? p->lev[l].k_end : nullptr)))
       return rc;
     if (timed) PIE_HIP(hipEventRecord(p->lev[l].attn_end, cs));
     if ((rc = compute_epilogue(p, l, cs))) return rc;
