@@ -111,10 +111,9 @@ def cpu_baseline(dw, n_seqs, n_layers):
     where, slots = dw.pool.block_where(dw.table[:n_seqs][dw.table[:n_seqs] >= 0])
     assert all(x == 0 for x in where)
     src = torch.as_tensor(np.asarray(slots, dtype=np.int64), device=dw.q.device)
-    sd = mod.gpu.dtype
     for l in range(n_layers):
         blocks = dw.pool.gpu_image()[l].index_select(0, src).cpu().numpy()       # [total][block_bytes]
-        mod.gpu[l, :total] = blocks.view(sd).reshape((total,) + mod.gpu.shape[2:])
+        mod.gpu[l, :total] = mod.blocks_from_bytes(blocks)
     i = 0
     for b in range(n_seqs):
         for j in range(int(nb[b])):

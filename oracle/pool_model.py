@@ -10,8 +10,10 @@ a block rather than a whole layer: a logical block is homed either in the GPU
 pool or in the host pool, in the same slot of every layer.
 
 The model is synchronous: a swap has completed when the call returns, so the
-two-phase states collapse.  It keeps byte images of both pools so that the GPU
-library's pool contents can be compared bit for bit.
+two-phase states collapse.  It keeps images of both pools, blocks in the logical
+order [K|V][head][token][dim]; gpu_bytes / host_bytes give them in the physical
+order the C ABI documents (oracle.layout), so that the GPU library's pool
+contents can be compared bit for bit.
 
 TEST INFRASTRUCTURE ONLY - never imported by the product path.
 """
@@ -19,7 +21,7 @@ from __future__ import annotations
 
 import numpy as np
 
-from . import numfmt
+from . import layout, numfmt
 from .attention import paged_attention_decode
 
 EINVAL, ENOMEM, ESTATE = -1, -2, -3
@@ -55,6 +57,19 @@ class PoolModel:
         self.stage_of = [dict(), dict()]     # region -> {handle: rank}
         self.region_layer = [-1, -1]         # which layer's data a region holds
         self.dirty = [set(), set()]          # staged handles written since they were brought in
+
+    # ---- byte images in the ABI's physical block order ---------------------
+    def gpu_bytes(self):
+        """uint8 [L][n_gpu + 2 n_stage][block_bytes]."""
+        return layout.to_physical(self.gpu).view(np.uint8)
+
+    def host_bytes(self):
+        """uint8 [L][n_host][block_bytes]."""
+        return layout.to_physical(self.host).view(np.uint8)
+
+    def blocks_from_bytes(self, raw):
+        """uint8 [..., block_bytes] in physical order -> storage dtype [..., 2, Hkv, T, d]."""
+        return layout.from_physical(np.ascontiguousarray(raw).view(self.gpu.dtype), self.Hkv, self.T, self.d)
 
     # ---- allocator -------------------------------------------------------
     def block_alloc(self, where, n):

@@ -49,12 +49,9 @@ def make_pools(case, n_gpu, n_stage, n_host, order_seed=0, upto_ctx=None, fill=N
 
 def load_images(lib, mod):
     """Copy the model's pool images (staging included) into the library's pools."""
-    L = mod.L
-    gi = torch.from_numpy(mod.gpu.reshape(L, mod.gpu.shape[1], -1).view(np.uint8).copy())
-    lib.gpu_image().copy_(gi.to(DEV))
+    lib.gpu_image().copy_(torch.from_numpy(mod.gpu_bytes().copy()).to(DEV))
     if mod.n_host:
-        hi = torch.from_numpy(mod.host.reshape(L, mod.n_host, -1).view(np.uint8).copy())
-        lib.host_image().copy_(hi)
+        lib.host_image().copy_(torch.from_numpy(mod.host_bytes().copy()))
     torch.cuda.synchronize()
 
 
@@ -66,8 +63,8 @@ def images_of(lib):
 
 
 def model_bytes(mod):
-    L = mod.L
-    return (mod.gpu.reshape(L, mod.gpu.shape[1], -1).view(np.uint8), mod.host.reshape(L, mod.n_host, -1).view(np.uint8))
+    """The model's pool images in the ABI's physical block order."""
+    return mod.gpu_bytes(), mod.host_bytes()
 
 
 def rowwise_rel_err(got: np.ndarray, ref: np.ndarray) -> float:
