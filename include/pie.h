@@ -27,10 +27,20 @@
  *     allocates no device memory at any time.
  *   - One pool is driven by one host thread; attention / append calls of one
  *     pool go to one compute stream at a time.
- *   - Block layout (both pools): [layer][slot][K|V][kv_head][token][head_dim],
- *     row-major, element type as in pie_config.dtype.  In the device buffer a
+ *   - Pool layout (both pools): [layer][slot][block]; in the device buffer a
  *     layer holds n_gpu_blocks resident slots, then staging region 0, then
- *     staging region 1 (n_stage_blocks each).
+ *     staging region 1 (n_stage_blocks each).  A block is one contiguous chunk
+ *     of 2 * n_kv_heads * 16 * head_dim elements: the K tiles of kv heads
+ *     0..n_kv_heads-1, then their V tiles, each tile 16 tokens x head_dim.
+ *     Inside a tile the elements are ordered for 16-byte vector access.  With
+ *     v = 16 / sizeof(element) and w = v / 4, element (token t, dim c) sits at
+ *       K tile:  (c / v) * (16 * v) + t * v + c % v
+ *       V tile:  (((c / (16 * w)) * 4 + t / 4) * 16 + c % 16) * v
+ *                + ((c / 16) % w) * 4 + t % 4
+ *     (a K vector = v consecutive dims of one token, the 16 tokens' vectors of
+ *     those dims adjacent; a V vector = 4 consecutive tokens of one dim and,
+ *     for 16-bit types, of the dim 16 further).  pie_kv_append writes rows in
+ *     this order; callers that fill blocks through pie_block_address must too.
  *   - Handles are int32 in [0, n_gpu_blocks + n_host_blocks); -1 marks an
  *     unused block-table entry.
  */
@@ -68,7 +78,7 @@ typedef struct pie_controller pie_controller;
 typedef struct {
   int32_t n_layers;
   int32_t n_q_heads;
-  int32_t n_kv_heads;        /* divides n_q_heads */
+  int32_t n_kv_heads;        /* divides n_q_heads; 16-bit dtypes: n_q_heads / n_kv_heads <= 16 */
   int32_t head_dim;          /* 64 or 128 */
   int32_t block_tokens;      /* 16 */
   int32_t dtype;             /* PIE_DTYPE_* */

@@ -6,9 +6,10 @@
 // per-layer access pattern of Section 3.2:
 //   out[b][h] = sum_t softmax_t(scale * <q[b][h], K[b][g][t]>) V[b][g][t],   t < ctx_b,  g = h / (Hq/Hkv).
 //
-// Data layout of one block (one layer): [K|V][kv_head][token][head_dim]; one (block, head) K or V tile is
-// block_tokens * head_dim contiguous elements.  The decode is bound by HBM bandwidth: every KV byte of the
-// layer is read exactly once, with 16-byte loads per lane that cover a tile in contiguous 1 KiB pieces.
+// One block of one layer holds the K tiles of the kv heads, then their V tiles; inside a tile the elements are
+// ordered so that a 16-byte lane vector is a matrix-core operand as loaded (see "element types and the layout
+// of a block" below).  The decode is bound by HBM bandwidth: every KV byte of the layer is read exactly once,
+// with 16-byte loads per lane that cover a tile in contiguous 1 KiB pieces.
 
 #include <hip/hip_bf16.h>
 #include <hip/hip_fp16.h>
@@ -105,14 +106,30 @@ int launch_swap_copy(char* dst_layer_base, const char* src_layer_base, size_t bl
 }
 
 // ---------------------------------------------------------------------------------------------------
-// element types
+// element types and the layout of a block
+//
+// A block is [K tiles of the kv heads][V tiles of the kv heads]; a tile is 16 tokens x head_dim elements.
+// With v = 16 / elem_bytes elements per 16-byte vector and w = v / 4:
+//   K tile: element (token t, dim c) at  (c / v) * (16 v) + t v + c % v
+//           -> a vector holds v consecutive dims of one token; lane i of a 64-lane load of 1 KiB gets
+//              token i % 16, dims 8 (i / 16) .. of a 4-vector-wide slab: the A operand of a 16x16x32 MFMA.
+//   V tile: element (t, c) at  (((c / (16 w)) * 4 + t / 4) * 16 + c % 16) * v + ((c / 16) % w) * 4 + t % 4
+//           -> a vector holds 4 consecutive tokens of dim c (and, 16-bit, of dim c + 16); lane i of a 1 KiB
+//              load gets tokens 4 (i / 16) .., dim i % 16 of a 16 w-dim slab: the A operand(s) of 16x16x16 MFMAs
+//              whose contraction runs over the 16 tokens of the block.
 // ---------------------------------------------------------------------------------------------------
 
-struct F32 { using T = float; };
-struct F16 { using T = uint16_t; };
-struct BF16 { using T = uint16_t; };
+struct F32 { static constexpr int kBytes = 4; };
+struct F16 { static constexpr int kBytes = 2; };
+struct BF16 { static constexpr int kBytes = 2; };
 
-__device__ __forceinline__ float bf16_bits_to_f32(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
+__host__ __device__ __forceinline__ int32_t k_tile_index(int32_t t, int32_t c, int32_t v) {
+  return (c / v) * (16 * v) + t * v + c % v;
+}
+__host__ __device__ __forceinline__ int32_t v_tile_index(int32_t t, int32_t c, int32_t v) {
+  const int32_t w = v / 4;
+  return (((c / (16 * w)) * 4 + t / 4) * 16 + c % 16) * v + ((c / 16) % w) * 4 + t % 4;
+}
 
 __device__ __forceinline__ uint16_t f32_to_bf16_bits(float x) {
   uint32_t u = __float_as_uint(x);
@@ -121,42 +138,16 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float x) {
   return (uint16_t)(u >> 16);
 }
 
-template <typename E> struct Elem;
-template <> struct Elem<F32> {
-  static constexpr int kVec = 4;  // elements in 16 bytes
-  __device__ static void unpack(const uint4& r, float* f) {
-    f[0] = __uint_as_float(r.x); f[1] = __uint_as_float(r.y); f[2] = __uint_as_float(r.z); f[3] = __uint_as_float(r.w);
-  }
-  __device__ static void store(void* base, size_t idx, float v) { reinterpret_cast<float*>(base)[idx] = v; }
-};
-template <> struct Elem<F16> {
-  static constexpr int kVec = 8;
-  __device__ static void unpack(const uint4& r, float* f) {
-    const uint32_t w[4] = {r.x, r.y, r.z, r.w};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      f[2 * i] = __half2float(__ushort_as_half((unsigned short)(w[i] & 0xffffu)));
-      f[2 * i + 1] = __half2float(__ushort_as_half((unsigned short)(w[i] >> 16)));
-    }
-  }
-  __device__ static void store(void* base, size_t idx, float v) {
-    reinterpret_cast<__half*>(base)[idx] = __float2half_rn(v);
-  }
-};
-template <> struct Elem<BF16> {
-  static constexpr int kVec = 8;
-  __device__ static void unpack(const uint4& r, float* f) {
-    const uint32_t w[4] = {r.x, r.y, r.z, r.w};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      f[2 * i] = __uint_as_float(w[i] << 16);
-      f[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
-    }
-  }
-  __device__ static void store(void* base, size_t idx, float v) {
-    reinterpret_cast<uint16_t*>(base)[idx] = f32_to_bf16_bits(v);
-  }
-};
+template <typename E> __device__ __forceinline__ void store_elem(void* base, size_t idx, float v);
+template <> __device__ __forceinline__ void store_elem<F32>(void* base, size_t idx, float v) {
+  reinterpret_cast<float*>(base)[idx] = v;
+}
+template <> __device__ __forceinline__ void store_elem<F16>(void* base, size_t idx, float v) {
+  reinterpret_cast<__half*>(base)[idx] = __float2half_rn(v);
+}
+template <> __device__ __forceinline__ void store_elem<BF16>(void* base, size_t idx, float v) {
+  reinterpret_cast<uint16_t*>(base)[idx] = f32_to_bf16_bits(v);
+}
 
 // ---------------------------------------------------------------------------------------------------
 // handle -> device slot, with the checks that keep a bad table from becoming a bad address
@@ -180,6 +171,8 @@ __device__ __forceinline__ int32_t resolve_slot(int32_t handle, const int32_t* _
 // ---------------------------------------------------------------------------------------------------
 // KV append: one workgroup per sequence copies the new token's key and value rows into its tail block
 // ---------------------------------------------------------------------------------------------------
+
+constexpr int kAppendBlockTokens = 16;
 
 struct AppendArgs {
   char* kv_layer;            // device pool base of this layer
@@ -211,18 +204,30 @@ __global__ __launch_bounds__(256) void k_kv_append(const AppendArgs a) {
   __syncthreads();
   const int32_t slot = s_slot;
   if (slot < 0) return;
-  const int32_t row_bytes = a.head_dim * a.elem_bytes;              // multiple of 16
-  const int32_t vec_per_row = row_bytes / 16;
-  const int32_t n_vec = a.n_kv_heads * vec_per_row;
+  // one 16-byte vector of a key row goes to one vector of the K tile; a value row is scattered element by
+  // element over the V tile's token-quad vectors
+  const int32_t v = 16 / a.elem_bytes;
+  const int32_t vec_per_row = a.head_dim / v;
+  const int32_t tile_bytes = kAppendBlockTokens * a.head_dim * a.elem_bytes;
   char* blk = a.kv_layer + (size_t)slot * a.block_bytes;
   const size_t v_off = a.block_bytes / 2;
-  const int32_t t = pos % a.block_tokens;
+  const int32_t t = pos % kAppendBlockTokens;
+  const int32_t n_vec = a.n_kv_heads * vec_per_row;
   for (int32_t i = threadIdx.x; i < n_vec; i += blockDim.x) {
-    const int32_t g = i / vec_per_row, c = i % vec_per_row;
-    const size_t src = ((size_t)b * a.n_kv_heads + g) * row_bytes + (size_t)c * 16;
-    const size_t dst = ((size_t)g * a.block_tokens + t) * row_bytes + (size_t)c * 16;
+    const int32_t g = i / vec_per_row, cv = i % vec_per_row;
+    const size_t src = ((size_t)b * a.n_kv_heads + g) * a.head_dim * a.elem_bytes + (size_t)cv * 16;
+    const size_t dst = (size_t)g * tile_bytes + (size_t)k_tile_index(t, cv * v, v) * a.elem_bytes;
     *reinterpret_cast<uint4*>(blk + dst) = *reinterpret_cast<const uint4*>(a.k_new + src);
-    *reinterpret_cast<uint4*>(blk + v_off + dst) = *reinterpret_cast<const uint4*>(a.v_new + src);
+  }
+  const int32_t n_el = a.n_kv_heads * a.head_dim;
+  for (int32_t i = threadIdx.x; i < n_el; i += blockDim.x) {
+    const int32_t g = i / a.head_dim, c = i % a.head_dim;
+    const size_t src = ((size_t)b * a.n_kv_heads + g) * a.head_dim + c;
+    const size_t dst = v_off + (size_t)g * tile_bytes + (size_t)v_tile_index(t, c, v) * a.elem_bytes;
+    if (a.elem_bytes == 2)
+      *reinterpret_cast<uint16_t*>(blk + dst) = reinterpret_cast<const uint16_t*>(a.v_new)[src];
+    else
+      *reinterpret_cast<uint32_t*>(blk + dst) = reinterpret_cast<const uint32_t*>(a.v_new)[src];
   }
 }
 
@@ -257,22 +262,31 @@ int launch_kv_append(const pie_pool* p, int32_t layer, const void* d_k, const vo
 //
 // Work is cut into items: `part_tokens` consecutive tokens of one sequence.  A small planning kernel lists
 // the non-empty items, full ones first and the sequences' shorter last pieces after them in descending
-// size, and a resolve kernel turns the block table (handles) into device slots once per step.  The decode
-// kernel is persistent: about as many workgroups as the GPU can hold resident, each taking (item, kv head)
-// units from an atomic ticket counter until none are left.  That evens out the 8 XCDs (which do not stream
-// at the same rate), leaves only small units for the end of the launch, and pays the launch ramp once.
+// size, and a resolve kernel turns the block table (handles) into device slots once per step.
 //
-// A workgroup of kWaves wavefronts handles one unit and all G query heads that share the kv head.  Wave w
-// takes blocks w, w + kWaves, ... of the item.  A tile (16 tokens x head_dim) is read with NLD loads of 16
-// bytes per lane: LPR lanes cover one token row, so a wave-wide load covers TPL = 64 / LPR consecutive tokens
-// = 1 KiB contiguous.  Lane (rg, c) = (lane / LPR, lane % LPR) owns head dims [c*VEC, (c+1)*VEC) of tokens
-// rg, rg + TPL, ...  Loads are non-temporal (every KV byte is read once) and double-buffered in registers.
+// 16-bit caches (fp16 / bf16): k_attn_decode_mfma.  The kernel is persistent: about as many workgroups as
+// the GPU can hold resident, each taking (item, kv head) units from an atomic ticket counter until none are
+// left.  That evens out the 8 XCDs (which do not stream at the same rate), leaves only small units for the
+// end of the launch, and pays the launch ramp once.  A workgroup of kWaves wavefronts handles one unit and
+// all G <= 16 query heads that share the kv head; wave w takes blocks w, w + kWaves, ... of the item.
+// Per block a wave issues head_dim/32 K loads and head_dim/32 V loads of 16 bytes per lane, each covering
+// 1 KiB contiguous, non-temporal (every KV byte is read once), double-buffered in registers.  The loaded
+// vectors are matrix-core operands as they are:
+//   S[token][head]  = sum_c K[token][c] Q[head][c]      head_dim/32 x  v_mfma_f32_16x16x32   (A = K, B = Q)
+//   O[dim][head]   += sum_t V[t][dim] P[t][head]        head_dim/16 x  v_mfma_f32_16x16x16   (A = V, B = P)
+// The 16 columns are the query heads of the group (columns >= G carry zeros); for G = 1 the products are
+// matrix-vector and most of the matrix core idles, which costs nothing: the kernel is bound by HBM, and what
+// the matrix core buys is that no vector-ALU work is spent on unpacking and multiplying the 16-bit elements.
+// The accumulator layout of S (lane = 16 (token / 4) + head, register = token % 4) is the B-operand layout
+// of the 16x16x16 form, so P goes from the softmax into the second product without leaving its lane.
+// The softmax is online, in the log2 domain, with one running maximum per head shared by the wave (two
+// cross-lane swaps per block); the accumulators are rescaled only when some maximum moved.  P is rounded
+// to the cache's 16-bit type for the second product; for bf16 the rounding residue goes through a second
+// MFMA so that P carries 16 significant bits.  At the end the kWaves partial states merge through LDS and
+// are written out (single partition) or stored as (m, l, acc) for the reduction kernel.
 //
-// Each of the TPL row groups runs its own online softmax (running max m, sum l, accumulator acc) over the
-// tokens it owns, in the log2 domain (scores are pre-multiplied by scale*log2(e)).  The only cross-lane
-// traffic in the loop is the sum of the partial dot products over the LPR lanes of a row.  At the end the
-// kWaves*TPL partial states are merged through LDS, then either written out (single partition) or stored
-// as (m, l, acc) for the reduction kernel.
+// fp32 caches: k_attn_decode_f32, a plain vector-ALU kernel over the same items, one workgroup per
+// (item, query head).  It exists for the fp32 parity configuration, which is latency-bound.
 // ---------------------------------------------------------------------------------------------------
 
 constexpr int kWaves = 4;
@@ -280,23 +294,84 @@ constexpr int kBlockTokens = 16;
 constexpr int kMinPartTokens = 256;
 constexpr int kMaxPlanBatch = 4096;   // sequences the planning kernel keeps in LDS
 constexpr int kPlanHdrInts = 16;
+constexpr int kMaxGroup = 16;         // query heads per kv head the MFMA kernel handles (its 16 columns)
 constexpr float kNegBig = -1.0e30f;   // finite stand-in for -inf as the initial running max
 
-template <int CTRL>
-__device__ __forceinline__ float dpp_add(float x) {
-  const int y = __builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false);
-  return x + __int_as_float(y);
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+
+template <typename TO, typename FROM>
+__device__ __forceinline__ TO bits_as(const FROM& x) {
+  static_assert(sizeof(TO) == sizeof(FROM), "size mismatch");
+  TO y;
+  __builtin_memcpy(&y, &x, sizeof(TO));
+  return y;
 }
 
-// Sum over the LPR consecutive lanes of a row; every lane of the row gets the total.
-template <int LPR>
-__device__ __forceinline__ float row_sum(float x) {
-  x = dpp_add<0xB1>(x);                      // quad_perm [1,0,3,2]: lane ^ 1
-  x = dpp_add<0x4E>(x);                      // quad_perm [2,3,0,1]: lane ^ 2
-  if (LPR >= 8) x = dpp_add<0x141>(x);       // row_half_mirror: the other quad of the 8
-  if (LPR >= 16) x = dpp_add<0x140>(x);      // row_mirror: the other half of the 16
-  if (LPR >= 32) x += __shfl_xor(x, 16, 64);
-  if (LPR >= 64) x += __shfl_xor(x, 32, 64);
+template <typename E> struct Mfma;
+template <> struct Mfma<F16> {
+  __device__ static f32x4 qk(const uint4& a, const uint4& b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(bits_as<f16x8>(a), bits_as<f16x8>(b), c, 0, 0, 0);
+  }
+  __device__ static f32x4 pv(const uint2& a, const uint2& b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x16f16(bits_as<f16x4>(a), bits_as<f16x4>(b), c, 0, 0, 0);
+  }
+  __device__ static uint2 round(const f32x4& p) { return bits_as<uint2>(__builtin_convertvector(p, f16x4)); }
+  __device__ static f32x4 widen(const uint2& r) { return __builtin_convertvector(bits_as<f16x4>(r), f32x4); }
+};
+template <> struct Mfma<BF16> {
+  __device__ static f32x4 qk(const uint4& a, const uint4& b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(bits_as<bf16x8>(a), bits_as<bf16x8>(b), c, 0, 0, 0);
+  }
+  __device__ static f32x4 pv(const uint2& a, const uint2& b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(bits_as<s16x4>(a), bits_as<s16x4>(b), c, 0, 0, 0);
+  }
+  __device__ static uint2 round(const f32x4& p) { return bits_as<uint2>(__builtin_convertvector(p, bf16x4)); }
+  __device__ static f32x4 widen(const uint2& r) {
+    f32x4 f;
+    f[0] = __uint_as_float(r.x << 16);
+    f[1] = __uint_as_float(r.x & 0xffff0000u);
+    f[2] = __uint_as_float(r.y << 16);
+    f[3] = __uint_as_float(r.y & 0xffff0000u);
+    return f;
+  }
+};
+
+// max / sum over the four lanes i, i ^ 16, i ^ 32, i ^ 48; every lane gets the result
+__device__ __forceinline__ float quad16_max(float x) {
+  auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  x = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+  auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+__device__ __forceinline__ float quad16_sum(float x) {
+  auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  x = __uint_as_float(a[0]) + __uint_as_float(a[1]);
+  auto b = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+  return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
+// max / sum over the 16 lanes of a row (lanes 16 r .. 16 r + 15); every lane of the row gets the result
+template <int CTRL>
+__device__ __forceinline__ float dpp_get(float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, false));
+}
+__device__ __forceinline__ float row16_max(float x) {
+  x = fmaxf(x, dpp_get<0xB1>(x));    // quad_perm [1,0,3,2]: lane ^ 1
+  x = fmaxf(x, dpp_get<0x4E>(x));    // quad_perm [2,3,0,1]: lane ^ 2
+  x = fmaxf(x, dpp_get<0x141>(x));   // row_half_mirror: the other quad of the 8
+  x = fmaxf(x, dpp_get<0x140>(x));   // row_mirror: the other half of the 16
+  return x;
+}
+__device__ __forceinline__ float row16_sum(float x) {
+  x += dpp_get<0xB1>(x);
+  x += dpp_get<0x4E>(x);
+  x += dpp_get<0x141>(x);
+  x += dpp_get<0x140>(x);
   return x;
 }
 
@@ -408,32 +483,33 @@ struct AttnArgs {
   const int32_t* ctx;
   size_t block_bytes;
   float scale_log2e;
-  int32_t max_blocks, n_kv_heads, part_tokens, n_parts;
-#ifdef PIE_EXPERIMENT
-  unsigned long long* dbg;   // per-unit timestamps
-  int32_t dbg_cap;
-#endif
+  int32_t max_blocks, n_kv_heads, group, part_tokens, n_parts;
 };
 
-template <typename E, int HD, int G, bool NT>
-__global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu((G == 1 && Elem<E>::kVec == 8) ? 4 : 1, 8)))
-void k_attn_decode(const AttnArgs a) {
-  using EL = Elem<E>;
-  constexpr int VEC = EL::kVec;
-  constexpr int LPR = HD / VEC;
-  constexpr int TPL = 64 / LPR;
-  constexpr int NLD = kBlockTokens / TPL;
-  constexpr int TILE_BYTES = kBlockTokens * HD * (16 / VEC);
-  constexpr int NP = kWaves * TPL;
-  constexpr int EB = 16 / VEC;                 // bytes per element
-  static_assert(LPR >= 4 && LPR <= 64 && NLD >= 1, "unsupported head_dim / dtype");
+// LDS floats the MFMA kernel needs for `group` query heads per kv head
+template <int HD>
+constexpr size_t mfma_lds_floats(int group) {
+  return (size_t)kWaves * 2 * kMaxGroup + (size_t)kWaves * group * (HD + 4);
+}
 
+template <typename E, int HD, bool SPLIT>
+__global__ __launch_bounds__(kWaves * 64) void k_attn_decode_mfma(const AttnArgs a) {
+  using MM = Mfma<E>;
+  constexpr int NKC = HD / 32;                    // 1 KiB loads per K tile and per V tile; QK MFMAs per block
+  constexpr int NO = HD / 16;                     // output accumulators (16 dims x 16 heads each)
+  constexpr int TILE_BYTES = kBlockTokens * HD * 2;
+  constexpr int ROW = HD + 4;                     // padded LDS row of one head's accumulator
+  static_assert(HD % 32 == 0, "unsupported head_dim");
+
+  extern __shared__ __align__(16) float s_dyn[];
   __shared__ uint32_t s_ticket;
-  __shared__ float s_m[NP], s_l[NP];
-  __shared__ float s_acc[NP][HD];
+  float* s_m = s_dyn;                             // [kWaves][16]
+  float* s_l = s_dyn + kWaves * kMaxGroup;        // [kWaves][16]
+  float* s_acc = s_dyn + 2 * kWaves * kMaxGroup;  // [kWaves][G][ROW]
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int rg = lane / LPR, c = lane % LPR;
+  const int col = lane & 15, quad = lane >> 4;    // MFMA column (query head of the group) and 4-row group
+  const int32_t G = a.group;
   const int32_t n_q_heads = a.n_kv_heads * G;
   const uint32_t n_kv = (uint32_t)a.n_kv_heads;
   const uint32_t n_units = (uint32_t)a.hdr[0] * n_kv;
@@ -448,25 +524,29 @@ void k_attn_decode(const AttnArgs a) {
   uint32_t unit = blockIdx.x;
   uint32_t next = gridDim.x + blockIdx.x;
 
+  // this lane's part of the B operand of the first product: head `col` of the group, dims 32 kc + 8 quad ..
+  auto load_q = [&](uint4 (&qr)[NKC], int32_t b, int32_t g) {
+#pragma unroll
+    for (int kc = 0; kc < NKC; ++kc) {
+      qr[kc] = make_uint4(0, 0, 0, 0);
+      if (col < G)
+        qr[kc] = *reinterpret_cast<const uint4*>(a.q + (((size_t)b * n_q_heads + g * G + col) * HD + 32 * kc + 8 * quad) * 2);
+    }
+  };
+
   uint2 rec = make_uint2(0, 0);
   int32_t my_slot = -1;
-  uint4 qraw[G];
+  uint4 qreg[NKC];
   if (unit < n_units) {
     const uint32_t item = unit / n_kv;
     rec = a.items[item];
     if (lane < my_n) my_slot = a.slots[(size_t)item * bpi + wave + kWaves * lane];
-    const int32_t b0 = (int32_t)(rec.x & 0xffffu), g0 = (int32_t)(unit % n_kv);
-#pragma unroll
-    for (int h = 0; h < G; ++h)
-      qraw[h] = *reinterpret_cast<const uint4*>(a.q + (((size_t)b0 * n_q_heads + g0 * G + h) * HD + c * VEC) * EB);
+    load_q(qreg, (int32_t)(rec.x & 0xffffu), (int32_t)(unit % n_kv));
   }
 
   while (unit < n_units) {                       // every workgroup ends on a ticket past the last unit
     uint2 rec_next = make_uint2(0, 0);
     if (next < n_units) rec_next = a.items[next / n_kv];          // consumed after the stream loop
-#ifdef PIE_EXPERIMENT
-    const unsigned long long t_entry = wall_clock64();
-#endif
     const int32_t g = (int32_t)(unit % n_kv);
     const int32_t b = (int32_t)(rec.x & 0xffffu), part = (int32_t)(rec.x >> 16);
     const int32_t tok0 = part * a.part_tokens;
@@ -478,100 +558,85 @@ void k_attn_decode(const AttnArgs a) {
     const int32_t jb1 = tok1 > 0 ? (tok1 + kBlockTokens - 1) / kBlockTokens : 0;   // exclusive, <= max_blocks
     const int32_t n_it = (jb1 - jb0 - wave + kWaves - 1) / kWaves;  // <= my_n <= 64; <= 0 when nothing to do
 
-    // query rows of the G heads, this lane's VEC dims, as fp32 pre-multiplied by scale*log2(e)
-    float q[G][VEC];
+    float m = kNegBig, l = 0.f;                   // running max of head `col`; this lane's share of the sum
+    f32x4 o[NO];
 #pragma unroll
-    for (int h = 0; h < G; ++h) {
-      EL::unpack(qraw[h], q[h]);
-#pragma unroll
-      for (int v = 0; v < VEC; ++v) q[h][v] *= a.scale_log2e;
-    }
+    for (int n = 0; n < NO; ++n) o[n] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    float m[G], l[G], acc[G][VEC];
-#pragma unroll
-    for (int h = 0; h < G; ++h) {
-      m[h] = kNegBig;
-      l[h] = 0.f;
-#pragma unroll
-      for (int v = 0; v < VEC; ++v) acc[h][v] = 0.f;
-    }
+    const size_t head_off = (size_t)g * TILE_BYTES + (size_t)lane * 16;
 
-    const size_t head_off = (size_t)g * TILE_BYTES;
-
-    // Two register sets: while one tile is consumed the next is already in flight (8 KiB per wave).
-    uint4 kA[NLD], vA[NLD], kB[NLD], vB[NLD];
-    auto load_tile = [&](uint4 (&kr)[NLD], uint4 (&vr)[NLD], int32_t it) {
+    // Two register sets: while one block is consumed the next is already in flight.
+    uint4 kA[NKC], vA[NKC], kB[NKC], vB[NKC];
+    auto load_tile = [&](uint4 (&kr)[NKC], uint4 (&vr)[NKC], int32_t it) {
       int32_t slot = __shfl(my_slot, it, 64);
       slot = slot < 0 ? 0 : slot;                                    // flagged blocks are masked below
-      const char* kp = a.kv_layer + (size_t)slot * a.block_bytes + head_off + (size_t)lane * 16;
+      const char* kp = a.kv_layer + (size_t)slot * a.block_bytes + head_off;
 #pragma unroll
-      for (int i = 0; i < NLD; ++i) kr[i] = NT ? nt_load16(kp + (size_t)i * 1024)
-                                               : *reinterpret_cast<const uint4*>(kp + (size_t)i * 1024);
+      for (int i = 0; i < NKC; ++i) kr[i] = nt_load16(kp + (size_t)i * 1024);
 #pragma unroll
-      for (int i = 0; i < NLD; ++i) vr[i] = NT ? nt_load16(kp + v_off + (size_t)i * 1024)
-                                               : *reinterpret_cast<const uint4*>(kp + v_off + (size_t)i * 1024);
+      for (int i = 0; i < NKC; ++i) vr[i] = nt_load16(kp + v_off + (size_t)i * 1024);
     };
-    auto consume = [&](uint4 (&kr)[NLD], uint4 (&vr)[NLD], int32_t it) {
-      const int32_t t_base = (jb0 + wave + kWaves * it) * kBlockTokens + rg;   // token of load 0
+    auto consume = [&](uint4 (&kr)[NKC], uint4 (&vr)[NKC], int32_t it) {
+      const int32_t t_first = (jb0 + wave + kWaves * it) * kBlockTokens;      // first token of the block
       const bool present = __shfl(my_slot, it, 64) >= 0;
       const int32_t limit = present ? tok1 : 0;                               // a missing block contributes nothing
-      const bool tail = t_base - rg + kBlockTokens > limit;
 
-      float s[G][NLD];
+      f32x4 s = {0.f, 0.f, 0.f, 0.f};             // s[r]: token t_first + 4 quad + r, head col
 #pragma unroll
-      for (int i = 0; i < NLD; ++i) {
-        float kf[VEC];
-        EL::unpack(kr[i], kf);
+      for (int kc = 0; kc < NKC; ++kc) s = MM::qk(kr[kc], qreg[kc], s);
 #pragma unroll
-        for (int h = 0; h < G; ++h) {
-          float d = 0.f;
+      for (int r = 0; r < 4; ++r) s[r] *= a.scale_log2e;
+      if (t_first + kBlockTokens > limit) {       // the block holds rows beyond the context
+        const int32_t t_lane = t_first + 4 * quad;
+        uint32_t keep_lo = 0, keep_hi = 0;        // 16-bit masks of tokens (0, 1) and (2, 3) of this lane's quad
 #pragma unroll
-          for (int v = 0; v < VEC; ++v) d = fmaf(q[h][v], kf[v], d);
-          s[h][i] = row_sum<LPR>(d);
+        for (int r = 0; r < 4; ++r) {
+          const bool valid = t_lane + r < limit;
+          s[r] = valid ? s[r] : -INFINITY;
+          const uint32_t bits = valid ? (0xffffu << (16 * (r & 1))) : 0u;
+          if (r < 2) keep_lo |= bits; else keep_hi |= bits;
+        }
+#pragma unroll
+        for (int i = 0; i < NKC; ++i) {           // garbage rows must not reach the sum
+          vr[i].x &= keep_lo; vr[i].y &= keep_hi; vr[i].z &= keep_lo; vr[i].w &= keep_hi;
         }
       }
-      if (tail) {
+      const float mx = quad16_max(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])));
+      const float m_new = fmaxf(m, mx);
+      if (__builtin_amdgcn_ballot_w64(m_new > m) != 0) {              // some head's maximum moved: rescale
+        const float corr = __builtin_amdgcn_exp2f(m - m_new);
+        l *= corr;
 #pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-          const bool valid = t_base + i * TPL < limit;
+        for (int n = 0; n < NO; ++n)
 #pragma unroll
-          for (int h = 0; h < G; ++h) s[h][i] = valid ? s[h][i] : -INFINITY;
-          if (!valid) vr[i] = make_uint4(0, 0, 0, 0);                // garbage rows must not reach the sum
-        }
+          for (int r = 0; r < 4; ++r) o[n][r] *= corr;
+        m = m_new;
       }
-      float p[G][NLD];
+      f32x4 p;
 #pragma unroll
-      for (int h = 0; h < G; ++h) {
-        float mx = s[h][0];
+      for (int r = 0; r < 4; ++r) p[r] = __builtin_amdgcn_exp2f(s[r] - m);
+      l += (p[0] + p[1]) + (p[2] + p[3]);
+      const uint2 p_hi = MM::round(p);
+      uint2 p_lo = make_uint2(0, 0);
+      if (SPLIT) {
+        const f32x4 back = MM::widen(p_hi);
+        f32x4 rest;
 #pragma unroll
-        for (int i = 1; i < NLD; ++i) mx = fmaxf(mx, s[h][i]);
-        const float m_new = fmaxf(m[h], mx);
-        const float corr = __builtin_amdgcn_exp2f(m[h] - m_new);
-        float ps = 0.f;
-#pragma unroll
-        for (int i = 0; i < NLD; ++i) {
-          p[h][i] = __builtin_amdgcn_exp2f(s[h][i] - m_new);
-          ps += p[h][i];
-        }
-        l[h] = l[h] * corr + ps;
-        m[h] = m_new;
-#pragma unroll
-        for (int v = 0; v < VEC; ++v) acc[h][v] *= corr;
+        for (int r = 0; r < 4; ++r) rest[r] = p[r] - back[r];
+        p_lo = MM::round(rest);
       }
 #pragma unroll
-      for (int i = 0; i < NLD; ++i) {
-        float vf[VEC];
-        EL::unpack(vr[i], vf);
-#pragma unroll
-        for (int h = 0; h < G; ++h)
-#pragma unroll
-          for (int v = 0; v < VEC; ++v) acc[h][v] = fmaf(p[h][i], vf[v], acc[h][v]);
+      for (int i = 0; i < NKC; ++i) {
+        const uint2 v0 = make_uint2(vr[i].x, vr[i].y), v1 = make_uint2(vr[i].z, vr[i].w);
+        o[2 * i] = MM::pv(v0, p_hi, o[2 * i]);
+        o[2 * i + 1] = MM::pv(v1, p_hi, o[2 * i + 1]);
+        if (SPLIT) {
+          o[2 * i] = MM::pv(v0, p_lo, o[2 * i]);
+          o[2 * i + 1] = MM::pv(v1, p_lo, o[2 * i + 1]);
+        }
       }
     };
 
-#ifdef PIE_EXPERIMENT
-    const unsigned long long t_pro = wall_clock64();
-#endif
     // the ticket after next is requested half way through the stream: late enough that the counter is not
     // hit by every workgroup at once, early enough that the answer is there when the unit ends
     uint32_t after_next = 0;
@@ -586,9 +651,6 @@ void k_attn_decode(const AttnArgs a) {
         consume(kB, vB, it + 1);
       }
     }
-#ifdef PIE_EXPERIMENT
-    const unsigned long long t_loop = wall_clock64();
-#endif
 
     if (n_it <= 0 && threadIdx.x == 0) after_next = 2 * gridDim.x + atomicAdd(a.counter, 1u);
     // behind the stream: the next unit's slots and query rows arrive while this unit's result is merged
@@ -596,58 +658,46 @@ void k_attn_decode(const AttnArgs a) {
     if (next < n_units) {
       const uint32_t item_n = next / n_kv;
       if (lane < my_n) my_slot_next = a.slots[(size_t)item_n * bpi + wave + kWaves * lane];
-      const int32_t bn = (int32_t)(rec_next.x & 0xffffu), gn = (int32_t)(next % n_kv);
-#pragma unroll
-      for (int h = 0; h < G; ++h)
-        qraw[h] = *reinterpret_cast<const uint4*>(a.q + (((size_t)bn * n_q_heads + gn * G + h) * HD + c * VEC) * EB);
+      load_q(qreg, (int32_t)(rec_next.x & 0xffffu), (int32_t)(next % n_kv));
     }
 
-    // merge the kWaves * TPL partial states, one query head at a time to keep LDS small
-    const int pidx = wave * TPL + rg;
-#pragma unroll
-    for (int h = 0; h < G; ++h) {
-      if (h > 0) __syncthreads();
-      if (c == 0) {
-        s_m[pidx] = m[h];
-        s_l[pidx] = l[h];
+    // merge the kWaves partial states: lane (quad, col) holds O[16 n + 4 quad + r][head col]
+    l = quad16_sum(l);
+    if (col < G) {
+      if (quad == 0) {
+        s_m[wave * kMaxGroup + col] = m;
+        s_l[wave * kMaxGroup + col] = l;
       }
+      float* row = s_acc + ((size_t)wave * G + col) * ROW + 4 * quad;
 #pragma unroll
-      for (int v = 0; v < VEC; ++v) s_acc[pidx][c * VEC + v] = acc[h][v];
-      __syncthreads();
-      for (int dim = threadIdx.x; dim < HD; dim += kWaves * 64) {
-        float M = s_m[0];
+      for (int n = 0; n < NO; ++n) *reinterpret_cast<f32x4*>(row + 16 * n) = o[n];
+    }
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < G * HD; idx += kWaves * 64) {
+      const int h = idx / HD, dim = idx % HD;
+      float M = s_m[h];
 #pragma unroll
-        for (int i = 1; i < NP; ++i) M = fmaxf(M, s_m[i]);
-        float L = 0.f, A = 0.f;
+      for (int w = 1; w < kWaves; ++w) M = fmaxf(M, s_m[w * kMaxGroup + h]);
+      float L = 0.f, A = 0.f;
 #pragma unroll
-        for (int i = 0; i < NP; ++i) {
-          const float w = __builtin_amdgcn_exp2f(s_m[i] - M);
-          L = fmaf(w, s_l[i], L);
-          A = fmaf(w, s_acc[i][dim], A);
+      for (int w = 0; w < kWaves; ++w) {
+        const float wt = __builtin_amdgcn_exp2f(s_m[w * kMaxGroup + h] - M);
+        L = fmaf(wt, s_l[w * kMaxGroup + h], L);
+        A = fmaf(wt, s_acc[((size_t)w * G + h) * ROW + dim], A);
+      }
+      const size_t orow = (size_t)b * n_q_heads + hq0 + h;
+      if (a.n_parts == 1) {
+        store_elem<E>(a.out, orow * HD + dim, L > 0.f ? A / L : 0.f);
+      } else {
+        float* w = a.ws + (orow * a.n_parts + part) * (HD + 2);
+        if (dim == 0) {
+          w[0] = M;
+          w[1] = L;
         }
-        const size_t row = (size_t)b * n_q_heads + hq0 + h;
-        if (a.n_parts == 1) {
-          EL::store(a.out, row * HD + dim, L > 0.f ? A / L : 0.f);
-        } else {
-          float* w = a.ws + (row * a.n_parts + part) * (HD + 2);
-          if (dim == 0) {
-            w[0] = M;
-            w[1] = L;
-          }
-          w[2 + dim] = A;
-        }
+        w[2 + dim] = A;
       }
     }
     if (threadIdx.x == 0) s_ticket = after_next;
-#ifdef PIE_EXPERIMENT
-    if (a.dbg && lane == 0 && (int32_t)unit < a.dbg_cap) {
-      unsigned long long* d = a.dbg + ((size_t)unit * kWaves + wave) * 6;
-      d[0] = t_entry; d[1] = t_pro; d[2] = t_loop; d[3] = wall_clock64();
-      d[4] = (unsigned long long)(n_it > 0 ? n_it : 0);
-      unsigned xcc; asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID)" : "=s"(xcc));
-      d[5] = ((unsigned long long)xcc << 32) | blockIdx.x;
-    }
-#endif
     __syncthreads();                             // merge buffers free again; the new ticket is visible
     unit = next;
     next = s_ticket;
@@ -657,10 +707,127 @@ void k_attn_decode(const AttnArgs a) {
   }
 }
 
+// fp32 caches.  One workgroup per (item, query head); wave w takes blocks w, w + kWaves, ...  Lane
+// (quad, row) = (lane / 16, lane % 16): for K it holds token `row` of the block and the 4-dim vectors
+// 4 i + quad; for V it holds dim 16 n + row and the tokens 4 quad .. 4 quad + 3.
+template <int HD>
+__global__ __launch_bounds__(kWaves * 64) void k_attn_decode_f32(const AttnArgs a) {
+  constexpr int NLD = HD / 16;                    // 1 KiB loads per K tile and per V tile
+  constexpr int TILE_BYTES = kBlockTokens * HD * 4;
+  __shared__ float s_m[kWaves], s_l[kWaves];
+  __shared__ float s_acc[kWaves][HD];
+
+  const int32_t item = blockIdx.x;
+  if (item >= a.hdr[0]) return;                   // uniform over the workgroup
+  const int32_t hq = blockIdx.y;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int row = lane & 15, quad = lane >> 4;
+  const int32_t G = a.group;
+  const int32_t n_q_heads = a.n_kv_heads * G;
+  const int32_t g = hq / G;
+  const int32_t bpi = a.part_tokens / kBlockTokens;
+  const int32_t my_n = (bpi + kWaves - 1 - wave) / kWaves;
+  const uint2 rec = a.items[item];
+  const int32_t b = (int32_t)(rec.x & 0xffffu), part = (int32_t)(rec.x >> 16);
+  const int32_t tok0 = part * a.part_tokens, tok1 = (int32_t)rec.y;
+  const int32_t jb0 = tok0 / kBlockTokens;
+  const int32_t jb1 = tok1 > 0 ? (tok1 + kBlockTokens - 1) / kBlockTokens : 0;
+  const int32_t n_it = (jb1 - jb0 - wave + kWaves - 1) / kWaves;
+  int32_t my_slot = -1;
+  if (lane < my_n) my_slot = a.slots[(size_t)item * bpi + wave + kWaves * lane];
+
+  float qf[NLD][4];
+#pragma unroll
+  for (int i = 0; i < NLD; ++i) {
+    const float4 t = *reinterpret_cast<const float4*>(a.q + (((size_t)b * n_q_heads + hq) * HD + 4 * (4 * i + quad)) * 4);
+    qf[i][0] = t.x * a.scale_log2e; qf[i][1] = t.y * a.scale_log2e;
+    qf[i][2] = t.z * a.scale_log2e; qf[i][3] = t.w * a.scale_log2e;
+  }
+  float m = kNegBig, l = 0.f, acc[NLD];
+#pragma unroll
+  for (int n = 0; n < NLD; ++n) acc[n] = 0.f;
+  const size_t v_off = a.block_bytes / 2;
+  const size_t head_off = (size_t)g * TILE_BYTES + (size_t)lane * 16;
+
+  for (int32_t it = 0; it < n_it; ++it) {
+    int32_t slot = __shfl(my_slot, it, 64);
+    const bool present = slot >= 0;
+    slot = present ? slot : 0;
+    const int32_t limit = present ? tok1 : 0;
+    const int32_t t_first = (jb0 + wave + kWaves * it) * kBlockTokens;
+    const char* kp = a.kv_layer + (size_t)slot * a.block_bytes + head_off;
+    float d = 0.f;
+#pragma unroll
+    for (int i = 0; i < NLD; ++i) {
+      const uint4 r = nt_load16(kp + (size_t)i * 1024);
+      d = fmaf(qf[i][0], __uint_as_float(r.x), d);
+      d = fmaf(qf[i][1], __uint_as_float(r.y), d);
+      d = fmaf(qf[i][2], __uint_as_float(r.z), d);
+      d = fmaf(qf[i][3], __uint_as_float(r.w), d);
+    }
+    float s = quad16_sum(d);                      // score of token t_first + row, on all four lanes of the token
+    if (t_first + row >= limit) s = -INFINITY;
+    const float m_new = fmaxf(m, row16_max(s));
+    const float corr = __builtin_amdgcn_exp2f(m - m_new);
+    const float p = __builtin_amdgcn_exp2f(s - m_new);
+    l = l * corr + p;                             // this lane's token only; summed over the row at the end
+    m = m_new;
+    float pt[4];
+#pragma unroll
+    for (int tt = 0; tt < 4; ++tt) pt[tt] = __shfl(p, 4 * quad + tt, 64);
+#pragma unroll
+    for (int n = 0; n < NLD; ++n) {
+      const uint4 r = nt_load16(kp + v_off + (size_t)n * 1024);
+      const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+      float x = acc[n] * corr;
+#pragma unroll
+      for (int tt = 0; tt < 4; ++tt) {
+        const bool valid = t_first + 4 * quad + tt < limit;        // garbage rows must not reach the sum
+        x = fmaf(pt[tt], valid ? __uint_as_float(w[tt]) : 0.f, x);
+      }
+      acc[n] = x;
+    }
+  }
+  l = row16_sum(l);
+#pragma unroll
+  for (int n = 0; n < NLD; ++n) acc[n] = quad16_sum(acc[n]);
+  if (lane == 0) {
+    s_m[wave] = m;
+    s_l[wave] = l;
+  }
+  if (quad == 0) {
+#pragma unroll
+    for (int n = 0; n < NLD; ++n) s_acc[wave][16 * n + row] = acc[n];
+  }
+  __syncthreads();
+  for (int dim = threadIdx.x; dim < HD; dim += kWaves * 64) {
+    float M = s_m[0];
+#pragma unroll
+    for (int w = 1; w < kWaves; ++w) M = fmaxf(M, s_m[w]);
+    float L = 0.f, A = 0.f;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+      const float wt = __builtin_amdgcn_exp2f(s_m[w] - M);
+      L = fmaf(wt, s_l[w], L);
+      A = fmaf(wt, s_acc[w][dim], A);
+    }
+    const size_t orow = (size_t)b * n_q_heads + hq;
+    if (a.n_parts == 1) {
+      store_elem<F32>(a.out, orow * HD + dim, L > 0.f ? A / L : 0.f);
+    } else {
+      float* w = a.ws + (orow * a.n_parts + part) * (HD + 2);
+      if (dim == 0) {
+        w[0] = M;
+        w[1] = L;
+      }
+      w[2 + dim] = A;
+    }
+  }
+}
+
 // Reduction over the partitions of one (sequence, query head): out = sum_s 2^(m_s - M) acc_s / sum_s 2^(m_s - M) l_s.
 template <typename E, int HD>
 __global__ __launch_bounds__(HD) void k_attn_reduce(const AttnArgs a, int32_t n_q_heads) {
-  using EL = Elem<E>;
   const int32_t hq = blockIdx.x, b = blockIdx.y, dim = threadIdx.x;
   const int32_t ctx = clamp_ctx(a.ctx[b], a.max_blocks);
   int32_t np = ctx <= 0 ? 1 : (ctx + a.part_tokens - 1) / a.part_tokens;
@@ -676,20 +843,17 @@ __global__ __launch_bounds__(HD) void k_attn_reduce(const AttnArgs a, int32_t n_
     L = fmaf(wt, ws[1], L);
     A = fmaf(wt, ws[2 + dim], A);
   }
-  EL::store(a.out, row * HD + dim, L > 0.f ? A / L : 0.f);
+  store_elem<E>(a.out, row * HD + dim, L > 0.f ? A / L : 0.f);
 }
 
 // ---- dispatch ----------------------------------------------------------------------------------------
 
-static bool pick(int32_t dtype, int32_t hd, int32_t g) {
-  if (dtype < 0 || dtype > 2) return false;
-  if (hd != 64 && hd != 128) return false;
-  return g == 1 || g == 2 || g == 4 || g == 8;
-}
-
 bool attn_config_supported(const pie_config& c) {
-  return c.block_tokens == kBlockTokens && pick(c.dtype, c.head_dim, c.n_q_heads / c.n_kv_heads) &&
-         c.max_batch <= kMaxPlanBatch && c.max_blocks_per_seq <= (1 << 19);
+  if (c.block_tokens != kBlockTokens || c.dtype < 0 || c.dtype > 2) return false;
+  if (c.head_dim != 64 && c.head_dim != 128) return false;
+  const int32_t g = c.n_q_heads / c.n_kv_heads;
+  if (c.dtype != PIE_DTYPE_F32 && g > kMaxGroup) return false;
+  return c.max_batch <= kMaxPlanBatch && c.max_blocks_per_seq <= (1 << 19);
 }
 
 static size_t max_parts_of(const pie_config& c) {
@@ -771,25 +935,24 @@ int launch_attn_resolve(const pie_pool* p, const int32_t* d_table, const int32_t
   return PIE_OK;
 }
 
-template <typename E, int HD, int G>
-static int launch_typed(const pie_pool* p, const AttnArgs& a, int32_t batch, int32_t n_q_heads, hipStream_t s,
-                        hipEvent_t e0, hipEvent_t e1) {
+template <typename E, int HD, bool SPLIT>
+static int launch_mfma(const pie_pool* p, const AttnArgs& a, int32_t batch, int32_t n_q_heads, hipStream_t s,
+                       hipEvent_t e0, hipEvent_t e1) {
+  const size_t lds = mfma_lds_floats<HD>(a.group) * sizeof(float);
   // as many workgroups as fit on the GPU at once; the ticket counter hands out the work
-  static int wgs_per_cu = 0;
-  if (wgs_per_cu == 0) {
+  static int wgs_per_cu[kMaxGroup + 1] = {};
+  if (wgs_per_cu[a.group] == 0) {
     int n = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_attn_decode<E, HD, G, true>, kWaves * 64, 0) != hipSuccess || n < 1) {
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_attn_decode_mfma<E, HD, SPLIT>, kWaves * 64, lds) != hipSuccess ||
+        n < 1) {
       (void)hipGetLastError();
       n = 2;
     }
-    wgs_per_cu = n;
+    wgs_per_cu[a.group] = n;
   }
-  const int grid = p->n_cu * wgs_per_cu;
+  const int grid = p->n_cu * wgs_per_cu[a.group];
   if (e0) PIE_HIP(hipEventRecord(e0, s));
-  if (p->attn_nontemporal)
-    hipLaunchKernelGGL((k_attn_decode<E, HD, G, true>), dim3(grid), dim3(kWaves * 64), 0, s, a);
-  else
-    hipLaunchKernelGGL((k_attn_decode<E, HD, G, false>), dim3(grid), dim3(kWaves * 64), 0, s, a);
+  hipLaunchKernelGGL((k_attn_decode_mfma<E, HD, SPLIT>), dim3(grid), dim3(kWaves * 64), lds, s, a);
   PIE_HIP(hipGetLastError());
   if (e1) PIE_HIP(hipEventRecord(e1, s));
   if (a.n_parts > 1) {
@@ -799,26 +962,19 @@ static int launch_typed(const pie_pool* p, const AttnArgs& a, int32_t batch, int
   return PIE_OK;
 }
 
-template <typename E, int HD>
-static int launch_g(const pie_pool* p, const AttnArgs& a, int32_t g, int32_t batch, int32_t nq, hipStream_t s,
-                    hipEvent_t e0, hipEvent_t e1) {
-  switch (g) {
-    case 1: return launch_typed<E, HD, 1>(p, a, batch, nq, s, e0, e1);
-    case 2: return launch_typed<E, HD, 2>(p, a, batch, nq, s, e0, e1);
-    case 4: return launch_typed<E, HD, 4>(p, a, batch, nq, s, e0, e1);
-    case 8: return launch_typed<E, HD, 8>(p, a, batch, nq, s, e0, e1);
-    default: return PIE_EINVAL;
+template <int HD>
+static int launch_f32(const AttnArgs& a, int32_t batch, int32_t n_q_heads, int32_t max_items, hipStream_t s,
+                      hipEvent_t e0, hipEvent_t e1) {
+  if (e0) PIE_HIP(hipEventRecord(e0, s));
+  // one workgroup per possible item and query head; those past the planned count return at once
+  hipLaunchKernelGGL((k_attn_decode_f32<HD>), dim3(max_items, n_q_heads), dim3(kWaves * 64), 0, s, a);
+  PIE_HIP(hipGetLastError());
+  if (e1) PIE_HIP(hipEventRecord(e1, s));
+  if (a.n_parts > 1) {
+    hipLaunchKernelGGL((k_attn_reduce<F32, HD>), dim3(n_q_heads, batch), dim3(HD), 0, s, a, n_q_heads);
+    PIE_HIP(hipGetLastError());
   }
-}
-
-template <typename E>
-static int launch_hd(const pie_pool* p, const AttnArgs& a, int32_t hd, int32_t g, int32_t batch, int32_t nq,
-                     hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
-  switch (hd) {
-    case 64: return launch_g<E, 64>(p, a, g, batch, nq, s, e0, e1);
-    case 128: return launch_g<E, 128>(p, a, g, batch, nq, s, e0, e1);
-    default: return PIE_EINVAL;
-  }
+  return PIE_OK;
 }
 
 // Needs launch_attn_plan and launch_attn_resolve (for region layer & 1) earlier on the same stream, with the
@@ -849,16 +1005,22 @@ int launch_attn_decode(const pie_pool* p, int32_t layer, const void* d_q, int32_
   a.scale_log2e = p->scale_log2e;
   a.max_blocks = max_blocks;
   a.n_kv_heads = c.n_kv_heads;
+  a.group = g;
   a.part_tokens = part;
   a.n_parts = n_parts;
-#ifdef PIE_EXPERIMENT
-  { const char* e = getenv("PIE_DBG_PTR"); a.dbg = e ? (unsigned long long*)strtoull(e, nullptr, 10) : nullptr;
-    const char* c2 = getenv("PIE_DBG_CAP"); a.dbg_cap = c2 ? atoi(c2) : 0; }
-#endif
+  const bool hd128 = c.head_dim == 128;
   switch (c.dtype) {
-    case PIE_DTYPE_F32: return launch_hd<F32>(p, a, c.head_dim, g, batch, c.n_q_heads, s, k_start, k_end);
-    case PIE_DTYPE_F16: return launch_hd<F16>(p, a, c.head_dim, g, batch, c.n_q_heads, s, k_start, k_end);
-    case PIE_DTYPE_BF16: return launch_hd<BF16>(p, a, c.head_dim, g, batch, c.n_q_heads, s, k_start, k_end);
+    case PIE_DTYPE_F32: {
+      const int32_t max_items = batch * n_parts;
+      return hd128 ? launch_f32<128>(a, batch, c.n_q_heads, max_items, s, k_start, k_end)
+                   : launch_f32<64>(a, batch, c.n_q_heads, max_items, s, k_start, k_end);
+    }
+    case PIE_DTYPE_F16:
+      return hd128 ? launch_mfma<F16, 128, false>(p, a, batch, c.n_q_heads, s, k_start, k_end)
+                   : launch_mfma<F16, 64, false>(p, a, batch, c.n_q_heads, s, k_start, k_end);
+    case PIE_DTYPE_BF16:
+      return hd128 ? launch_mfma<BF16, 128, true>(p, a, batch, c.n_q_heads, s, k_start, k_end)
+                   : launch_mfma<BF16, 64, true>(p, a, batch, c.n_q_heads, s, k_start, k_end);
     default: return PIE_EINVAL;
   }
 }
