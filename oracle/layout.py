@@ -19,9 +19,12 @@ TEST INFRASTRUCTURE ONLY - never imported by the product path.
 """
 from __future__ import annotations
 
+from functools import lru_cache
+
 import numpy as np
 
 
+@lru_cache(maxsize=32)
 def element_index(n_kv_heads: int, block_tokens: int, head_dim: int, elem_bytes: int) -> np.ndarray:
     """int64 [2][Hkv][T][d]: position (in elements) of each logical element inside the physical block."""
     T, d = block_tokens, head_dim
@@ -46,13 +49,13 @@ def to_physical(logical: np.ndarray) -> np.ndarray:
     two, hkv, T, d = logical.shape[-4:]
     assert two == 2
     idx = element_index(hkv, T, d, logical.dtype.itemsize).ravel()
+    inverse = np.empty_like(idx)
+    inverse[idx] = np.arange(idx.size)
     flat = logical.reshape(logical.shape[:-4] + (-1,))
-    out = np.empty_like(flat)
-    out[..., idx] = flat
-    return out
+    return np.take(flat, inverse, axis=-1)          # out[..., idx[i]] = flat[..., i]
 
 
 def from_physical(physical: np.ndarray, n_kv_heads: int, block_tokens: int, head_dim: int) -> np.ndarray:
     """Inverse of to_physical."""
     idx = element_index(n_kv_heads, block_tokens, head_dim, physical.dtype.itemsize).ravel()
-    return physical[..., idx].reshape(physical.shape[:-1] + (2, n_kv_heads, block_tokens, head_dim))
+    return np.take(physical, idx, axis=-1).reshape(physical.shape[:-1] + (2, n_kv_heads, block_tokens, head_dim))

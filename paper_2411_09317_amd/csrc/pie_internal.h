@@ -135,8 +135,9 @@ int launch_map_patch(int32_t* d_map, const MapPatch& patch, hipStream_t s);
 int launch_zero_u32(uint32_t* d, int32_t n, hipStream_t s);
 int launch_swap_copy(char* dst_layer_base, const char* src_layer_base, size_t block_bytes, const SwapPairs& pairs,
                      int n_wgs, hipStream_t s);
-int launch_kv_append(const pie_pool* p, int32_t layer, const void* d_k, const void* d_v, const int32_t* d_table,
-                     int32_t max_blocks, const int32_t* d_ctx, int32_t batch, bool stage_valid, hipStream_t s);
+int launch_kv_append(const pie_pool* p, int32_t layer, int32_t n_layers, const void* d_k, const void* d_v,
+                     const int32_t* d_table, int32_t max_blocks, const int32_t* d_ctx, int32_t batch,
+                     bool stage_valid, hipStream_t s);
 int launch_attn_plan(const pie_pool* p, const int32_t* d_ctx, int32_t batch, int32_t max_blocks, hipStream_t s);
 int launch_attn_resolve(const pie_pool* p, const int32_t* d_table, const int32_t* d_ctx, int32_t batch,
                         int32_t max_blocks, bool region0, bool valid0, bool region1, bool valid1, hipStream_t s);

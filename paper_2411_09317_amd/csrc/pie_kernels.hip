@@ -183,6 +183,8 @@ struct AppendArgs {
   const int32_t* table;
   const int32_t* ctx;
   size_t block_bytes;
+  size_t kv_layer_stride;    // blockIdx.y walks layers: bytes between layers in the pool ...
+  size_t new_layer_stride;   // ... and in k_new / v_new
   int32_t max_blocks, n_handles, n_gpu_blocks, n_slots, n_kv_heads, head_dim, block_tokens, elem_bytes;
   int32_t stage_valid;
 };
@@ -209,7 +211,9 @@ __global__ __launch_bounds__(256) void k_kv_append(const AppendArgs a) {
   const int32_t v = 16 / a.elem_bytes;
   const int32_t vec_per_row = a.head_dim / v;
   const int32_t tile_bytes = kAppendBlockTokens * a.head_dim * a.elem_bytes;
-  char* blk = a.kv_layer + (size_t)slot * a.block_bytes;
+  char* blk = a.kv_layer + blockIdx.y * a.kv_layer_stride + (size_t)slot * a.block_bytes;
+  const char* k_new = a.k_new + blockIdx.y * a.new_layer_stride;
+  const char* v_new = a.v_new + blockIdx.y * a.new_layer_stride;
   const size_t v_off = a.block_bytes / 2;
   const int32_t t = pos % kAppendBlockTokens;
   const int32_t n_vec = a.n_kv_heads * vec_per_row;
@@ -217,7 +221,7 @@ __global__ __launch_bounds__(256) void k_kv_append(const AppendArgs a) {
     const int32_t g = i / vec_per_row, cv = i % vec_per_row;
     const size_t src = ((size_t)b * a.n_kv_heads + g) * a.head_dim * a.elem_bytes + (size_t)cv * 16;
     const size_t dst = (size_t)g * tile_bytes + (size_t)k_tile_index(t, cv * v, v) * a.elem_bytes;
-    *reinterpret_cast<uint4*>(blk + dst) = *reinterpret_cast<const uint4*>(a.k_new + src);
+    *reinterpret_cast<uint4*>(blk + dst) = *reinterpret_cast<const uint4*>(k_new + src);
   }
   const int32_t n_el = a.n_kv_heads * a.head_dim;
   for (int32_t i = threadIdx.x; i < n_el; i += blockDim.x) {
@@ -225,15 +229,19 @@ __global__ __launch_bounds__(256) void k_kv_append(const AppendArgs a) {
     const size_t src = ((size_t)b * a.n_kv_heads + g) * a.head_dim + c;
     const size_t dst = v_off + (size_t)g * tile_bytes + (size_t)v_tile_index(t, c, v) * a.elem_bytes;
     if (a.elem_bytes == 2)
-      *reinterpret_cast<uint16_t*>(blk + dst) = reinterpret_cast<const uint16_t*>(a.v_new)[src];
+      *reinterpret_cast<uint16_t*>(blk + dst) = reinterpret_cast<const uint16_t*>(v_new)[src];
     else
-      *reinterpret_cast<uint32_t*>(blk + dst) = reinterpret_cast<const uint32_t*>(a.v_new)[src];
+      *reinterpret_cast<uint32_t*>(blk + dst) = reinterpret_cast<const uint32_t*>(v_new)[src];
   }
 }
 
-int launch_kv_append(const pie_pool* p, int32_t layer, const void* d_k, const void* d_v, const int32_t* d_table,
-                     int32_t max_blocks, const int32_t* d_ctx, int32_t batch, bool stage_valid, hipStream_t s) {
+// Appends for n_layers consecutive layers starting at `layer` in one launch.  With n_layers > 1 every
+// sequence's tail block must be GPU-homed (stage_valid is false: a host-homed tail raises NOT_PRESENT).
+int launch_kv_append(const pie_pool* p, int32_t layer, int32_t n_layers, const void* d_k, const void* d_v,
+                     const int32_t* d_table, int32_t max_blocks, const int32_t* d_ctx, int32_t batch,
+                     bool stage_valid, hipStream_t s) {
   if (((uintptr_t)d_k | (uintptr_t)d_v) % 16) return PIE_EINVAL;
+  if (n_layers < 1 || (n_layers > 1 && stage_valid)) return PIE_EINVAL;
   AppendArgs a;
   a.kv_layer = p->d_kv + (size_t)layer * p->d_layer_stride;
   a.map = p->d_map[layer & 1];
@@ -243,6 +251,8 @@ int launch_kv_append(const pie_pool* p, int32_t layer, const void* d_k, const vo
   a.table = d_table;
   a.ctx = d_ctx;
   a.block_bytes = p->block_bytes;
+  a.kv_layer_stride = p->d_layer_stride;
+  a.new_layer_stride = (size_t)batch * p->cfg.n_kv_heads * p->cfg.head_dim * p->elem_bytes;
   a.max_blocks = max_blocks;
   a.n_handles = p->n_handles;
   a.n_gpu_blocks = p->cfg.n_gpu_blocks;
@@ -252,7 +262,7 @@ int launch_kv_append(const pie_pool* p, int32_t layer, const void* d_k, const vo
   a.block_tokens = p->cfg.block_tokens;
   a.elem_bytes = p->elem_bytes;
   a.stage_valid = stage_valid ? 1 : 0;
-  hipLaunchKernelGGL(k_kv_append, dim3(batch), dim3(256), 0, s, a);
+  hipLaunchKernelGGL(k_kv_append, dim3(batch, n_layers), dim3(256), 0, s, a);
   PIE_HIP(hipGetLastError());
   return PIE_OK;
 }
@@ -387,7 +397,8 @@ __device__ __forceinline__ int32_t clamp_ctx(int32_t ctx, int32_t max_blocks) {
 }
 
 // ---- planning: the list of work items ------------------------------------------------------------------
-// items[i] = {sequence | part << 16, end token of the item}.  hdr[0] = number of items.  Full items
+// items[i] = {sequence | part << 16, context length of the sequence}: item `part` covers the tokens
+// [part * part_tokens, min((part + 1) * part_tokens, context)).  hdr[0] = number of items.  Full items
 // (part_tokens tokens) come first, then one shorter item per sequence whose length is not a multiple of
 // part_tokens (or is <= 0, so that its output is still written), longest first.  Also zeroes the ticket
 // counters of all layers.
@@ -397,6 +408,7 @@ __global__ __launch_bounds__(256) void k_attn_plan(const int32_t* __restrict__ c
                                                    int32_t n_counters, uint32_t* __restrict__ err) {
   __shared__ int32_t s_off[kMaxPlanBatch];   // first full item of the sequence
   __shared__ int32_t s_nf[kMaxPlanBatch];
+  __shared__ int32_t s_ctx[kMaxPlanBatch];  // context length, clamped to [0, what the table can name]
   __shared__ int32_t s_rem[kMaxPlanBatch];   // size of the short item, -1 if none
   __shared__ int32_t s_total_full;
   for (int32_t b = threadIdx.x; b < batch; b += blockDim.x) {
@@ -406,6 +418,7 @@ __global__ __launch_bounds__(256) void k_attn_plan(const int32_t* __restrict__ c
     const int32_t nf = c > 0 ? c / part_tokens : 0;
     const int32_t rem = c > 0 ? c % part_tokens : 0;
     s_nf[b] = nf;
+    s_ctx[b] = c > 0 ? c : 0;
     s_rem[b] = (rem > 0 || c <= 0) ? rem : -1;
   }
   for (int32_t i = threadIdx.x; i < n_counters; i += blockDim.x) counters[i] = 0;
@@ -425,7 +438,7 @@ __global__ __launch_bounds__(256) void k_attn_plan(const int32_t* __restrict__ c
   for (int32_t b = threadIdx.x; b < batch; b += blockDim.x) {
     const int32_t nf = s_nf[b];
     for (int32_t p = 0; p < nf; ++p)
-      items[s_off[b] + p] = make_uint2((uint32_t)b | ((uint32_t)p << 16), (uint32_t)((p + 1) * part_tokens));
+      items[s_off[b] + p] = make_uint2((uint32_t)b | ((uint32_t)p << 16), (uint32_t)s_ctx[b]);
     const int32_t key = s_rem[b];
     if (key >= 0) {
       int32_t rank = 0;                                  // longest first, ties by sequence index
@@ -433,7 +446,7 @@ __global__ __launch_bounds__(256) void k_attn_plan(const int32_t* __restrict__ c
         const int32_t k2 = s_rem[o];
         rank += (k2 > key || (k2 == key && o < b)) ? 1 : 0;
       }
-      items[total_full + rank] = make_uint2((uint32_t)b | ((uint32_t)nf << 16), (uint32_t)(nf * part_tokens + key));
+      items[total_full + rank] = make_uint2((uint32_t)b | ((uint32_t)nf << 16), (uint32_t)s_ctx[b]);
     }
   }
 }
@@ -492,8 +505,13 @@ constexpr size_t mfma_lds_floats(int group) {
   return (size_t)kWaves * 2 * kMaxGroup + (size_t)kWaves * group * (HD + 4);
 }
 
+#ifndef PIE_MFMA_WAVES_PER_EU
+#define PIE_MFMA_WAVES_PER_EU 2
+#endif
+
 template <typename E, int HD, bool SPLIT>
-__global__ __launch_bounds__(kWaves * 64) void k_attn_decode_mfma(const AttnArgs a) {
+__global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(PIE_MFMA_WAVES_PER_EU, 8)))
+void k_attn_decode_mfma(const AttnArgs a) {
   using MM = Mfma<E>;
   constexpr int NKC = HD / 32;                    // 1 KiB loads per K tile and per V tile; QK MFMAs per block
   constexpr int NO = HD / 16;                     // output accumulators (16 dims x 16 heads each)
@@ -549,8 +567,10 @@ __global__ __launch_bounds__(kWaves * 64) void k_attn_decode_mfma(const AttnArgs
     if (next < n_units) rec_next = a.items[next / n_kv];          // consumed after the stream loop
     const int32_t g = (int32_t)(unit % n_kv);
     const int32_t b = (int32_t)(rec.x & 0xffffu), part = (int32_t)(rec.x >> 16);
+    const int32_t ctx_b = (int32_t)rec.y;                          // clamped context length of the sequence
     const int32_t tok0 = part * a.part_tokens;
-    const int32_t tok1 = (int32_t)rec.y;                           // <= tok0 only for an empty sequence
+    const int32_t tok1 = min(ctx_b, tok0 + a.part_tokens);         // <= tok0 only for an empty sequence
+    const int32_t np_b = ctx_b > 0 ? (ctx_b + a.part_tokens - 1) / a.part_tokens : 1;   // partitions of the sequence
     const int32_t hq0 = g * G;
 
     // blocks of this item handled by this wave: j = jb0 + wave + kWaves * it
@@ -686,7 +706,7 @@ __global__ __launch_bounds__(kWaves * 64) void k_attn_decode_mfma(const AttnArgs
         A = fmaf(wt, s_acc[((size_t)w * G + h) * ROW + dim], A);
       }
       const size_t orow = (size_t)b * n_q_heads + hq0 + h;
-      if (a.n_parts == 1) {
+      if (np_b == 1) {                           // the only partition of its sequence: this is the result
         store_elem<E>(a.out, orow * HD + dim, L > 0.f ? A / L : 0.f);
       } else {
         float* w = a.ws + (orow * a.n_parts + part) * (HD + 2);
@@ -729,7 +749,9 @@ __global__ __launch_bounds__(kWaves * 64) void k_attn_decode_f32(const AttnArgs 
   const int32_t my_n = (bpi + kWaves - 1 - wave) / kWaves;
   const uint2 rec = a.items[item];
   const int32_t b = (int32_t)(rec.x & 0xffffu), part = (int32_t)(rec.x >> 16);
-  const int32_t tok0 = part * a.part_tokens, tok1 = (int32_t)rec.y;
+  const int32_t ctx_b = (int32_t)rec.y;           // clamped context length of the sequence
+  const int32_t tok0 = part * a.part_tokens, tok1 = min(ctx_b, tok0 + a.part_tokens);
+  const int32_t np_b = ctx_b > 0 ? (ctx_b + a.part_tokens - 1) / a.part_tokens : 1;
   const int32_t jb0 = tok0 / kBlockTokens;
   const int32_t jb1 = tok1 > 0 ? (tok1 + kBlockTokens - 1) / kBlockTokens : 0;
   const int32_t n_it = (jb1 - jb0 - wave + kWaves - 1) / kWaves;
@@ -812,7 +834,7 @@ __global__ __launch_bounds__(kWaves * 64) void k_attn_decode_f32(const AttnArgs 
       A = fmaf(wt, s_acc[w][dim], A);
     }
     const size_t orow = (size_t)b * n_q_heads + hq;
-    if (a.n_parts == 1) {
+    if (np_b == 1) {                             // the only partition of its sequence: this is the result
       store_elem<F32>(a.out, orow * HD + dim, L > 0.f ? A / L : 0.f);
     } else {
       float* w = a.ws + (orow * a.n_parts + part) * (HD + 2);
@@ -832,6 +854,7 @@ __global__ __launch_bounds__(HD) void k_attn_reduce(const AttnArgs a, int32_t n_
   const int32_t ctx = clamp_ctx(a.ctx[b], a.max_blocks);
   int32_t np = ctx <= 0 ? 1 : (ctx + a.part_tokens - 1) / a.part_tokens;
   if (np > a.n_parts) np = a.n_parts;
+  if (np <= 1) return;                          // a lone partition wrote its result itself
   const size_t row = (size_t)b * n_q_heads + hq;
   const float* w = a.ws + row * a.n_parts * (HD + 2);
   float M = kNegBig;
@@ -873,16 +896,17 @@ static size_t slot_list_ints(const pie_config& c) {
 
 // int32 words of planning state: header, per-layer ticket counters, item records (2 words each), and the
 // per-item slot lists of the two staging regions
+static size_t plan_counter_ints(const pie_config& c) {
+  return (size_t)c.n_layers + ((size_t)c.n_layers & 1);    // keeps the item records 8-byte aligned
+}
+
 size_t attn_plan_ints(const pie_config& c) {
-  return kPlanHdrInts + (size_t)c.n_layers + ((size_t)c.n_layers & 1) + 2 * (size_t)c.max_batch * max_parts_of(c) +
-         2 * slot_list_ints(c);
+  return kPlanHdrInts + plan_counter_ints(c) + 2 * (size_t)c.max_batch * max_parts_of(c) + 2 * slot_list_ints(c);
 }
 
 static int32_t* plan_hdr(const pie_pool* p) { return p->d_plan; }
 static uint32_t* plan_counters(const pie_pool* p) { return reinterpret_cast<uint32_t*>(p->d_plan + kPlanHdrInts); }
-static size_t plan_items_off(const pie_pool* p) {          // kept 8-byte aligned
-  return kPlanHdrInts + (size_t)p->cfg.n_layers + ((size_t)p->cfg.n_layers & 1);
-}
+static size_t plan_items_off(const pie_pool* p) { return kPlanHdrInts + plan_counter_ints(p->cfg); }
 static uint2* plan_items(const pie_pool* p) { return reinterpret_cast<uint2*>(p->d_plan + plan_items_off(p)); }
 static int32_t* plan_slots(const pie_pool* p, int region) {
   return p->d_plan + plan_items_off(p) + 2 * (size_t)p->cfg.max_batch * max_parts_of(p->cfg) +

@@ -639,7 +639,7 @@ int pie_kv_append(pie_pool* p, int32_t layer, const void* d_k, const void* d_v, 
   hipStream_t s = (hipStream_t)stream;
   bool stage_valid = false;
   if ((rc = compute_prologue(p, layer, s, &stage_valid))) return rc;
-  if ((rc = launch_kv_append(p, layer, d_k, d_v, d_block_table, max_blocks, d_ctx_lens, batch, stage_valid, s)))
+  if ((rc = launch_kv_append(p, layer, 1, d_k, d_v, d_block_table, max_blocks, d_ctx_lens, batch, stage_valid, s)))
     return rc;
   return compute_epilogue(p, layer, s);
 }
@@ -738,6 +738,13 @@ int pie_step(pie_pool* p, const void* d_q_all, const void* d_k_new, const void* 
   if ((rc = launch_attn_plan(p, d_ctx_lens, batch, max_blocks, cs))) return rc;
   if ((rc = launch_attn_resolve(p, d_block_table, d_ctx_lens, batch, max_blocks, true, true, L > 1, true, cs)))
     return rc;
+  // When no tail block is host-homed, the new token's rows of every layer go in with one launch up front;
+  // otherwise a layer's append has to wait for that layer's staged blocks.
+  const bool append_up_front = d_k_new && n_dirty == 0;
+  if (append_up_front) {
+    if ((rc = launch_kv_append(p, 0, L, d_k_new, d_v_new, d_block_table, max_blocks, d_ctx_lens, batch, false, cs)))
+      return rc;
+  }
   // layer 0's blocks have no earlier layer to hide behind
   if (n_prefetch > 0) {
     if ((rc = swap_in_impl(p, 0, n_prefetch, h_prefetch, is, true, timed ? p->lev[0].in_start : nullptr,
@@ -754,10 +761,12 @@ int pie_step(pie_pool* p, const void* d_q_all, const void* d_k_new, const void* 
       p->lev[l + 1].in_used = timed;
     }
     bool stage_valid = false;
-    if ((rc = compute_prologue(p, l, cs, &stage_valid))) return rc;
+    if (n_prefetch > 0) {
+      if ((rc = compute_prologue(p, l, cs, &stage_valid))) return rc;     // the presence check
+    }
     if (timed) PIE_HIP(hipEventRecord(p->lev[l].attn_start, cs));
-    if (d_k_new) {
-      if ((rc = launch_kv_append(p, l, (const char*)d_k_new + l * kv_stride, (const char*)d_v_new + l * kv_stride,
+    if (d_k_new && !append_up_front) {
+      if ((rc = launch_kv_append(p, l, 1, (const char*)d_k_new + l * kv_stride, (const char*)d_v_new + l * kv_stride,
                                  d_block_table, max_blocks, d_ctx_lens, batch, stage_valid, cs)))
         return rc;
     }
@@ -766,7 +775,11 @@ int pie_step(pie_pool* p, const void* d_q_all, const void* d_k_new, const void* 
                                  timed ? p->lev[l].k_end : nullptr)))
       return rc;
     if (timed) PIE_HIP(hipEventRecord(p->lev[l].attn_end, cs));
-    if ((rc = compute_epilogue(p, l, cs))) return rc;
+    if (n_prefetch > 0) {
+      // the next user of this staging region (layer l + 2's prefetch, this layer's write-back) waits for it
+      PIE_HIP(hipEventRecord(p->ev_read[l & 1], cs));
+      p->ev_read_rec[l & 1] = true;
+    }
     if (n_dirty > 0 && d_k_new) {
       if ((rc = swap_out_impl(p, l, n_dirty, h_dirty, os, timed ? p->lev[l].out_start : nullptr,
                               timed ? p->lev[l].out_end : nullptr)))
@@ -774,6 +787,9 @@ int pie_step(pie_pool* p, const void* d_q_all, const void* d_k_new, const void* 
       p->lev[l].out_used = timed;
     }
   }
+  // later migrations wait for the step's compute work
+  PIE_HIP(hipEventRecord(p->ev_compute, cs));
+  p->ev_compute_rec = true;
   p->step_timed = timed;
   return PIE_OK;
 }
