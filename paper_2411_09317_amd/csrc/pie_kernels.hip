@@ -848,25 +848,66 @@ __global__ __launch_bounds__(kWaves * 64) void k_attn_decode_f32(const AttnArgs 
 }
 
 // Reduction over the partitions of one (sequence, query head): out = sum_s 2^(m_s - M) acc_s / sum_s 2^(m_s - M) l_s.
+// 256 threads: thread (sub, dim) = (tid / HD, tid % HD) merges the partitions sub, sub + 256/HD, ... online,
+// four loads in flight, and the 256/HD partial merges meet in LDS.
 template <typename E, int HD>
-__global__ __launch_bounds__(HD) void k_attn_reduce(const AttnArgs a, int32_t n_q_heads) {
-  const int32_t hq = blockIdx.x, b = blockIdx.y, dim = threadIdx.x;
+__global__ __launch_bounds__(256) void k_attn_reduce(const AttnArgs a, int32_t n_q_heads) {
+  constexpr int NSUB = 256 / HD;
+  constexpr int UNR = 4;
+  __shared__ float s_M[NSUB], s_L[NSUB], s_A[NSUB][HD];
+  const int32_t hq = blockIdx.x, b = blockIdx.y;
+  const int dim = threadIdx.x % HD, sub = threadIdx.x / HD;
   const int32_t ctx = clamp_ctx(a.ctx[b], a.max_blocks);
   int32_t np = ctx <= 0 ? 1 : (ctx + a.part_tokens - 1) / a.part_tokens;
   if (np > a.n_parts) np = a.n_parts;
   if (np <= 1) return;                          // a lone partition wrote its result itself
   const size_t row = (size_t)b * n_q_heads + hq;
   const float* w = a.ws + row * a.n_parts * (HD + 2);
-  float M = kNegBig;
-  for (int32_t s = 0; s < np; ++s) M = fmaxf(M, w[(size_t)s * (HD + 2)]);
-  float L = 0.f, A = 0.f;
-  for (int32_t s = 0; s < np; ++s) {
-    const float* ws = w + (size_t)s * (HD + 2);
-    const float wt = __builtin_amdgcn_exp2f(ws[0] - M);
-    L = fmaf(wt, ws[1], L);
-    A = fmaf(wt, ws[2 + dim], A);
+  float M = kNegBig, L = 0.f, A = 0.f;
+  for (int32_t s0 = sub; s0 < np; s0 += NSUB * UNR) {
+    float mi[UNR], li[UNR], ai[UNR];
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      const int32_t sp = s0 + u * NSUB;
+      const bool live = sp < np;
+      const float* wp = w + (size_t)(live ? sp : s0) * (HD + 2);
+      mi[u] = live ? wp[0] : kNegBig;
+      li[u] = live ? wp[1] : 0.f;
+      ai[u] = live ? wp[2 + dim] : 0.f;
+    }
+    float m_new = M;
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) m_new = fmaxf(m_new, mi[u]);
+    const float corr = __builtin_amdgcn_exp2f(M - m_new);
+    L *= corr;
+    A *= corr;
+#pragma unroll
+    for (int u = 0; u < UNR; ++u) {
+      const float wt = __builtin_amdgcn_exp2f(mi[u] - m_new);
+      L = fmaf(wt, li[u], L);
+      A = fmaf(wt, ai[u], A);
+    }
+    M = m_new;
   }
-  store_elem<E>(a.out, row * HD + dim, L > 0.f ? A / L : 0.f);
+  if (dim == 0) {
+    s_M[sub] = M;
+    s_L[sub] = L;
+  }
+  s_A[sub][dim] = A;
+  __syncthreads();
+  if (sub == 0) {
+    float Mt = s_M[0];
+#pragma unroll
+    for (int i = 1; i < NSUB; ++i) Mt = fmaxf(Mt, s_M[i]);
+    float Lt = 0.f, At = 0.f;
+#pragma unroll
+    for (int i = 0; i < NSUB; ++i) {
+      const float wt = __builtin_amdgcn_exp2f(s_M[i] - Mt);
+      Lt = fmaf(wt, s_L[i], Lt);
+      At = fmaf(wt, s_A[i][dim], At);
+    }
+    store_elem<E>(a.out, row * HD + dim, Lt > 0.f ? At / Lt : 0.f);
+  }
 }
 
 // ---- dispatch ----------------------------------------------------------------------------------------
@@ -980,7 +1021,7 @@ static int launch_mfma(const pie_pool* p, const AttnArgs& a, int32_t batch, int3
   PIE_HIP(hipGetLastError());
   if (e1) PIE_HIP(hipEventRecord(e1, s));
   if (a.n_parts > 1) {
-    hipLaunchKernelGGL((k_attn_reduce<E, HD>), dim3(n_q_heads, batch), dim3(HD), 0, s, a, n_q_heads);
+    hipLaunchKernelGGL((k_attn_reduce<E, HD>), dim3(n_q_heads, batch), dim3(256), 0, s, a, n_q_heads);
     PIE_HIP(hipGetLastError());
   }
   return PIE_OK;
@@ -995,7 +1036,7 @@ static int launch_f32(const AttnArgs& a, int32_t batch, int32_t n_q_heads, int32
   PIE_HIP(hipGetLastError());
   if (e1) PIE_HIP(hipEventRecord(e1, s));
   if (a.n_parts > 1) {
-    hipLaunchKernelGGL((k_attn_reduce<F32, HD>), dim3(n_q_heads, batch), dim3(HD), 0, s, a, n_q_heads);
+    hipLaunchKernelGGL((k_attn_reduce<F32, HD>), dim3(n_q_heads, batch), dim3(256), 0, s, a, n_q_heads);
     PIE_HIP(hipGetLastError());
   }
   return PIE_OK;
