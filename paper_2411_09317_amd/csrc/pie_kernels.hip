@@ -497,6 +497,7 @@ struct AttnArgs {
   size_t block_bytes;
   float scale_log2e;
   int32_t max_blocks, n_kv_heads, group, part_tokens, n_parts;
+  int32_t max_items;         // entries the item list has room for (batch x n_parts)
 };
 
 // LDS floats the MFMA kernel needs for `group` query heads per kv head
@@ -530,18 +531,29 @@ void k_attn_decode_mfma(const AttnArgs a) {
   const int32_t G = a.group;
   const int32_t n_q_heads = a.n_kv_heads * G;
   const uint32_t n_kv = (uint32_t)a.n_kv_heads;
-  const uint32_t n_units = (uint32_t)a.hdr[0] * n_kv;
+  const uint32_t max_units = (uint32_t)a.max_items * n_kv;        // what the item and slot lists have room for
   const size_t v_off = a.block_bytes / 2;
   const int32_t bpi = a.part_tokens / kBlockTokens;               // blocks per item, <= 64 * kWaves
   const int32_t my_n = (bpi + kWaves - 1 - wave) / kWaves;        // blocks of an item this wave may own
 
   // Units are handed out by tickets.  A workgroup's first two are static (its index, and its index plus the
   // grid size); the rest come from an atomic counter.  The ticket for the unit after next is requested
-  // behind a unit's stream, so the next unit is always known one unit ahead, its metadata is fetched while
-  // the current unit is merged, and no load ever waits behind the contended counter.
+  // behind a unit's stream, so the next unit is always known one unit ahead: its record and slot list are
+  // fetched at the start of the current unit, its first block is requested as soon as the current unit's
+  // stream ends, and the merge of the current unit runs behind those loads.
   uint32_t unit = blockIdx.x;
   uint32_t next = gridDim.x + blockIdx.x;
 
+  // record and this wave's slot list of unit u; entries beyond the planned items are never used
+  auto fetch_meta = [&](uint32_t u, uint2& r, int32_t& sl) {
+    r = make_uint2(0, 0);
+    sl = -1;
+    if (u < max_units) {
+      const uint32_t item = u / n_kv;
+      r = a.items[item];
+      if (lane < my_n) sl = a.slots[(size_t)item * bpi + wave + kWaves * lane];
+    }
+  };
   // this lane's part of the B operand of the first product: head `col` of the group, dims 32 kc + 8 quad ..
   auto load_q = [&](uint4 (&qr)[NKC], int32_t b, int32_t g) {
 #pragma unroll
@@ -551,20 +563,37 @@ void k_attn_decode_mfma(const AttnArgs a) {
         qr[kc] = *reinterpret_cast<const uint4*>(a.q + (((size_t)b * n_q_heads + g * G + col) * HD + 32 * kc + 8 * quad) * 2);
     }
   };
+  // Two register sets: while one block is consumed the next is already in flight.
+  uint4 kA[NKC], vA[NKC], kB[NKC], vB[NKC];
+  auto load_tile = [&](uint4 (&kr)[NKC], uint4 (&vr)[NKC], int32_t slots, int32_t it, int32_t g) {
+    int32_t slot = __shfl(slots, it, 64);
+    slot = slot < 0 ? 0 : slot;                                    // flagged blocks are masked when consumed
+    const char* kp = a.kv_layer + (size_t)slot * a.block_bytes + (size_t)g * TILE_BYTES + (size_t)lane * 16;
+#pragma unroll
+    for (int i = 0; i < NKC; ++i) kr[i] = nt_load16(kp + (size_t)i * 1024);
+#pragma unroll
+    for (int i = 0; i < NKC; ++i) vr[i] = nt_load16(kp + v_off + (size_t)i * 1024);
+  };
+  // blocks of unit (r, u) this wave handles: j = jb0 + wave + kWaves * it, it < n_it (<= 0: nothing)
+  auto wave_blocks = [&](const uint2& r) {
+    const int32_t ctx_u = (int32_t)r.y, tok0_u = (int32_t)(r.x >> 16) * a.part_tokens;
+    const int32_t tok1_u = min(ctx_u, tok0_u + a.part_tokens);
+    const int32_t jb1_u = tok1_u > 0 ? (tok1_u + kBlockTokens - 1) / kBlockTokens : 0;
+    return (jb1_u - tok0_u / kBlockTokens - wave + kWaves - 1) / kWaves;
+  };
 
-  uint2 rec = make_uint2(0, 0);
-  int32_t my_slot = -1;
+  uint2 rec, rec_next;
+  int32_t my_slot, my_slot_next;
   uint4 qreg[NKC];
+  fetch_meta(unit, rec, my_slot);
+  fetch_meta(next, rec_next, my_slot_next);
+  const uint32_t n_units = (uint32_t)a.hdr[0] * n_kv;              // <= max_units
   if (unit < n_units) {
-    const uint32_t item = unit / n_kv;
-    rec = a.items[item];
-    if (lane < my_n) my_slot = a.slots[(size_t)item * bpi + wave + kWaves * lane];
     load_q(qreg, (int32_t)(rec.x & 0xffffu), (int32_t)(unit % n_kv));
+    if (wave_blocks(rec) > 0) load_tile(kA, vA, my_slot, 0, (int32_t)(unit % n_kv));
   }
 
   while (unit < n_units) {                       // every workgroup ends on a ticket past the last unit
-    uint2 rec_next = make_uint2(0, 0);
-    if (next < n_units) rec_next = a.items[next / n_kv];          // consumed after the stream loop
     const int32_t g = (int32_t)(unit % n_kv);
     const int32_t b = (int32_t)(rec.x & 0xffffu), part = (int32_t)(rec.x >> 16);
     const int32_t ctx_b = (int32_t)rec.y;                          // clamped context length of the sequence
@@ -572,30 +601,14 @@ void k_attn_decode_mfma(const AttnArgs a) {
     const int32_t tok1 = min(ctx_b, tok0 + a.part_tokens);         // <= tok0 only for an empty sequence
     const int32_t np_b = ctx_b > 0 ? (ctx_b + a.part_tokens - 1) / a.part_tokens : 1;   // partitions of the sequence
     const int32_t hq0 = g * G;
-
-    // blocks of this item handled by this wave: j = jb0 + wave + kWaves * it
     const int32_t jb0 = tok0 / kBlockTokens;
-    const int32_t jb1 = tok1 > 0 ? (tok1 + kBlockTokens - 1) / kBlockTokens : 0;   // exclusive, <= max_blocks
-    const int32_t n_it = (jb1 - jb0 - wave + kWaves - 1) / kWaves;  // <= my_n <= 64; <= 0 when nothing to do
+    const int32_t n_it = wave_blocks(rec);                         // <= my_n <= 64
 
     float m = kNegBig, l = 0.f;                   // running max of head `col`; this lane's share of the sum
     f32x4 o[NO];
 #pragma unroll
     for (int n = 0; n < NO; ++n) o[n] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    const size_t head_off = (size_t)g * TILE_BYTES + (size_t)lane * 16;
-
-    // Two register sets: while one block is consumed the next is already in flight.
-    uint4 kA[NKC], vA[NKC], kB[NKC], vB[NKC];
-    auto load_tile = [&](uint4 (&kr)[NKC], uint4 (&vr)[NKC], int32_t it) {
-      int32_t slot = __shfl(my_slot, it, 64);
-      slot = slot < 0 ? 0 : slot;                                    // flagged blocks are masked below
-      const char* kp = a.kv_layer + (size_t)slot * a.block_bytes + head_off;
-#pragma unroll
-      for (int i = 0; i < NKC; ++i) kr[i] = nt_load16(kp + (size_t)i * 1024);
-#pragma unroll
-      for (int i = 0; i < NKC; ++i) vr[i] = nt_load16(kp + v_off + (size_t)i * 1024);
-    };
     auto consume = [&](uint4 (&kr)[NKC], uint4 (&vr)[NKC], int32_t it) {
       const int32_t t_first = (jb0 + wave + kWaves * it) * kBlockTokens;      // first token of the block
       const bool present = __shfl(my_slot, it, 64) >= 0;
@@ -657,28 +670,27 @@ void k_attn_decode_mfma(const AttnArgs a) {
       }
     };
 
-    // the ticket after next is requested half way through the stream: late enough that the counter is not
-    // hit by every workgroup at once, early enough that the answer is there when the unit ends
+    // The ticket after next is requested half way through the stream: late enough that the counter is not
+    // hit by every workgroup at once, early enough that the answer is there when the unit ends.  Block 0 of
+    // the unit is already on its way in kA / vA.
     uint32_t after_next = 0;
     const int32_t it_ticket = n_it > 2 ? ((n_it / 2) & ~1) : 0;
-    if (n_it > 0) load_tile(kA, vA, 0);
     for (int32_t it = 0; it < n_it; it += 2) {
       if (it == it_ticket && threadIdx.x == 0) after_next = 2 * gridDim.x + atomicAdd(a.counter, 1u);
-      if (it + 1 < n_it) load_tile(kB, vB, it + 1);
+      if (it + 1 < n_it) load_tile(kB, vB, my_slot, it + 1, g);
       consume(kA, vA, it);
       if (it + 1 < n_it) {
-        if (it + 2 < n_it) load_tile(kA, vA, it + 2);
+        if (it + 2 < n_it) load_tile(kA, vA, my_slot, it + 2, g);
         consume(kB, vB, it + 1);
       }
     }
-
     if (n_it <= 0 && threadIdx.x == 0) after_next = 2 * gridDim.x + atomicAdd(a.counter, 1u);
-    // behind the stream: the next unit's slots and query rows arrive while this unit's result is merged
-    int32_t my_slot_next = -1;
+
+    // behind the stream: the next unit's first block and query rows arrive while this unit's result is merged
     if (next < n_units) {
-      const uint32_t item_n = next / n_kv;
-      if (lane < my_n) my_slot_next = a.slots[(size_t)item_n * bpi + wave + kWaves * lane];
-      load_q(qreg, (int32_t)(rec_next.x & 0xffffu), (int32_t)(next % n_kv));
+      const int32_t g_next = (int32_t)(next % n_kv);
+      if (wave_blocks(rec_next) > 0) load_tile(kA, vA, my_slot_next, 0, g_next);
+      load_q(qreg, (int32_t)(rec_next.x & 0xffffu), g_next);
     }
 
     // merge the kWaves partial states: lane (quad, col) holds O[16 n + 4 quad + r][head col]
@@ -724,6 +736,7 @@ void k_attn_decode_mfma(const AttnArgs a) {
     rec = rec_next;
     my_slot = my_slot_next;
     __syncthreads();                             // all have read the ticket before it is overwritten
+    fetch_meta(next, rec_next, my_slot_next);    // consumed when this unit's stream ends
   }
 }
 
@@ -1073,12 +1086,12 @@ int launch_attn_decode(const pie_pool* p, int32_t layer, const void* d_q, int32_
   a.group = g;
   a.part_tokens = part;
   a.n_parts = n_parts;
+  a.max_items = batch * n_parts;
   const bool hd128 = c.head_dim == 128;
   switch (c.dtype) {
     case PIE_DTYPE_F32: {
-      const int32_t max_items = batch * n_parts;
-      return hd128 ? launch_f32<128>(a, batch, c.n_q_heads, max_items, s, k_start, k_end)
-                   : launch_f32<64>(a, batch, c.n_q_heads, max_items, s, k_start, k_end);
+      return hd128 ? launch_f32<128>(a, batch, c.n_q_heads, a.max_items, s, k_start, k_end)
+                   : launch_f32<64>(a, batch, c.n_q_heads, a.max_items, s, k_start, k_end);
     }
     case PIE_DTYPE_F16:
       return hd128 ? launch_mfma<F16, 128, false>(p, a, batch, c.n_q_heads, s, k_start, k_end)
