@@ -54,6 +54,9 @@ SHAPES = [
     ("gqa4_bf16_d128", I.DTYPE_BF16, 8, 2, 128, 3, (17, 900), 256),
     ("gqa8_bf16_d128", I.DTYPE_BF16, 16, 2, 128, 3, (1, 1100), 512),
     ("gqa2_f16_d64", I.DTYPE_F16, 4, 2, 64, 4, (1, 600), 256),
+    ("gqa16_f16_d128", I.DTYPE_F16, 16, 1, 128, 2, (33, 1500), 512),
+    ("gqa3_bf16_d64", I.DTYPE_BF16, 6, 2, 64, 3, (2, 777), 256),
+    ("mha_bf16_d64", I.DTYPE_BF16, 3, 3, 64, 4, (15, 300), 256),
     ("mha_f32_d128", I.DTYPE_F32, 4, 4, 128, 3, (5, 530), 256),
     ("gqa4_f32_d64", I.DTYPE_F32, 8, 2, 64, 3, (60, 800), 512),
 ]

@@ -1,0 +1,128 @@
+"""GPU parity at the benchmark's sizes, in the launch configuration bench.py times.
+
+The full workloads hold tens of GB, so the float64 oracle checks sampled outputs:
+for sampled (layer, sequence) pairs the sequence's blocks are read back from the
+library's pool, de-paged with the oracle's own statement of the block layout, and
+the dense definition is evaluated for all of that sequence's query heads.  On top
+of that, properties that hold at any size: every output finite, the swap leg's
+outputs bit-identical to the all-resident ones (residency independence), no device
+error flags.
+
+The 70B-shaped workload needs more memory than one GPU has; its test keeps the real
+per-layer shape (batch 32 x 32768 tokens, 64 / 8 heads) on fewer layers.
+"""
+import numpy as np
+import pytest
+import torch
+
+import gpu_helpers as GH
+from oracle import attention as A
+from oracle import layout as LY
+from oracle import numfmt
+from paper_2411_09317_amd import binding as B
+from paper_2411_09317_amd import inputs as I
+from paper_2411_09317_amd import workload as WL
+
+pytestmark = pytest.mark.gpu
+
+REL = {I.DTYPE_F16: 2e-3, I.DTYPE_BF16: 1e-2}
+ABS = 2e-2
+
+
+def oracle_rows(dw, layer, b):
+    """float64 oracle output [Hq][d] of sequence b in `layer`, from the bytes the pool holds."""
+    w = dw.w
+    nb = int(dw.n_blocks[b])
+    where, slots = dw.pool.block_where(dw.table[b, :nb])
+    sd = I.storage_numpy_dtype(w.dtype)
+    raw = []
+    for wh, sl in zip(where, slots):
+        img = dw.pool.gpu_image() if wh == B.GPU else dw.pool.host_image()
+        raw.append(img[layer, sl].cpu().numpy())
+    blocks = LY.from_physical(np.stack(raw).view(sd), w.n_kv_heads, w.block_tokens, w.head_dim)   # [nb][2][Hkv][T][d]
+    blocks = numfmt.to_f64(blocks, w.dtype)
+    ctx = int(dw.ctx_lens[b])
+    K = blocks[:, 0].transpose(0, 2, 1, 3).reshape(nb * w.block_tokens, w.n_kv_heads, w.head_dim)[:ctx]
+    V = blocks[:, 1].transpose(0, 2, 1, 3).reshape(nb * w.block_tokens, w.n_kv_heads, w.head_dim)[:ctx]
+    qd = dw.q[layer, b]
+    q = (qd.view(torch.int16).cpu().numpy().view(np.uint16) if w.dtype == I.DTYPE_BF16 else qd.cpu().numpy())
+    q = numfmt.to_f64(q, w.dtype)
+    return A.dense_attention(q[None], [K], [V], np.array([ctx]))[0]
+
+
+def run_steps(dw, pf, dirty, n=1):
+    streams = (torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream())
+    for _ in range(n):
+        dw.pool.step(dw.q, dw.k_new, dw.v_new, dw.d_table, dw.d_ctx, pf, dirty, dw.out, *streams)
+    dw.pool.sync()
+    assert dw.pool.check_errors() == 0
+
+
+def check_samples(dw, samples):
+    w = dw.w
+    got_all = dw.out
+    assert bool(torch.isfinite(got_all.float()).all())
+    worst = 0.0
+    for layer, b in samples:
+        ref = oracle_rows(dw, layer, b)
+        got = got_all[layer, b].to(torch.float64).cpu().numpy()
+        worst = max(worst, GH.rowwise_rel_err(got, ref))
+        assert np.abs(got - ref).max() <= ABS
+    assert worst <= REL[w.dtype], worst
+    return worst
+
+
+def sample_pairs(dw, n, seed):
+    """Seeded (layer, sequence) pairs that always include the shortest and the longest sequence."""
+    rng = np.random.Generator(np.random.PCG64([dw.w.seed, 901, seed]))
+    pairs = [(int(rng.integers(dw.w.n_layers)), int(np.argmin(dw.ctx_lens))),
+             (int(rng.integers(dw.w.n_layers)), int(np.argmax(dw.ctx_lens)))]
+    while len(pairs) < n:
+        pairs.append((int(rng.integers(dw.w.n_layers)), int(rng.integers(dw.w.batch))))
+    return pairs
+
+
+def test_llama2_7b_shape_all_resident_then_thirty_percent_on_the_host():
+    """The benchmark's workload: all resident, then the 30 % leg; sampled outputs against the oracle, and the
+    swap leg's outputs bit-identical to the resident ones."""
+    none = np.zeros(0, dtype=np.int32)
+    dw = WL.build(I.CONFIGS["cfg2"], host_capacity_fraction=0.32)
+    try:
+        run_steps(dw, none, none, n=2)
+        samples = sample_pairs(dw, 6, 0)
+        check_samples(dw, samples)
+        resident = dw.out.clone()
+        streams = torch.cuda.Stream()
+        hs = WL.per_sequence_host_order(dw, 0.30, I.CONFIGS["cfg3"])
+        dw.pool.migrate(hs, B.HOST, streams)
+        dw.pool.sync()
+        pf, dirty = dw.pool.prefetch_list(dw.table, dw.ctx_lens)
+        assert len(pf) == len(hs) and len(dirty) > 0
+        dw.out.zero_()
+        run_steps(dw, pf, dirty, n=1)
+        assert torch.equal(dw.out.view(torch.int16), resident.view(torch.int16))
+        check_samples(dw, samples[:3])          # the oracle now reads 30 % of the blocks from the host pool
+        st = dw.pool.stats()
+        assert abs(st.host_fraction - 0.30) < 0.01
+    finally:
+        dw.pool.close()
+
+
+def test_llama3_8b_shape_gqa_bf16():
+    none = np.zeros(0, dtype=np.int32)
+    dw = WL.build(I.CONFIGS["cfg4"])
+    try:
+        run_steps(dw, none, none, n=2)
+        check_samples(dw, sample_pairs(dw, 6, 1))
+    finally:
+        dw.pool.close()
+
+
+def test_70b_shape_long_context_per_layer_shape_on_four_layers():
+    none = np.zeros(0, dtype=np.int32)
+    dw = WL.build(I.CONFIGS["cfg5"], n_layers=4)
+    try:
+        run_steps(dw, none, none, n=1)
+        check_samples(dw, [(0, 0), (3, 17), (2, 31)])
+    finally:
+        dw.pool.close()
