@@ -41,10 +41,16 @@ def parse():
     ap.add_argument("--swap-fraction", type=float, default=0.30)
     ap.add_argument("--swap-steps", type=int, default=3)
     ap.add_argument("--swap-path", type=int, default=0)
+    ap.add_argument("--swap-wgs", type=int, default=0, help="workgroups of the gather / scatter kernel (0 = library default)")
     ap.add_argument("--no-swap", action="store_true")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--cpu-seqs", type=int, default=64)
     ap.add_argument("--cpu-layers", type=int, default=6)
+    ap.add_argument("--sweep", default="", help="comma-separated host-resident fractions to run in fixed-fraction mode "
+                    "(e.g. 0,0.005,0.01,0.02,0.05,0.1,0.2,0.3,0.4,0.5,0.6); adds a 'sweep' list to the line")
+    ap.add_argument("--adaptive-steps", type=int, default=0,
+                    help="run the adaptive-expansion controller from f = 0 for this many decode steps; adds 'adaptive'")
+    ap.add_argument("--adaptive-units", type=int, default=0, help="controller levels per 100 %% (default 8 x layers)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run a plain elementwise copy of this many MiB (a known-size reference for HBM counters)")
     return ap.parse_args()
@@ -81,6 +87,76 @@ def layer_profile(dw, streams, pf, dirty, reps=3):
     out["bytes_in"] = int(acc["bytes_in"][-1])
     out["bytes_out"] = int(acc["bytes_out"][-1])
     return out
+
+
+def leg_metrics(w, dw, sp, s_per_step, base_kernel_ms, base_step_ms, achieved):
+    """Numbers of one swap leg from its per-layer profile `sp` and its untimed seconds per step."""
+    st = dw.pool.stats()
+    t_in = float(np.mean(sp["swap_in"]))
+    in_gbs = sp["bytes_in"] / w.n_layers / (t_in * 1e-3) / 1e9 if t_in > 0 else 0.0
+    return {
+        "host_fraction": st.host_fraction, "host_blocks": st.host_blocks_in_use,
+        "expansion_simple": st.expansion_simple, "expansion_staged": st.expansion_staged,
+        "tokens_per_s": w.batch / s_per_step, "ms_per_step": s_per_step * 1e3,
+        "bytes_in_per_layer": sp["bytes_in"] // w.n_layers, "bytes_out_per_layer": sp["bytes_out"] // w.n_layers,
+        "swap_in_ms_per_layer": t_in, "swap_out_ms_per_layer": float(np.mean(sp["swap_out"])),
+        "host_link_GBps": in_gbs, "host_link_peak_GBps": LINK_PEAK_GBS, "host_link_frac": in_gbs / LINK_PEAK_GBS,
+        "attn_kernel_ms_per_layer": float(np.mean(sp["kernel"])),
+        "inflation_kernel": float(np.median(sp["kernel"]) / np.median(base_kernel_ms) - 1.0),
+        "stall_ms_per_step": float(np.sum(sp["stall"])),
+        "inflation_e2e": s_per_step * 1e3 / base_step_ms - 1.0,
+        "transparent_fraction_bound": in_gbs / achieved if achieved > 0 else None,
+    }
+
+
+def fixed_fraction_leg(w, dw, streams, f, n_steps, base_kernel_ms, base_step_ms, achieved):
+    """Fixed-fraction mode: the first round(f * blocks) handles of the seeded order live on the host."""
+    dw.pool.set_host_fraction(f, dw.order, streams[1])
+    dw.pool.sync()
+    pf, dirty = dw.pool.prefetch_list(dw.table, dw.ctx_lens)
+    timed_steps(dw, streams, 1, pf, dirty)
+    s_total = timed_steps(dw, streams, n_steps, pf, dirty)
+    sp = layer_profile(dw, streams, pf, dirty, reps=2)
+    assert dw.pool.check_errors() == 0
+    m = leg_metrics(w, dw, sp, s_total / n_steps, base_kernel_ms, base_step_ms, achieved)
+    keep = ("host_fraction", "tokens_per_s", "ms_per_step", "swap_in_ms_per_layer", "attn_kernel_ms_per_layer",
+            "host_link_GBps", "inflation_kernel", "inflation_e2e", "stall_ms_per_step", "expansion_simple")
+    return {k: m[k] for k in keep}
+
+
+def adaptive_leg(w, dw, streams, n_steps, units, k_max):
+    """The controller in the loop: it starts at f = 0, sees every step's per-layer times, and moves the host
+    fraction one level at a time.  The throughput signal is tokens/s x expansion: a larger effective cache
+    admits a proportionally larger batch (the premise of the method); the batch itself is fixed here."""
+    from paper_2411_09317_amd import binding as B
+    ctl = B.Controller(units, k_max)
+    dw.pool.set_host_fraction(0.0, dw.order, streams[1])
+    dw.pool.sync()
+    dw.pool.set_timing(True)
+    level, traj = 0, []
+    for step in range(n_steps):
+        pf, dirty = dw.pool.prefetch_list(dw.table, dw.ctx_lens)
+        t0 = time.perf_counter()
+        dw.pool.step(dw.q, dw.k_new, dw.v_new, dw.d_table, dw.d_ctx, pf, dirty, dw.out, *streams)
+        dw.pool.sync()
+        dt = time.perf_counter() - t0
+        st = dw.pool.stats()
+        f_next = ctl.update_from_pool(dw.pool, w.batch / dt * st.expansion_simple)
+        traj.append((level, round(dt * 1e3, 3)))
+        new_level = int(round(f_next * units))
+        if new_level != level:
+            dw.pool.set_host_fraction(new_level / units, dw.order, streams[1])
+            dw.pool.sync()
+            level = new_level
+    dw.pool.set_timing(False)
+    assert dw.pool.check_errors() == 0
+    k, ceiling = ctl.level()
+    ctl.close()
+    levels = [t[0] for t in traj]
+    tail = levels[len(levels) // 2:]
+    return {"units": units, "k_max": k_max, "steps": n_steps, "final_level": k, "ceiling": ceiling,
+            "final_host_fraction": k / units, "level_min_second_half": min(tail), "level_max_second_half": max(tail),
+            "levels": levels, "ms_per_step_last": traj[-1][1]}
 
 
 def traffic_from_profile(name):
@@ -155,13 +231,20 @@ def main():
     if args.ctx_fixed:
         w = I.scaled(w, name=w.name + "-fixedctx", ctx_dist="fixed", ctx_lo=args.ctx_fixed, ctx_hi=args.ctx_fixed)
     swap_leg = not args.no_swap and args.swap_fraction > 0
+    host_cap = args.swap_fraction if swap_leg else 0.0
+    if args.sweep:
+        host_cap = max([host_cap] + [float(f) for f in args.sweep.split(",")])
+    if args.adaptive_steps:
+        host_cap = max(host_cap, 0.10)
     t_build = time.perf_counter()
-    dw = WL.build(w, host_capacity_fraction=(args.swap_fraction + 0.02) if swap_leg else 0.0, n_layers=args.layers)
+    dw = WL.build(w, host_capacity_fraction=(host_cap + 0.02) if host_cap > 0 else 0.0, n_layers=args.layers)
     w = dw.w
     t_build = time.perf_counter() - t_build
     if args.partition:
         dw.pool.set_attn_partition(args.partition)
     dw.pool.set_swap_path(args.swap_path)
+    if args.swap_wgs:
+        dw.pool.set_swap_workgroups(args.swap_wgs)
     streams = (torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream())
     none = np.zeros(0, dtype=np.int32)
 
@@ -195,7 +278,7 @@ def main():
                    "context_tokens": int(dw.ctx_lens.sum()), "kv_bytes_per_layer": bytes_layer,
                    "kv_blocks_per_layer": dw.total_blocks, "attn_partition_tokens": args.partition or 512,
                    "build_s": round(t_build, 1)},
-        "roofline": {"bound": "hbm", "kernel": "k_attn_decode", "achieved": achieved, "peak": HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": "k_attn_decode_mfma", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic_from_profile(f"attn_decode_{w.name}_pmc.txt"),
                      "kernel_ms": k_ms, "algorithmic_bytes_per_launch": bytes_layer},
@@ -221,22 +304,19 @@ def main():
         s_total = timed_steps(dw, streams, args.swap_steps, pf, dirty)
         sp = layer_profile(dw, streams, pf, dirty, reps=2)
         assert dw.pool.check_errors() == 0
-        st = dw.pool.stats()
-        in_gbs = sp["bytes_in"] / w.n_layers / (float(np.mean(sp["swap_in"])) * 1e-3) / 1e9
-        result["swap"] = {
-            "host_fraction": st.host_fraction, "host_blocks": st.host_blocks_in_use,
-            "expansion_simple": st.expansion_simple, "expansion_staged": st.expansion_staged,
-            "tokens_per_s": w.batch / (s_total / args.swap_steps), "ms_per_step": s_total / args.swap_steps * 1e3,
-            "bytes_in_per_layer": sp["bytes_in"] // w.n_layers, "bytes_out_per_layer": sp["bytes_out"] // w.n_layers,
-            "swap_in_ms_per_layer": float(np.mean(sp["swap_in"])), "swap_out_ms_per_layer": float(np.mean(sp["swap_out"])),
-            "host_link_GBps": in_gbs, "host_link_peak_GBps": LINK_PEAK_GBS, "host_link_frac": in_gbs / LINK_PEAK_GBS,
-            "attn_kernel_ms_per_layer": float(np.mean(sp["kernel"])),
-            "inflation_kernel": float(np.median(sp["kernel"]) / np.median(base_kernel_ms) - 1.0),
-            "stall_ms_per_step": float(np.sum(sp["stall"])),
-            "inflation_e2e": (s_total / args.swap_steps * 1e3) / base_step_ms - 1.0,
-            "transparent_fraction_bound": in_gbs / achieved, "migrate_s": round(t_mig, 2),
-            "swap_path": args.swap_path,
-        }
+        result["swap"] = leg_metrics(w, dw, sp, s_total / args.swap_steps, base_kernel_ms, base_step_ms, achieved)
+        result["swap"].update({"migrate_s": round(t_mig, 2), "swap_path": args.swap_path})
+        dw.pool.migrate(hs, B.GPU, streams[1])
+        dw.pool.sync()
+
+    # ---- optional: fixed-fraction sweep and the adaptive controller ---------------------------------------
+    if args.sweep:
+        result["sweep"] = [fixed_fraction_leg(w, dw, streams, float(f), args.swap_steps, base_kernel_ms, base_step_ms,
+                                              achieved) for f in args.sweep.split(",")]
+    if args.adaptive_steps:
+        units = args.adaptive_units or 8 * w.n_layers
+        k_max = int(host_cap * units)
+        result["adaptive"] = adaptive_leg(w, dw, streams, args.adaptive_steps, units, k_max)
     dw.pool.close()
     print(json.dumps(result))
 

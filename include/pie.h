@@ -21,7 +21,10 @@
  *     unless stated otherwise.
  *   - Pointers named d_* are device pointers, h_* host pointers.  `stream`
  *     arguments are hipStream_t passed as void*; NULL is the default stream.
- *   - No function blocks the host unless its name ends in _sync.
+ *   - No function waits for the GPU unless its name ends in _sync, with one exception: a swap or migration
+ *     that goes through the copy engine (PIE_SWAP_DMA, or PIE_SWAP_AUTO choosing it) waits on the host for
+ *     the work the copy must follow (the staging region's last reader and write-back), and then enqueues
+ *     the copy.  pie_step therefore paces the host one layer behind the GPU on that path.
  *   - Ownership: the caller allocates the device buffer, the pinned host buffer
  *     and the streams, and frees them after pie_pool_destroy.  The library
  *     allocates no device memory at any time.
@@ -102,7 +105,7 @@ typedef struct {
   float   attn_ms;              /* sum over layers of append + attention time */
   float   swap_in_ms;           /* sum over layers */
   float   swap_out_ms;
-  float   stall_ms;             /* sum over layers of time the compute stream idled before a layer */
+  float   stall_ms;             /* sum over layers of the compute stream's waits for a layer's prefetch */
   uint64_t bytes_in;            /* host -> GPU bytes moved by the last pie_step */
   uint64_t bytes_out;
   uint32_t device_error_flags;  /* PIE_DEVERR_* collected by pie_check_errors_sync calls so far */
@@ -215,8 +218,8 @@ int pie_attn_decode(pie_pool* pool, int32_t layer, const void* d_q,
 /* ---- the pipeline ---------------------------------------------------------- */
 
 /* One decode step over all layers.  h_prefetch: the n_prefetch host-homed handles this batch touches, in
- * (sequence, logical block) order - the host cannot read the device block table, so the caller names them
- * (pie_prefetch_list computes it from a host copy of the table).  h_dirty: the n_dirty of those that receive
+ * any order - the host cannot read the device block table, so the caller names them (pie_prefetch_list
+ * computes the list from a host copy of the table, ordered by host slot so that the copies are contiguous).  h_dirty: the n_dirty of those that receive
  * this step's token (host-homed tail blocks).  For l = 0..L-1: layer l+1's blocks are prefetched on
  * swap_in_stream while layer l runs (append, then attention) on compute_stream; layer l's dirty blocks are
  * written back on swap_out_stream afterwards.
@@ -227,8 +230,9 @@ int pie_step(pie_pool* pool, const void* d_q_all, const void* d_k_new, const voi
              int32_t n_prefetch, const int32_t* h_prefetch, int32_t n_dirty, const int32_t* h_dirty,
              void* d_out_all, void* compute_stream, void* swap_in_stream, void* swap_out_stream);
 
-/* Host-homed handles among h_block_table[b][j], j < ceil(ctx/T), in (b, j) order without repeats; and of
- * those the tail blocks (entry (ctx-1)/T).  out arrays need room for batch*max_blocks and batch entries. */
+/* Host-homed handles among h_block_table[b][j], j < ceil(ctx/T), without repeats, in ascending order of their
+ * host slot (a densely used host pool is then read as one contiguous run); and of those the tail blocks
+ * (entry (ctx-1)/T), same order.  out arrays need room for batch*max_blocks and batch entries. */
 int pie_prefetch_list(pie_pool* pool, const int32_t* h_block_table, int32_t max_blocks,
                       const int32_t* h_ctx_lens, int32_t batch,
                       int32_t* out_prefetch, int32_t* out_n_prefetch, int32_t* out_dirty, int32_t* out_n_dirty);
@@ -244,7 +248,8 @@ int pie_get_stats(pie_pool* pool, pie_stats* out);
 
 /* Per-layer times in ms of the last pie_step; each array has n_layers entries (NULL to skip one).
  * t_attn: append + attention + reduction; t_kernel: the attention decode kernel alone; t_in / t_out: the
- * layer's prefetch / write-back; t_stall: idle time of the compute stream before the layer. */
+ * layer's prefetch / write-back; t_stall: how long the compute stream, free after the previous layer, still had
+ * to wait for this layer's prefetch to finish (0 when the prefetch was hidden). */
 int pie_get_layer_times(pie_pool* pool, float* t_attn, float* t_kernel, float* t_in, float* t_out, float* t_stall);
 
 /* Reads and clears the device error flags after synchronising the pool. */

@@ -232,16 +232,17 @@ class PoolModel:
                                       lambda h: self.read_block(layer, h), self.T, self.scale)
 
     def prefetch_list(self, block_table, ctx_lens):
-        """Host-homed handles a batch touches, in (sequence, logical block) order."""
-        out, seen = [], set()
+        """Host-homed handles a batch touches, each once, in ascending order of
+        their host slot (so that a densely used host pool is read as one
+        contiguous piece and lands, in the same order, in the staging region)."""
+        seen = set()
         for b in range(len(ctx_lens)):
             nb = (int(ctx_lens[b]) + self.T - 1) // self.T
             for j in range(nb):
                 h = int(block_table[b, j])
-                if h in self.home and self.home[h][0] == HOST and h not in seen:
+                if h in self.home and self.home[h][0] == HOST:
                     seen.add(h)
-                    out.append(h)
-        return out
+        return sorted(seen, key=lambda h: self.home[h][1])
 
     def step(self, q_all, k_new, v_new, block_table, ctx_lens):
         """One decode step over all layers: bring layer l's host-homed blocks

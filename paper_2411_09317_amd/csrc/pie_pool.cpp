@@ -132,30 +132,40 @@ static void drop_staged(pie_pool* p, int32_t h) {
   }
 }
 
-// Moves n (src slot -> dst slot) block copies of one layer between the pools or within the device pool.
-// kind: 0 host->device, 1 device->host.  Chooses the copy engine for long contiguous runs and the
-// gather / scatter kernel otherwise.
-static int copy_blocks(pie_pool* p, int kind, int32_t layer, const std::vector<int32_t>& src,
-                       const std::vector<int32_t>& dst, hipStream_t s) {
-  const size_t n = src.size();
-  if (!n) return PIE_OK;
-  // contiguous runs
+// A list of (src slot -> dst slot) block copies of one layer, cut into contiguous runs, and the way it
+// will be moved: the copy engine when the runs are few and long, the gather / scatter kernel otherwise.
+struct CopyPlan {
   struct Run { int32_t src, dst, len; };
   std::vector<Run> runs;
+  int path = PIE_SWAP_KERNEL;
+};
+
+static CopyPlan plan_copy(const pie_pool* p, const std::vector<int32_t>& src, const std::vector<int32_t>& dst) {
+  CopyPlan cp;
+  const size_t n = src.size();
   for (size_t i = 0; i < n; ++i) {
-    if (!runs.empty() && runs.back().src + runs.back().len == src[i] && runs.back().dst + runs.back().len == dst[i])
-      ++runs.back().len;
+    if (!cp.runs.empty() && cp.runs.back().src + cp.runs.back().len == src[i] &&
+        cp.runs.back().dst + cp.runs.back().len == dst[i])
+      ++cp.runs.back().len;
     else
-      runs.push_back({src[i], dst[i], 1});
+      cp.runs.push_back({src[i], dst[i], 1});
   }
-  int path = p->swap_path;
-  if (path == PIE_SWAP_AUTO) {
+  cp.path = p->swap_path;
+  if (cp.path == PIE_SWAP_AUTO) {
     // the copy engine pays a fixed cost per call; use it when runs are long on average
-    const size_t avg_bytes = n * p->block_bytes / runs.size();
-    path = (runs.size() <= 64 && avg_bytes >= ((size_t)1 << 20)) ? PIE_SWAP_DMA : PIE_SWAP_KERNEL;
+    const size_t avg_bytes = n ? n * p->block_bytes / cp.runs.size() : 0;
+    cp.path = (cp.runs.size() <= 64 && avg_bytes >= ((size_t)1 << 20)) ? PIE_SWAP_DMA : PIE_SWAP_KERNEL;
   }
-  if (path == PIE_SWAP_DMA) {
-    for (const Run& r : runs) {
+  return cp;
+}
+
+// kind: 0 host->device, 1 device->host.
+static int copy_blocks(pie_pool* p, int kind, int32_t layer, const std::vector<int32_t>& src,
+                       const std::vector<int32_t>& dst, const CopyPlan& cp, hipStream_t s) {
+  const size_t n = src.size();
+  if (!n) return PIE_OK;
+  if (cp.path == PIE_SWAP_DMA) {
+    for (const CopyPlan::Run& r : cp.runs) {
       const size_t bytes = (size_t)r.len * p->block_bytes;
       if (kind == 0)
         PIE_HIP(hipMemcpyAsync(d_block(p, layer, r.dst), h_block(p, layer, r.src), bytes, hipMemcpyHostToDevice, s));
@@ -181,6 +191,19 @@ static int copy_blocks(pie_pool* p, int kind, int32_t layer, const std::vector<i
     int rc = launch_swap_copy(dst_base, src_base, p->block_bytes, pairs, p->swap_wgs, s);
     if (rc) return rc;
   }
+  return PIE_OK;
+}
+
+// Orders stream s after event ev.  Kernels wait on the device.  A copy-engine transfer whose stream has an
+// unfinished wait on another stream's event makes the runtime hold the host inside the copy call, for an
+// unpredictable time; so for those the host waits for the event itself, and the copy is then enqueued on a
+// stream with nothing pending.
+static int order_after(hipStream_t s, hipEvent_t ev, bool recorded, bool on_host) {
+  if (!recorded) return PIE_OK;
+  if (on_host)
+    PIE_HIP(hipEventSynchronize(ev));
+  else
+    PIE_HIP(hipStreamWaitEvent(s, ev, 0));
   return PIE_OK;
 }
 
@@ -223,18 +246,20 @@ static int swap_in_impl(pie_pool* p, int32_t layer, int32_t n, const int32_t* ha
   note_stream(p, s);
   publish_stage_list(p, r, n, handles);
   p->region_layer[r] = layer;
-  // the region may still be read by compute or written back
-  int rc;
-  if ((rc = wait_if(s, p->ev_read[r], p->ev_read_rec[r]))) return rc;
-  if ((rc = wait_if(s, p->ev_out[r], p->ev_out_rec[r]))) return rc;
-  if ((rc = wait_if(s, p->ev_migrate, p->ev_migrate_rec))) return rc;
-  if (t0) PIE_HIP(hipEventRecord(t0, s));
   std::vector<int32_t> src(n), dst(n);
   for (int32_t i = 0; i < n; ++i) {
     src[i] = p->home[handles[i]].slot;
     dst[i] = stage_slot(p, r, i);
   }
-  if ((rc = copy_blocks(p, 0, layer, src, dst, s))) return rc;
+  const CopyPlan cp = plan_copy(p, src, dst);
+  const bool on_host = n > 0 && cp.path == PIE_SWAP_DMA;
+  // the region may still be read by compute or written back
+  int rc;
+  if ((rc = order_after(s, p->ev_read[r], p->ev_read_rec[r], on_host))) return rc;
+  if ((rc = order_after(s, p->ev_out[r], p->ev_out_rec[r], on_host))) return rc;
+  if ((rc = order_after(s, p->ev_migrate, p->ev_migrate_rec, on_host))) return rc;
+  if (t0) PIE_HIP(hipEventRecord(t0, s));
+  if ((rc = copy_blocks(p, 0, layer, src, dst, cp, s))) return rc;
   if (t1) PIE_HIP(hipEventRecord(t1, s));
   // phase two happens when this event completes
   PIE_HIP(hipEventRecord(p->ev_in[r], s));
@@ -255,15 +280,17 @@ static int swap_out_impl(pie_pool* p, int32_t layer, int32_t n, const int32_t* h
     if (p->stage_rank[r][handles[i]] < 0) return PIE_ESTATE;
   if (!p->device) return PIE_ESTATE;
   note_stream(p, s);
-  if ((rc = wait_if(s, p->ev_in[r], p->ev_in_rec[r]))) return rc;
-  if ((rc = wait_if(s, p->ev_read[r], p->ev_read_rec[r]))) return rc;
-  if (t0) PIE_HIP(hipEventRecord(t0, s));
   std::vector<int32_t> src(n), dst(n);
   for (int32_t i = 0; i < n; ++i) {
     src[i] = stage_slot(p, r, p->stage_rank[r][handles[i]]);
     dst[i] = p->home[handles[i]].slot;
   }
-  if ((rc = copy_blocks(p, 1, layer, src, dst, s))) return rc;
+  const CopyPlan cp = plan_copy(p, src, dst);
+  const bool on_host = n > 0 && cp.path == PIE_SWAP_DMA;
+  if ((rc = order_after(s, p->ev_in[r], p->ev_in_rec[r], on_host))) return rc;
+  if ((rc = order_after(s, p->ev_read[r], p->ev_read_rec[r], on_host))) return rc;
+  if (t0) PIE_HIP(hipEventRecord(t0, s));
+  if ((rc = copy_blocks(p, 1, layer, src, dst, cp, s))) return rc;
   if (t1) PIE_HIP(hipEventRecord(t1, s));
   PIE_HIP(hipEventRecord(p->ev_out[r], s));
   p->ev_out_rec[r] = true;
@@ -551,14 +578,6 @@ int pie_migrate(pie_pool* p, int32_t n, const int32_t* handles, int32_t to_where
   if (movers.size() > p->free_slots[to_where].size()) return PIE_ENOMEM;
   if (movers.empty()) return PIE_OK;
   hipStream_t s = (hipStream_t)stream;
-  if (p->device) {
-    note_stream(p, s);
-    if ((rc = wait_if(s, p->ev_compute, p->ev_compute_rec))) return rc;
-    for (int r = 0; r < 2; ++r) {
-      if ((rc = wait_if(s, p->ev_in[r], p->ev_in_rec[r]))) return rc;
-      if ((rc = wait_if(s, p->ev_out[r], p->ev_out_rec[r]))) return rc;
-    }
-  }
   std::vector<int32_t> src(movers.size()), dst(movers.size());
   const int from = 1 - to_where;
   for (size_t i = 0; i < movers.size(); ++i) {
@@ -580,8 +599,16 @@ int pie_migrate(pie_pool* p, int32_t n, const int32_t* handles, int32_t to_where
   p->n_in_use[from] -= (int32_t)movers.size();
   p->n_in_use[to_where] += (int32_t)movers.size();
   if (p->device) {
+    const CopyPlan cp = plan_copy(p, src, dst);
+    const bool on_host = cp.path == PIE_SWAP_DMA;
+    note_stream(p, s);
+    if ((rc = order_after(s, p->ev_compute, p->ev_compute_rec, on_host))) return rc;
+    for (int r = 0; r < 2; ++r) {
+      if ((rc = order_after(s, p->ev_in[r], p->ev_in_rec[r], on_host))) return rc;
+      if ((rc = order_after(s, p->ev_out[r], p->ev_out_rec[r], on_host))) return rc;
+    }
     for (int32_t layer = 0; layer < p->cfg.n_layers; ++layer)
-      if ((rc = copy_blocks(p, to_where == PIE_WHERE_GPU ? 0 : 1, layer, src, dst, s))) return rc;
+      if ((rc = copy_blocks(p, to_where == PIE_WHERE_GPU ? 0 : 1, layer, src, dst, cp, s))) return rc;
     PIE_HIP(hipEventRecord(p->ev_migrate, s));
     p->ev_migrate_rec = true;
   }
@@ -691,6 +718,10 @@ int pie_prefetch_list(pie_pool* p, const int32_t* h_block_table, int32_t max_blo
       }
     }
   }
+  // ascending host slot: a densely used host pool is then one contiguous run, copied by one DMA transfer
+  auto by_slot = [p](int32_t x, int32_t y) { return p->home[x].slot < p->home[y].slot; };
+  std::sort(out_prefetch, out_prefetch + np, by_slot);
+  std::sort(out_dirty, out_dirty + nd, by_slot);
   *out_n_prefetch = np;
   *out_n_dirty = nd;
   return PIE_OK;
@@ -753,13 +784,6 @@ int pie_step(pie_pool* p, const void* d_q_all, const void* d_k_new, const void* 
     p->lev[0].in_used = timed;
   }
   for (int32_t l = 0; l < L; ++l) {
-    if (l + 1 < L && n_prefetch > 0) {
-      // enqueue the next layer's prefetch before this layer's compute so the two overlap
-      if ((rc = swap_in_impl(p, l + 1, n_prefetch, h_prefetch, is, true, timed ? p->lev[l + 1].in_start : nullptr,
-                             timed ? p->lev[l + 1].in_end : nullptr)))
-        return rc;
-      p->lev[l + 1].in_used = timed;
-    }
     bool stage_valid = false;
     if (n_prefetch > 0) {
       if ((rc = compute_prologue(p, l, cs, &stage_valid))) return rc;     // the presence check
@@ -779,6 +803,16 @@ int pie_step(pie_pool* p, const void* d_q_all, const void* d_k_new, const void* 
       // the next user of this staging region (layer l + 2's prefetch, this layer's write-back) waits for it
       PIE_HIP(hipEventRecord(p->ev_read[l & 1], cs));
       p->ev_read_rec[l & 1] = true;
+    }
+    if (l + 1 < L && n_prefetch > 0) {
+      // The next layer's prefetch goes into the region layer l - 1 used, so it starts when that layer ends
+      // and runs behind this one.  It is enqueued after this layer's kernels because a copy-engine
+      // transfer makes the host wait for layer l - 1 here (see order_after): the compute stream must
+      // already hold this layer's work then.
+      if ((rc = swap_in_impl(p, l + 1, n_prefetch, h_prefetch, is, true, timed ? p->lev[l + 1].in_start : nullptr,
+                             timed ? p->lev[l + 1].in_end : nullptr)))
+        return rc;
+      p->lev[l + 1].in_used = timed;
     }
     if (n_dirty > 0 && d_k_new) {
       if ((rc = swap_out_impl(p, l, n_dirty, h_dirty, os, timed ? p->lev[l].out_start : nullptr,
@@ -836,9 +870,12 @@ int pie_get_layer_times(pie_pool* p, float* t_attn, float* t_kernel, float* t_in
       t_out[l] = ms;
     }
     if (t_stall) {
-      // idle time of the compute stream before this layer: from the previous layer's end (or the step's
-      // start) to this layer's start
-      if ((rc = elapsed(l == 0 ? p->ev_step_start : p->lev[l - 1].attn_end, p->lev[l].attn_start, &ms))) return rc;
+      // time the compute stream, free since the previous layer ended (or the step began), still had to wait
+      // for this layer's prefetch: from that moment to the end of the swap-in, if the swap-in ended later
+      ms = 0.f;
+      if (p->lev[l].in_used &&
+          (rc = elapsed(l == 0 ? p->ev_step_start : p->lev[l - 1].attn_end, p->lev[l].in_end, &ms)))
+        return rc;
       t_stall[l] = ms > 0.f ? ms : 0.f;
     }
   }

@@ -236,3 +236,13 @@ def test_append_to_unstaged_host_block_is_an_error():
     with pytest.raises(PoolError) as e:
         m.kv_append(0, k, k, table, case.ctx_lens)
     assert e.value.code == ESTATE
+
+
+def test_prefetch_list_is_the_host_homed_set_in_host_slot_order():
+    case, m, table = populated()
+    plist = m.prefetch_list(table, case.ctx_lens)
+    want = {int(table[b, j]) for b in range(W.batch) for j in range(int(case.n_blocks[b]))
+            if m.home[int(table[b, j])][0] == 1}
+    assert set(plist) == want and len(plist) == len(want)
+    slots = [m.home[h][1] for h in plist]
+    assert slots == sorted(slots)
