@@ -51,6 +51,9 @@ def parse():
     ap.add_argument("--adaptive-steps", type=int, default=0,
                     help="run the adaptive-expansion controller from f = 0 for this many decode steps; adds 'adaptive'")
     ap.add_argument("--adaptive-units", type=int, default=0, help="controller levels per 100 %% (default 8 x layers)")
+    ap.add_argument("--t-other-us", type=float, default=0.0,
+                    help="experiments only: keep the compute stream busy this long after each layer's attention, standing "
+                         "for the rest of a transformer layer (default 0 = the measured path)")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run a plain elementwise copy of this many MiB (a known-size reference for HBM counters)")
     return ap.parse_args()
@@ -245,6 +248,8 @@ def main():
     dw.pool.set_swap_path(args.swap_path)
     if args.swap_wgs:
         dw.pool.set_swap_workgroups(args.swap_wgs)
+    if args.t_other_us:
+        dw.pool.set_layer_compute_us(args.t_other_us)
     streams = (torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream())
     none = np.zeros(0, dtype=np.int32)
 
@@ -277,6 +282,7 @@ def main():
                                f"[{w.ctx_lo},{w.ctx_hi}], all KV GPU-resident",
                    "context_tokens": int(dw.ctx_lens.sum()), "kv_bytes_per_layer": bytes_layer,
                    "kv_blocks_per_layer": dw.total_blocks, "attn_partition_tokens": args.partition or 512,
+                   "t_other_us": args.t_other_us,
                    "build_s": round(t_build, 1)},
         "roofline": {"bound": "hbm", "kernel": "k_attn_decode_mfma", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,

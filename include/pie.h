@@ -193,6 +193,14 @@ int pie_set_attn_partition(pie_pool* pool, int32_t tokens);
  * so few are enough and the rest of the GPU stays free for attention. */
 int pie_set_swap_workgroups(pie_pool* pool, int32_t n);
 
+/* Stand-in for the rest of a transformer layer.  The paper's per-layer compute time (Section 3.1, the
+ * t_compute of its swap constraint) covers the whole layer - projections and MLP, i.e. mostly the time to
+ * read the layer's weights - while this library computes only the attention.  With us > 0, pie_step keeps
+ * the compute stream busy for about `us` microseconds after each layer's attention (one idle wave watching
+ * the clock; no memory traffic), and counts that time in the layer's t_attn.  Default 0: off.  It is a
+ * knob for experiments on the controller and the overlap, not part of the measured path. */
+int pie_set_layer_compute_us(pie_pool* pool, float us);
+
 /* ---- per-layer operations ------------------------------------------------ */
 
 /* Appends this step's key and value rows.  d_k, d_v: [batch][n_kv_heads][head_dim] in the pool's dtype.

@@ -103,6 +103,8 @@ struct pie_pool {
   int32_t attn_partition = 512;   // tokens per work item (one workgroup)
   bool attn_nontemporal = true;   // non-temporal K/V loads in the attention kernel
   int32_t swap_wgs = 64;          // workgroups of the gather / scatter kernel
+  float layer_compute_us = 0.f;   // stand-in for the rest of a layer's compute in pie_step (0 = none)
+  int32_t wall_clock_khz = 100000;
   bool timing = false;
   uint32_t last_err_flags = 0;    // device error flags seen by pie_check_errors_sync so far
 
@@ -130,6 +132,7 @@ inline char* h_block(const pie_pool* p, int32_t layer, int32_t slot) {
 }
 
 // kernel launchers (pie_kernels.hip)
+int launch_busy(double us, int wall_clock_khz, hipStream_t s);
 int launch_map_fill(int32_t* d_map, int32_t n, int32_t value, hipStream_t s);
 int launch_map_patch(int32_t* d_map, const MapPatch& patch, hipStream_t s);
 int launch_zero_u32(uint32_t* d, int32_t n, hipStream_t s);

@@ -35,6 +35,27 @@ __global__ void k_map_patch(int32_t* __restrict__ map, const MapPatch patch) {
   if (i < patch.n) map[patch.handle[i]] = patch.slot[i];
 }
 
+// Occupies a stream for about `ticks` ticks of the constant wall clock: one wave that sleeps and looks at
+// the clock.  max_iter bounds the loop, so the wave exits whatever the clock does.
+__global__ void k_busy(unsigned long long ticks, uint32_t max_iter) {
+  const unsigned long long t0 = wall_clock64();
+  for (uint32_t i = 0; i < max_iter; ++i) {
+    if (wall_clock64() - t0 >= ticks) break;
+    __builtin_amdgcn_s_sleep(16);
+  }
+}
+
+int launch_busy(double us, int wall_clock_khz, hipStream_t s) {
+  if (!(us > 0.0)) return PIE_OK;
+  const unsigned long long ticks = (unsigned long long)(us * 1e-3 * (double)wall_clock_khz);
+  // an iteration takes at least the sleep's 16 x 64 clocks, i.e. well over 0.1 us: 16 iterations per us plus
+  // slack always reach the deadline first
+  const uint32_t max_iter = (uint32_t)(us * 16.0) + 4096u;
+  hipLaunchKernelGGL(k_busy, dim3(1), dim3(64), 0, s, ticks, max_iter);
+  PIE_HIP(hipGetLastError());
+  return PIE_OK;
+}
+
 int launch_map_fill(int32_t* d_map, int32_t n, int32_t value, hipStream_t s) {
   if (n <= 0) return PIE_OK;
   hipLaunchKernelGGL(k_fill_i32, dim3((n + 255) / 256), dim3(256), 0, s, d_map, n, value);

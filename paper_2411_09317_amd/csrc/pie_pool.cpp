@@ -398,6 +398,11 @@ int pie_pool_init(const pie_config* cfg, void* d_base, size_t d_bytes, void* h_p
         p->n_cu = n_cu;
       else
         (void)hipGetLastError();
+      int khz = 0;
+      if (hipDeviceGetAttribute(&khz, hipDeviceAttributeWallClockRate, dev) == hipSuccess && khz > 0)
+        p->wall_clock_khz = khz;
+      else
+        (void)hipGetLastError();
     }
     auto fail = [&](int code) { pie_pool_destroy(p); return code; };
     if (cfg->n_host_blocks > 0) {
@@ -649,6 +654,12 @@ int pie_set_attn_partition(pie_pool* p, int32_t tokens) {
   return PIE_OK;
 }
 
+int pie_set_layer_compute_us(pie_pool* p, float us) {
+  if (!p || !(us >= 0.f) || us > 1.0e6f) return PIE_EINVAL;
+  p->layer_compute_us = us;
+  return PIE_OK;
+}
+
 int pie_set_swap_workgroups(pie_pool* p, int32_t n) {
   if (!p || n < 1 || n > 1024) return PIE_EINVAL;
   p->swap_wgs = n;
@@ -798,6 +809,7 @@ int pie_step(pie_pool* p, const void* d_q_all, const void* d_k_new, const void* 
                                  (char*)d_out_all + l * q_stride, cs, timed ? p->lev[l].k_start : nullptr,
                                  timed ? p->lev[l].k_end : nullptr)))
       return rc;
+    if (p->layer_compute_us > 0.f && (rc = launch_busy(p->layer_compute_us, p->wall_clock_khz, cs))) return rc;
     if (timed) PIE_HIP(hipEventRecord(p->lev[l].attn_end, cs));
     if (n_prefetch > 0) {
       // the next user of this staging region (layer l + 2's prefetch, this layer's write-back) waits for it
