@@ -287,6 +287,102 @@ int pie_controller_level(pie_controller* ctl, int32_t* out_level, int32_t* out_c
 /* Convenience: feeds the pool's last-step timings (timing on, step complete) to the controller. */
 int pie_controller_update(pie_pool* pool, pie_controller* ctl, double throughput, float* out_host_fraction);
 
+/* ---- layer-granular swapping (Section 3.2 mapping table; Section 3.3 protocol) ------------------------
+ *
+ * The paper's own unit of swapping is a whole layer's KV cache.  pie_layer_sched is its swapping control as
+ * pure host logic: a mapping table logical layer -> (state, GPU layer slot, CPU layer slot), at most one
+ * swap-in and one swap-out in flight, and at the beginning of each layer's computation
+ *   - a swap-out of the coldest layer on the GPU (the one whose next access is farthest: the layer that just
+ *     finished) if the previous swap-out has completed and a CPU slot is free - unless every layer in CPU
+ *     memory is colder still;
+ *   - a swap-in of the hottest layer in CPU memory (the one accessed soonest) if the previous swap-in has
+ *     completed and a GPU slot is free;
+ *   - before that, the presence check: a layer that is not physically on the GPU is waited for, and brought
+ *     back at once if it is not even on its way.
+ * Moves update the table in two phases: starting a move names the destination slot (state MOVING_*);
+ * pie_layer_sched_complete, called when the copy has finished, makes the layer present there and frees the
+ * slot it left.  Layers are numbered 0 .. n_layers-1 and computed in that order, cyclically. */
+typedef struct pie_layer_sched pie_layer_sched;
+typedef struct pie_layer_pool pie_layer_pool;
+
+#define PIE_LAYER_GPU        0
+#define PIE_LAYER_HOST       1
+#define PIE_LAYER_MOVING_OUT 2   /* GPU -> CPU copy in flight; both slots held */
+#define PIE_LAYER_MOVING_IN  3
+
+#define PIE_LAYER_WAIT_NONE 0
+#define PIE_LAYER_WAIT_IN   1    /* wait for the swap-in in flight, report it complete, ask again */
+#define PIE_LAYER_WAIT_OUT  2    /* likewise for the swap-out in flight */
+
+#define PIE_LAYER_SKIP_NOT            0   /* the move was started */
+#define PIE_LAYER_SKIP_BUSY           1   /* the previous move in that direction has not completed */
+#define PIE_LAYER_SKIP_NO_SLOT        2   /* no free slot on the destination */
+#define PIE_LAYER_SKIP_COLDER_ON_HOST 3   /* every layer in CPU memory is colder than the candidate */
+#define PIE_LAYER_SKIP_NONE           4   /* no candidate */
+
+typedef struct {
+  int32_t state;       /* PIE_LAYER_* */
+  int32_t gpu_slot;    /* -1 = none */
+  int32_t host_slot;   /* -1 = none */
+} pie_layer_entry;
+
+typedef struct {
+  int32_t wait;                                      /* PIE_LAYER_WAIT_*; when not NONE, gpu_slot is invalid */
+  int32_t gpu_slot;                                  /* where the layer to compute lives */
+  int32_t in_layer, in_gpu_slot, in_host_slot;       /* swap-in to start now; in_layer -1 = none */
+  int32_t out_layer, out_gpu_slot, out_host_slot;    /* swap-out to start now; out_layer -1 = none */
+  int32_t forced_in;                                 /* the swap-in is of the layer to compute itself */
+  int32_t out_skipped, in_skipped;                   /* PIE_LAYER_SKIP_* (policy only) */
+} pie_layer_action;
+
+/* on_host: the n_on_host layers that start in CPU memory; the others start on the GPU.  Slots are handed
+ * out lowest first, in layer order.  PIE_ENOMEM if the placement does not fit the slot counts. */
+int pie_layer_sched_create(int32_t n_layers, int32_t n_gpu_slots, int32_t n_host_slots, int32_t n_on_host,
+                           const int32_t* on_host, pie_layer_sched** out);
+int pie_layer_sched_destroy(pie_layer_sched* s);
+/* Phase two of the move in flight: which = 0 swap-in, 1 swap-out.  PIE_ESTATE if none is in flight. */
+int pie_layer_sched_complete(pie_layer_sched* s, int32_t which);
+/* The presence check for `layer`.  Either out->wait == NONE and out->gpu_slot says where the layer is, or
+ * the caller must start the moves named in *out (a forced swap-in of the layer, or the swap-out of a victim
+ * that makes room for it), wait as out->wait says, call pie_layer_sched_complete, and ask again. */
+int pie_layer_sched_present(pie_layer_sched* s, int32_t layer, pie_layer_action* out);
+/* The two checks at the beginning of `layer`'s computation (it must be present: PIE_ESTATE otherwise).  The
+ * caller starts the moves named in *out. */
+int pie_layer_sched_policy(pie_layer_sched* s, int32_t layer, pie_layer_action* out);
+/* The mapping table: n_layers entries. */
+int pie_layer_sched_table(pie_layer_sched* s, pie_layer_entry* out);
+
+/* pie_layer_pool runs that protocol on the GPU.  `pool` provides the GPU layer slots: a device pool created
+ * with n_stage_blocks = n_host_blocks = 0 whose n_layers is the number of GPU layer slots; a layer's image is
+ * its n_gpu_blocks blocks, contiguous, and block handles / tables are those of `pool`, the same for every
+ * layer (base pointer per layer, offsets unchanged: Section 4.1).  h_pinned holds n_host_slots layer images
+ * (pie_layer_pool_bytes_required).  The pool must outlive the layer pool.  Transfers are whole layers
+ * through the copy engine; all ordering between streams is done on the host, so pie_layer_step paces the
+ * host with the GPU, one layer ahead. */
+typedef struct {
+  int64_t n_steps, n_swap_in, n_swap_out, n_forced_in;
+  uint64_t bytes_in, bytes_out;
+  double  stall_ms;            /* host time spent waiting in presence checks */
+} pie_layer_stats;
+
+int pie_layer_pool_bytes_required(pie_pool* pool, int32_t n_host_slots, size_t* h_bytes);
+int pie_layer_pool_create(pie_pool* pool, int32_t n_layers, int32_t n_host_slots, void* h_pinned, size_t h_bytes,
+                          int32_t n_on_host, const int32_t* on_host, pie_layer_pool** out);
+int pie_layer_pool_destroy(pie_layer_pool* lp);
+/* One decode step over the n_layers logical layers, in order.  Arguments as pie_step, with
+ * d_q_all / d_out_all [n_layers][batch][n_q_heads][head_dim] and d_k_new / d_v_new
+ * [n_layers][batch][n_kv_heads][head_dim] indexed by logical layer. */
+int pie_layer_step(pie_layer_pool* lp, const void* d_q_all, const void* d_k_new, const void* d_v_new,
+                   const int32_t* d_block_table, int32_t max_blocks, const int32_t* d_ctx_lens, int32_t batch,
+                   void* d_out_all, void* compute_stream, void* swap_in_stream, void* swap_out_stream);
+/* Waits for the moves in flight and completes them in the table. */
+int pie_layer_pool_settle_sync(pie_layer_pool* lp);
+/* Where a logical layer's image is now: *out_where = PIE_WHERE_*, *out_ptr its device or host address.
+ * PIE_ESTATE while the layer is in flight. */
+int pie_layer_pool_address(pie_layer_pool* lp, int32_t layer, int32_t* out_where, void** out_ptr);
+int pie_layer_pool_table(pie_layer_pool* lp, pie_layer_entry* out);
+int pie_layer_pool_stats(pie_layer_pool* lp, pie_layer_stats* out);
+
 /* ---- diagnostics -------------------------------------------------------------- */
 int pie_last_hip_error(void);            /* hipError_t of the last PIE_EHIP on this thread, 0 if none */
 const char* pie_strerror(int code);      /* static string for a PIE_* code */

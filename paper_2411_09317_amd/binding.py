@@ -33,6 +33,10 @@ SYMBOLS = [
     "pie_check_errors_sync", "pie_controller_create", "pie_controller_destroy", "pie_controller_config",
     "pie_controller_observe", "pie_controller_level", "pie_controller_update", "pie_last_hip_error", "pie_strerror",
     "pie_version",
+    "pie_layer_sched_create", "pie_layer_sched_destroy", "pie_layer_sched_complete", "pie_layer_sched_present",
+    "pie_layer_sched_policy", "pie_layer_sched_table", "pie_layer_pool_bytes_required", "pie_layer_pool_create",
+    "pie_layer_pool_destroy", "pie_layer_step", "pie_layer_pool_settle_sync", "pie_layer_pool_address",
+    "pie_layer_pool_table", "pie_layer_pool_stats",
 ]
 
 
@@ -319,6 +323,128 @@ class Controller:
     def close(self):
         if self._h:
             _lib.pie_controller_destroy(self._h)
+            self._h = C.c_void_p(0)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+# ---- layer-granular swapping ----------------------------------------------------------------------------
+
+LAYER_GPU, LAYER_HOST, LAYER_MOVING_OUT, LAYER_MOVING_IN = 0, 1, 2, 3
+WAIT_NONE, WAIT_IN, WAIT_OUT = 0, 1, 2
+SKIP_NOT, SKIP_BUSY, SKIP_NO_SLOT, SKIP_COLDER_ON_HOST, SKIP_NONE = 0, 1, 2, 3, 4
+
+
+class LayerEntry(C.Structure):
+    _fields_ = [("state", C.c_int32), ("gpu_slot", C.c_int32), ("host_slot", C.c_int32)]
+
+
+class LayerAction(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("wait", "gpu_slot", "in_layer", "in_gpu_slot", "in_host_slot", "out_layer",
+                                         "out_gpu_slot", "out_host_slot", "forced_in", "out_skipped", "in_skipped")]
+
+
+class LayerStats(C.Structure):
+    _fields_ = [("n_steps", C.c_int64), ("n_swap_in", C.c_int64), ("n_swap_out", C.c_int64),
+                ("n_forced_in", C.c_int64), ("bytes_in", C.c_uint64), ("bytes_out", C.c_uint64),
+                ("stall_ms", C.c_double)]
+
+
+class LayerSched:
+    """The layer-granular swapping protocol as pure host logic (no GPU)."""
+
+    def __init__(self, n_layers: int, n_gpu_slots: int, n_host_slots: int, on_host: Sequence[int]):
+        self._h = C.c_void_p(0)
+        self.n_layers = n_layers
+        oh = _i32(on_host)
+        _check(_lib.pie_layer_sched_create(C.c_int32(n_layers), C.c_int32(n_gpu_slots), C.c_int32(n_host_slots),
+                                           C.c_int32(len(oh)), _ptr(oh), C.byref(self._h)), "layer_sched_create")
+
+    def complete(self, which: int):
+        _check(_lib.pie_layer_sched_complete(self._h, C.c_int32(which)), "layer_sched_complete")
+
+    def present(self, layer: int) -> LayerAction:
+        a = LayerAction()
+        _check(_lib.pie_layer_sched_present(self._h, C.c_int32(layer), C.byref(a)), "layer_sched_present")
+        return a
+
+    def policy(self, layer: int) -> LayerAction:
+        a = LayerAction()
+        _check(_lib.pie_layer_sched_policy(self._h, C.c_int32(layer), C.byref(a)), "layer_sched_policy")
+        return a
+
+    def table(self) -> List[Tuple[int, int, int]]:
+        arr = (LayerEntry * self.n_layers)()
+        _check(_lib.pie_layer_sched_table(self._h, arr), "layer_sched_table")
+        return [(e.state, e.gpu_slot, e.host_slot) for e in arr]
+
+    def close(self):
+        if self._h:
+            _lib.pie_layer_sched_destroy(self._h)
+            self._h = C.c_void_p(0)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class LayerPool:
+    """Logical layers over a Pool of GPU layer slots plus a pinned array of CPU layer slots."""
+
+    def __init__(self, pool: Pool, n_layers: int, n_host_slots: int, on_host: Sequence[int]):
+        import torch
+        self.pool = pool
+        self.n_layers = n_layers
+        self._h = C.c_void_p(0)
+        hb = C.c_size_t(0)
+        _check(_lib.pie_layer_pool_bytes_required(pool._h, C.c_int32(n_host_slots), C.byref(hb)), "layer_pool_bytes")
+        self.layer_bytes = pool.cfg.n_gpu_blocks * pool.block_bytes
+        self.h_buf = torch.empty(max(hb.value, 1), dtype=torch.uint8, pin_memory=True)
+        oh = _i32(on_host)
+        _check(_lib.pie_layer_pool_create(pool._h, C.c_int32(n_layers), C.c_int32(n_host_slots),
+                                          C.c_void_p(self.h_buf.data_ptr()), C.c_size_t(hb.value), C.c_int32(len(oh)),
+                                          _ptr(oh), C.byref(self._h)), "layer_pool_create")
+
+    def step(self, q_all, k_new, v_new, block_table, ctx_lens, out_all, compute_stream=None, swap_in_stream=None,
+             swap_out_stream=None):
+        _check(_lib.pie_layer_step(self._h, _dptr(q_all), _dptr(k_new), _dptr(v_new), _dptr(block_table),
+                                   C.c_int32(block_table.shape[1]), _dptr(ctx_lens), C.c_int32(ctx_lens.shape[0]),
+                                   _dptr(out_all), _stream_ptr(compute_stream), _stream_ptr(swap_in_stream),
+                                   _stream_ptr(swap_out_stream)), "layer_step")
+
+    def settle(self):
+        _check(_lib.pie_layer_pool_settle_sync(self._h), "layer_pool_settle")
+
+    def table(self) -> List[Tuple[int, int, int]]:
+        arr = (LayerEntry * self.n_layers)()
+        _check(_lib.pie_layer_pool_table(self._h, arr), "layer_pool_table")
+        return [(e.state, e.gpu_slot, e.host_slot) for e in arr]
+
+    def layer_image(self, layer: int):
+        """uint8 torch tensor [n_gpu_blocks][block_bytes] aliasing the logical layer's image where it is now."""
+        where, ptr = C.c_int32(0), C.c_void_p(0)
+        _check(_lib.pie_layer_pool_address(self._h, C.c_int32(layer), C.byref(where), C.byref(ptr)), "layer_pool_address")
+        if where.value == GPU:
+            off = ptr.value - self.pool._d_base
+            return self.pool.d_buf[self.pool._d_off + off: self.pool._d_off + off + self.layer_bytes].view(
+                self.pool.cfg.n_gpu_blocks, self.pool.block_bytes)
+        off = ptr.value - self.h_buf.data_ptr()
+        return self.h_buf[off: off + self.layer_bytes].view(self.pool.cfg.n_gpu_blocks, self.pool.block_bytes)
+
+    def stats(self) -> LayerStats:
+        s = LayerStats()
+        _check(_lib.pie_layer_pool_stats(self._h, C.byref(s)), "layer_pool_stats")
+        return s
+
+    def close(self):
+        if self._h:
+            _lib.pie_layer_pool_destroy(self._h)
             self._h = C.c_void_p(0)
 
     def __del__(self):

@@ -1079,7 +1079,8 @@ static int launch_f32(const AttnArgs& a, int32_t batch, int32_t n_q_heads, int32
 // Needs launch_attn_plan and launch_attn_resolve (for region layer & 1) earlier on the same stream, with the
 // same batch, table width and context lengths.
 int launch_attn_decode(const pie_pool* p, int32_t layer, const void* d_q, int32_t max_blocks, const int32_t* d_ctx,
-                       int32_t batch, void* d_out, hipStream_t s, hipEvent_t k_start, hipEvent_t k_end) {
+                       int32_t batch, void* d_out, hipStream_t s, hipEvent_t k_start, hipEvent_t k_end,
+                       int32_t ticket_index) {
   const pie_config& c = p->cfg;
   if (((uintptr_t)d_q | (uintptr_t)d_out) % 16) return PIE_EINVAL;
   if (max_blocks <= 0) return PIE_EINVAL;
@@ -1095,7 +1096,10 @@ int launch_attn_decode(const pie_pool* p, int32_t layer, const void* d_q, int32_
   a.slots = plan_slots(p, layer & 1);
   a.items = plan_items(p);
   a.hdr = plan_hdr(p);
-  a.counter = plan_counters(p) + layer;
+  // one ticket counter per launch since the last planning kernel (by default the layer's)
+  if (ticket_index < 0) ticket_index = layer;
+  if (ticket_index >= c.n_layers) return PIE_EINVAL;
+  a.counter = plan_counters(p) + ticket_index;
   a.q = (const char*)d_q;
   a.out = (char*)d_out;
   a.ws = p->d_ws;
