@@ -51,6 +51,9 @@ def parse():
     ap.add_argument("--adaptive-steps", type=int, default=0,
                     help="run the adaptive-expansion controller from f = 0 for this many decode steps; adds 'adaptive'")
     ap.add_argument("--adaptive-units", type=int, default=0, help="controller levels per 100 %% (default 8 x layers)")
+    ap.add_argument("--layer-fifo", type=int, default=0,
+                    help="also run the paper's layer-granular protocol with this many layers starting in CPU memory "
+                         "(GPU layer slots = layers - m, CPU slots = m + 2); adds 'layer_fifo'")
     ap.add_argument("--t-other-us", type=float, default=0.0,
                     help="experiments only: keep the compute stream busy this long after each layer's attention, standing "
                          "for the rest of a transformer layer (default 0 = the measured path)")
@@ -160,6 +163,52 @@ def adaptive_leg(w, dw, streams, n_steps, units, k_max):
     return {"units": units, "k_max": k_max, "steps": n_steps, "final_level": k, "ceiling": ceiling,
             "final_host_fraction": k / units, "level_min_second_half": min(tail), "level_max_second_half": max(tail),
             "levels": levels, "ms_per_step_last": traj[-1][1]}
+
+
+def layer_fifo_leg(w, dw, m, n_steps, t_other_us, base_step_ms):
+    """The paper's own unit: whole layers move.  n - m GPU layer slots, m + 2 CPU layer slots, the last m
+    layers start in CPU memory.  Content is random (only timing is measured here; parity is in the tests)."""
+    import torch
+    from paper_2411_09317_amd import binding as B
+    n = w.n_layers
+    inner = B.Pool(n - m, w.n_q_heads, w.n_kv_heads, w.head_dim, w.block_tokens, w.dtype, dw.total_blocks + 64, 0, 0,
+                   max_batch=w.batch, max_blocks_per_seq=dw.table.shape[1])
+    hs = np.asarray(inner.block_alloc(B.GPU, dw.total_blocks), dtype=np.int32)
+    table = np.full_like(dw.table, -1)
+    table[dw.table >= 0] = hs                                  # same shape of table, this pool's handles
+    inner.gpu_image().view(torch.int16).copy_(dw.pool.gpu_image()[: n - m, : inner.n_slots].view(torch.int16))
+    lp = B.LayerPool(inner, n, m + 2, list(range(n - m, n)))
+    for l in range(n - m, n):
+        lp.layer_image(l).copy_(dw.pool.gpu_image()[l, : inner.n_slots])
+    if t_other_us:
+        inner.set_layer_compute_us(t_other_us)
+    d_table = torch.from_numpy(table).to(dw.q.device)
+    streams = (torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream())
+    out = torch.empty_like(dw.q)
+    def run(k):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(k):
+            lp.step(dw.q, dw.k_new, dw.v_new, d_table, dw.d_ctx, out, *streams)
+        inner.sync()
+        return time.perf_counter() - t0
+    run(1)
+    s0 = lp.stats()
+    dt = run(n_steps)
+    s1 = lp.stats()
+    assert inner.check_errors() == 0
+    res = {"layers_on_cpu": m, "gpu_layer_slots": n - m, "cpu_layer_slots": m + 2, "expansion_simple": n / (n - m),
+           "expansion_buffered": (n + 4) / (n - m + 2), "layer_MB": lp.layer_bytes / 1e6,
+           "tokens_per_s": w.batch * n_steps / dt, "ms_per_step": dt / n_steps * 1e3,
+           "inflation_e2e": dt / n_steps * 1e3 / base_step_ms - 1.0,
+           "swap_ins_per_step": (s1.n_swap_in - s0.n_swap_in) / n_steps,
+           "swap_outs_per_step": (s1.n_swap_out - s0.n_swap_out) / n_steps,
+           "forced_ins_per_step": (s1.n_forced_in - s0.n_forced_in) / n_steps,
+           "host_wait_ms_per_step": (s1.stall_ms - s0.stall_ms) / n_steps,
+           "link_GBps_in": (s1.bytes_in - s0.bytes_in) / dt / 1e9, "link_GBps_out": (s1.bytes_out - s0.bytes_out) / dt / 1e9}
+    lp.close()
+    inner.close()
+    return res
 
 
 def traffic_from_profile(name):
@@ -319,6 +368,8 @@ def main():
     if args.sweep:
         result["sweep"] = [fixed_fraction_leg(w, dw, streams, float(f), args.swap_steps, base_kernel_ms, base_step_ms,
                                               achieved) for f in args.sweep.split(",")]
+    if args.layer_fifo:
+        result["layer_fifo"] = layer_fifo_leg(w, dw, args.layer_fifo, args.swap_steps, args.t_other_us, base_step_ms)
     if args.adaptive_steps:
         units = args.adaptive_units or 8 * w.n_layers
         k_max = int(host_cap * units)
