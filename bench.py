@@ -73,6 +73,34 @@ def timed_steps(dw, streams, n, pf, dirty):
     return time.perf_counter() - t0
 
 
+def step_distribution(dw, streams, n, pf, dirty):
+    """p10 / p50 / p90 of single steps, each bracketed by a synchronisation (ms)."""
+    import torch
+    ts = []
+    for _ in range(n):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        dw.pool.step(dw.q, dw.k_new, dw.v_new, dw.d_table, dw.d_ctx, pf, dirty, dw.out, *streams)
+        dw.pool.sync()
+        ts.append((time.perf_counter() - t0) * 1e3)
+    return [float(np.percentile(ts, q)) for q in (10, 50, 90)]
+
+
+def measured_link_peak(mib=512):
+    """One large pinned-host to device copy: the link's measured large-transfer rate (GB/s)."""
+    import torch
+    src = torch.empty(mib << 20, dtype=torch.uint8, pin_memory=True)
+    dst = torch.empty(mib << 20, dtype=torch.uint8, device="cuda:0")
+    best = 0.0
+    for _ in range(3):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        dst.copy_(src, non_blocking=True)
+        torch.cuda.synchronize()
+        best = max(best, (mib << 20) / (time.perf_counter() - t0) / 1e9)
+    return best
+
+
 def layer_profile(dw, streams, pf, dirty, reps=3):
     """Per-layer event times (ms), median over a few timed steps."""
     acc = {}
@@ -317,6 +345,7 @@ def main():
     ms_per_step = total_s / args.steps * 1e3
     tokens_per_s = w.batch / (total_s / args.steps)
     prof = layer_profile(dw, streams, none, none)
+    p10, p50, p90 = step_distribution(dw, streams, min(args.steps, 20), none, none)
     assert dw.pool.check_errors() == 0
     k_ms = float(np.mean(prof["kernel"]))
     bytes_layer = dw.kv_bytes_per_layer
@@ -338,7 +367,8 @@ def main():
                      "traffic": traffic_from_profile(f"attn_decode_{w.name}_pmc.txt"),
                      "kernel_ms": k_ms, "algorithmic_bytes_per_launch": bytes_layer},
         "per_layer_ms": {"attn_total": float(np.mean(prof["attn"])), "attn_kernel": k_ms,
-                         "step_ms_events": prof["step_ms"]},
+                         "step_ms_events": prof["step_ms"],
+                         "single_step_ms_p10_p50_p90": [p10, p50, p90]},
     }
     base_kernel_ms = prof["kernel"].copy()
     base_step_ms = ms_per_step
@@ -360,7 +390,8 @@ def main():
         sp = layer_profile(dw, streams, pf, dirty, reps=2)
         assert dw.pool.check_errors() == 0
         result["swap"] = leg_metrics(w, dw, sp, s_total / args.swap_steps, base_kernel_ms, base_step_ms, achieved)
-        result["swap"].update({"migrate_s": round(t_mig, 2), "swap_path": args.swap_path})
+        result["swap"].update({"migrate_s": round(t_mig, 2), "swap_path": args.swap_path,
+                               "host_link_measured_peak_GBps": measured_link_peak()})
         dw.pool.migrate(hs, B.GPU, streams[1])
         dw.pool.sync()
 

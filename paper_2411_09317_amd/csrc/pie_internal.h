@@ -101,7 +101,6 @@ struct pie_pool {
   // options
   int32_t swap_path = PIE_SWAP_AUTO;
   int32_t attn_partition = 512;   // tokens per work item (one workgroup)
-  bool attn_nontemporal = true;   // non-temporal K/V loads in the attention kernel
   int32_t swap_wgs = 64;          // workgroups of the gather / scatter kernel
   float layer_compute_us = 0.f;   // stand-in for the rest of a layer's compute in pie_step (0 = none)
   int32_t wall_clock_khz = 100000;

@@ -379,7 +379,6 @@ int pie_pool_init(const pie_config* cfg, void* d_base, size_t d_bytes, void* h_p
   }
   p->h_kv = (char*)h_pinned_base;
   // tuning hooks for experiments; the defaults are what the benchmarks use
-  if (const char* e = std::getenv("PIE_ATTN_NT")) p->attn_nontemporal = std::atoi(e) != 0;
   if (const char* e = std::getenv("PIE_ATTN_PART")) { const int v = std::atoi(e); if (v > 0) p->attn_partition = v; }
   if (device) {
     char* base = (char*)d_base;
