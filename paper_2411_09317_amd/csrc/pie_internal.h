@@ -94,8 +94,9 @@ struct pie_pool {
   hipEvent_t ev_out[2] = {nullptr, nullptr};      // last write-back from region r
   hipEvent_t ev_compute = nullptr;                // last compute work
   hipEvent_t ev_migrate = nullptr;                // last migration
+  hipEvent_t ev_map = nullptr;                    // last map update sent on the compute stream
   bool ev_in_rec[2] = {false, false}, ev_read_rec[2] = {false, false}, ev_out_rec[2] = {false, false};
-  bool ev_compute_rec = false, ev_migrate_rec = false, migrate_pending = false;
+  bool ev_compute_rec = false, ev_migrate_rec = false, ev_map_rec = false, migrate_pending = false;
   std::vector<hipStream_t> streams_seen;
 
   // options
@@ -137,9 +138,14 @@ int launch_map_patch(int32_t* d_map, const MapPatch& patch, hipStream_t s);
 int launch_zero_u32(uint32_t* d, int32_t n, hipStream_t s);
 int launch_swap_copy(char* dst_layer_base, const char* src_layer_base, size_t block_bytes, const SwapPairs& pairs,
                      int n_wgs, hipStream_t s);
+// which tail blocks an append launch writes (a tail block is GPU-homed, staged for the layer, or neither)
+constexpr int32_t kAppendPresent = 0;     // GPU-homed or staged; neither raises NOT_PRESENT
+constexpr int32_t kAppendGpuStrict = 1;   // GPU-homed; anything else raises NOT_PRESENT (the layer's region is not valid)
+constexpr int32_t kAppendGpuHomed = 2;    // GPU-homed; host-homed tails are left to a kAppendStaged launch
+constexpr int32_t kAppendStaged = 3;      // staged copies only; GPU-homed tails were written before
 int launch_kv_append(const pie_pool* p, int32_t layer, int32_t n_layers, const void* d_k, const void* d_v,
                      const int32_t* d_table, int32_t max_blocks, const int32_t* d_ctx, int32_t batch,
-                     bool stage_valid, hipStream_t s);
+                     int32_t mode, hipStream_t s);
 int launch_attn_plan(const pie_pool* p, const int32_t* d_ctx, int32_t batch, int32_t max_blocks, hipStream_t s);
 int launch_attn_resolve(const pie_pool* p, const int32_t* d_table, const int32_t* d_ctx, int32_t batch,
                         int32_t max_blocks, bool region0, bool valid0, bool region1, bool valid1, hipStream_t s);

@@ -207,7 +207,7 @@ struct AppendArgs {
   size_t kv_layer_stride;    // blockIdx.y walks layers: bytes between layers in the pool ...
   size_t new_layer_stride;   // ... and in k_new / v_new
   int32_t max_blocks, n_handles, n_gpu_blocks, n_slots, n_kv_heads, head_dim, block_tokens, elem_bytes;
-  int32_t stage_valid;
+  int32_t mode;              // kAppend*: which tail blocks this launch writes
 };
 
 __global__ __launch_bounds__(256) void k_kv_append(const AppendArgs a) {
@@ -221,9 +221,27 @@ __global__ __launch_bounds__(256) void k_kv_append(const AppendArgs a) {
     return;
   }
   __shared__ int32_t s_slot;
-  if (threadIdx.x == 0)
-    s_slot = resolve_slot(a.table[(size_t)b * a.max_blocks + j], a.map, a.n_handles, a.n_gpu_blocks, a.n_slots,
-                          a.stage_valid != 0, a.err);
+  if (threadIdx.x == 0) {
+    int32_t slot = -1;
+    const int32_t handle = a.table[(size_t)b * a.max_blocks + j];
+    if (handle < 0 || handle >= a.n_handles) {
+      atomicOr(a.err, PIE_DEVERR_BAD_HANDLE);
+    } else {
+      slot = a.map[handle];
+      const bool gpu_homed = slot >= 0 && slot < a.n_gpu_blocks;
+      const bool staged = slot >= a.n_gpu_blocks && slot < a.n_slots;
+      bool take = false, missing = false;
+      switch (a.mode) {
+        case kAppendPresent: take = gpu_homed || staged; missing = !take; break;
+        case kAppendGpuStrict: take = gpu_homed; missing = !take; break;
+        case kAppendGpuHomed: take = gpu_homed; missing = !gpu_homed && !staged && slot != -1; break;
+        default: take = staged; missing = !gpu_homed && !staged; break;                    // kAppendStaged
+      }
+      if (missing) atomicOr(a.err, PIE_DEVERR_NOT_PRESENT);
+      if (!take) slot = -1;
+    }
+    s_slot = slot;
+  }
   __syncthreads();
   const int32_t slot = s_slot;
   if (slot < 0) return;
@@ -256,13 +274,13 @@ __global__ __launch_bounds__(256) void k_kv_append(const AppendArgs a) {
   }
 }
 
-// Appends for n_layers consecutive layers starting at `layer` in one launch.  With n_layers > 1 every
-// sequence's tail block must be GPU-homed (stage_valid is false: a host-homed tail raises NOT_PRESENT).
+// Appends for n_layers consecutive layers starting at `layer` in one launch.  With n_layers > 1 only modes
+// that leave staged copies alone make sense (staging regions hold one layer each).
 int launch_kv_append(const pie_pool* p, int32_t layer, int32_t n_layers, const void* d_k, const void* d_v,
                      const int32_t* d_table, int32_t max_blocks, const int32_t* d_ctx, int32_t batch,
-                     bool stage_valid, hipStream_t s) {
+                     int32_t mode, hipStream_t s) {
   if (((uintptr_t)d_k | (uintptr_t)d_v) % 16) return PIE_EINVAL;
-  if (n_layers < 1 || (n_layers > 1 && stage_valid)) return PIE_EINVAL;
+  if (n_layers < 1 || (n_layers > 1 && (mode == kAppendPresent || mode == kAppendStaged))) return PIE_EINVAL;
   AppendArgs a;
   a.kv_layer = p->d_kv + (size_t)layer * p->d_layer_stride;
   a.map = p->d_map[layer & 1];
@@ -282,7 +300,7 @@ int launch_kv_append(const pie_pool* p, int32_t layer, int32_t n_layers, const v
   a.head_dim = p->cfg.head_dim;
   a.block_tokens = p->cfg.block_tokens;
   a.elem_bytes = p->elem_bytes;
-  a.stage_valid = stage_valid ? 1 : 0;
+  a.mode = mode;
   hipLaunchKernelGGL(k_kv_append, dim3(batch, n_layers), dim3(256), 0, s, a);
   PIE_HIP(hipGetLastError());
   return PIE_OK;

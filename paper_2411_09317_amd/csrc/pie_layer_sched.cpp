@@ -434,7 +434,7 @@ int pie_layer_step(pie_layer_pool* lp, const void* d_q_all, const void* d_k_new,
     const int32_t slot = act.gpu_slot;
     if (d_k_new) {
       if ((rc = pie::launch_kv_append(p, slot, 1, (const char*)d_k_new + k * kv_stride, (const char*)d_v_new + k * kv_stride,
-                                      d_block_table, max_blocks, d_ctx_lens, batch, false, cs)))
+                                      d_block_table, max_blocks, d_ctx_lens, batch, pie::kAppendGpuStrict, cs)))
         return rc;
     }
     if ((rc = pie::launch_attn_decode(p, slot, (const char*)d_q_all + k * q_stride, max_blocks, d_ctx_lens, batch,

@@ -231,8 +231,18 @@ static void publish_stage_list(pie_pool* p, int r, int32_t n, const int32_t* han
   }
 }
 
+// The new token's rows for the tail blocks that a prefetch brings in: written into the staged copies on the
+// swap stream right behind the copy, so that the compute stream does not have to.
+struct StagedAppend {
+  const void* d_k;
+  const void* d_v;
+  const int32_t* d_table;
+  const int32_t* d_ctx;
+  int32_t max_blocks, batch;
+};
+
 static int swap_in_impl(pie_pool* p, int32_t layer, int32_t n, const int32_t* handles, hipStream_t s,
-                        bool validated, hipEvent_t t0, hipEvent_t t1) {
+                        bool validated, hipEvent_t t0, hipEvent_t t1, const StagedAppend* job = nullptr) {
   const int r = layer & 1;
   if (!validated) {
     if (layer < 0 || layer >= p->cfg.n_layers) return PIE_EINVAL;
@@ -258,9 +268,13 @@ static int swap_in_impl(pie_pool* p, int32_t layer, int32_t n, const int32_t* ha
   if ((rc = order_after(s, p->ev_read[r], p->ev_read_rec[r], on_host))) return rc;
   if ((rc = order_after(s, p->ev_out[r], p->ev_out_rec[r], on_host))) return rc;
   if ((rc = order_after(s, p->ev_migrate, p->ev_migrate_rec, on_host))) return rc;
+  if (job && (rc = order_after(s, p->ev_map, p->ev_map_rec, on_host))) return rc;   // the append reads the map
   if (t0) PIE_HIP(hipEventRecord(t0, s));
   if ((rc = copy_blocks(p, 0, layer, src, dst, cp, s))) return rc;
   if (t1) PIE_HIP(hipEventRecord(t1, s));
+  if (job && (rc = launch_kv_append(p, layer, 1, job->d_k, job->d_v, job->d_table, job->max_blocks, job->d_ctx,
+                                    job->batch, kAppendStaged, s)))
+    return rc;
   // phase two happens when this event completes
   PIE_HIP(hipEventRecord(p->ev_in[r], s));
   p->ev_in_rec[r] = true;
@@ -411,7 +425,7 @@ int pie_pool_init(const pie_config* cfg, void* d_base, size_t d_bytes, void* h_p
       p->h_kv_dev = (char*)dev_ptr;
     }
     hipEvent_t* evs[] = {&p->ev_in[0], &p->ev_in[1], &p->ev_read[0], &p->ev_read[1], &p->ev_out[0], &p->ev_out[1],
-                         &p->ev_compute, &p->ev_migrate};
+                         &p->ev_compute, &p->ev_migrate, &p->ev_map};
     for (hipEvent_t* e : evs) {
       hipError_t err = hipEventCreateWithFlags(e, hipEventDisableTiming);
       if (err != hipSuccess) { g_last_hip_error = (int)err; (void)hipGetLastError(); return fail(PIE_EHIP); }
@@ -451,7 +465,7 @@ int pie_pool_destroy(pie_pool* p) {
   if (p->device) {
     for (hipStream_t s : p->streams_seen) (void)hipStreamSynchronize(s);
     hipEvent_t evs[] = {p->ev_in[0], p->ev_in[1], p->ev_read[0], p->ev_read[1], p->ev_out[0], p->ev_out[1],
-                        p->ev_compute, p->ev_migrate, p->ev_step_start};
+                        p->ev_compute, p->ev_migrate, p->ev_map, p->ev_step_start};
     for (hipEvent_t e : evs)
       if (e) (void)hipEventDestroy(e);
     for (auto& le : p->lev) {
@@ -676,7 +690,8 @@ int pie_kv_append(pie_pool* p, int32_t layer, const void* d_k, const void* d_v, 
   hipStream_t s = (hipStream_t)stream;
   bool stage_valid = false;
   if ((rc = compute_prologue(p, layer, s, &stage_valid))) return rc;
-  if ((rc = launch_kv_append(p, layer, 1, d_k, d_v, d_block_table, max_blocks, d_ctx_lens, batch, stage_valid, s)))
+  if ((rc = launch_kv_append(p, layer, 1, d_k, d_v, d_block_table, max_blocks, d_ctx_lens, batch,
+                             stage_valid ? kAppendPresent : kAppendGpuStrict, s)))
     return rc;
   return compute_epilogue(p, layer, s);
 }
@@ -779,31 +794,37 @@ int pie_step(pie_pool* p, const void* d_q_all, const void* d_k_new, const void* 
   if ((rc = launch_attn_plan(p, d_ctx_lens, batch, max_blocks, cs))) return rc;
   if ((rc = launch_attn_resolve(p, d_block_table, d_ctx_lens, batch, max_blocks, true, true, L > 1, true, cs)))
     return rc;
-  // When no tail block is host-homed, the new token's rows of every layer go in with one launch up front;
-  // otherwise a layer's append has to wait for that layer's staged blocks.
-  const bool append_up_front = d_k_new && n_dirty == 0;
-  if (append_up_front) {
-    if ((rc = launch_kv_append(p, 0, L, d_k_new, d_v_new, d_block_table, max_blocks, d_ctx_lens, batch, false, cs)))
+  // The new token's rows of every layer go into the GPU-homed tail blocks with one launch up front.  The
+  // tails that are host-homed get theirs on the swap stream, behind the copy that stages them for a layer.
+  const bool staged_tails = d_k_new && n_dirty > 0;
+  if (d_k_new) {
+    if ((rc = launch_kv_append(p, 0, L, d_k_new, d_v_new, d_block_table, max_blocks, d_ctx_lens, batch,
+                               staged_tails ? kAppendGpuHomed : kAppendGpuStrict, cs)))
       return rc;
+  }
+  StagedAppend job{nullptr, nullptr, d_block_table, d_ctx_lens, max_blocks, batch};
+  auto job_for = [&](int32_t l) -> const StagedAppend* {
+    if (!staged_tails) return nullptr;
+    job.d_k = (const char*)d_k_new + l * kv_stride;
+    job.d_v = (const char*)d_v_new + l * kv_stride;
+    return &job;
+  };
+  if (staged_tails) {                            // the swap stream's appends read the maps sent above
+    PIE_HIP(hipEventRecord(p->ev_map, cs));
+    p->ev_map_rec = true;
   }
   // layer 0's blocks have no earlier layer to hide behind
   if (n_prefetch > 0) {
     if ((rc = swap_in_impl(p, 0, n_prefetch, h_prefetch, is, true, timed ? p->lev[0].in_start : nullptr,
-                           timed ? p->lev[0].in_end : nullptr)))
+                           timed ? p->lev[0].in_end : nullptr, job_for(0))))
       return rc;
     p->lev[0].in_used = timed;
   }
   for (int32_t l = 0; l < L; ++l) {
-    bool stage_valid = false;
-    if (n_prefetch > 0) {
-      if ((rc = compute_prologue(p, l, cs, &stage_valid))) return rc;     // the presence check
-    }
+    // the presence check: the layer's staged blocks have arrived (migrations and map updates were waited
+    // for and sent once, at the start of the step)
+    if (n_prefetch > 0 && (rc = wait_if(cs, p->ev_in[l & 1], p->ev_in_rec[l & 1]))) return rc;
     if (timed) PIE_HIP(hipEventRecord(p->lev[l].attn_start, cs));
-    if (d_k_new && !append_up_front) {
-      if ((rc = launch_kv_append(p, l, 1, (const char*)d_k_new + l * kv_stride, (const char*)d_v_new + l * kv_stride,
-                                 d_block_table, max_blocks, d_ctx_lens, batch, stage_valid, cs)))
-        return rc;
-    }
     if ((rc = launch_attn_decode(p, l, (const char*)d_q_all + l * q_stride, max_blocks, d_ctx_lens, batch,
                                  (char*)d_out_all + l * q_stride, cs, timed ? p->lev[l].k_start : nullptr,
                                  timed ? p->lev[l].k_end : nullptr)))
@@ -821,7 +842,7 @@ int pie_step(pie_pool* p, const void* d_q_all, const void* d_k_new, const void* 
       // transfer makes the host wait for layer l - 1 here (see order_after): the compute stream must
       // already hold this layer's work then.
       if ((rc = swap_in_impl(p, l + 1, n_prefetch, h_prefetch, is, true, timed ? p->lev[l + 1].in_start : nullptr,
-                             timed ? p->lev[l + 1].in_end : nullptr)))
+                             timed ? p->lev[l + 1].in_end : nullptr, job_for(l + 1))))
         return rc;
       p->lev[l + 1].in_used = timed;
     }
