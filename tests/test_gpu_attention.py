@@ -229,3 +229,28 @@ def test_argument_checks():
     with pytest.raises(B.PieError) as e:
         B.Pool(1, 4, 4, 96, 16, I.DTYPE_F16, 4, 2, 2, device=GH.DEV)     # unsupported head_dim
     assert e.value.code == B.EINVAL
+
+
+def test_batch_at_the_planning_limit_and_contexts_on_partition_edges():
+    """4096 sequences (the most the planning kernel lists), contexts that sit exactly on, one under and one over
+    block and partition boundaries."""
+    w = I.Workload("wide", 1, 4096, 2, 1, 64, I.DTYPE_F16, ctx_lo=1, ctx_hi=40, value_scale=1.0, seed=37)
+    case = I.make_case(w)
+    edges = [1, 15, 16, 17, 31, 32, 33, 40]
+    for b in range(w.batch):
+        case.ctx_lens[b] = min(edges[b % len(edges)], case.k_dense[b].shape[1])
+    case = _recase(case)
+    lib, mod, table = GH.make_pools(case, int(case.n_blocks.sum()) + 3, 2, 2, fill=H.nan_fill(w.dtype))
+    got = run_attn(lib, case, table)
+    check(got, A.dense_attention(*H.dense_f64(case, 0), case.ctx_lens), w.dtype)
+    lib.close()
+    w = I.Workload("edges", 1, 9, 4, 2, 128, I.DTYPE_BF16, ctx_lo=1100, ctx_hi=1100, value_scale=0.5, seed=38)
+    case = I.make_case(w)
+    for b, c in enumerate([255, 256, 257, 511, 512, 513, 1023, 1024, 1025]):
+        case.ctx_lens[b] = c
+    case = _recase(case)
+    lib, mod, table = GH.make_pools(case, int(case.n_blocks.sum()), 2, 2, fill=H.nan_fill(w.dtype))
+    for part in (256, 512):
+        lib.set_attn_partition(part)
+        check(run_attn(lib, case, table), A.dense_attention(*H.dense_f64(case, 0), case.ctx_lens), w.dtype)
+    lib.close()
