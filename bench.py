@@ -348,6 +348,8 @@ def main():
     p10, p50, p90 = step_distribution(dw, streams, min(args.steps, 20), none, none)
     assert dw.pool.check_errors() == 0
     k_ms = float(np.mean(prof["kernel"]))
+    probe_ms = float(np.mean([dw.pool.attn_stream_probe(l % w.n_layers, dw.d_table, dw.d_ctx, streams[0])
+                              for l in range(2 * min(w.n_layers, 8))][2:]))
     bytes_layer = dw.kv_bytes_per_layer
     achieved = bytes_layer / (k_ms * 1e-3) / 1e9
     elem = {0: "f32", 1: "f16", 2: "bf16"}[w.dtype]
@@ -365,7 +367,9 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "k_attn_decode_mfma", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic_from_profile(f"attn_decode_{w.name}_pmc.txt"),
-                     "kernel_ms": k_ms, "algorithmic_bytes_per_launch": bytes_layer},
+                     "kernel_ms": k_ms, "algorithmic_bytes_per_launch": bytes_layer,
+                     "stream_probe_ms": probe_ms, "stream_probe_GBps": bytes_layer / (probe_ms * 1e-3) / 1e9,
+                     "frac_of_stream_probe": probe_ms / k_ms},
         "per_layer_ms": {"attn_total": float(np.mean(prof["attn"])), "attn_kernel": k_ms,
                          "step_ms_events": prof["step_ms"],
                          "single_step_ms_p10_p50_p90": [p10, p50, p90]},

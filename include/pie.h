@@ -223,6 +223,13 @@ int pie_attn_decode(pie_pool* pool, int32_t layer, const void* d_q,
                     const int32_t* d_ctx_lens, int32_t batch,
                     void* d_out, void* stream);
 
+/* Calibration for the roofline of pie_attn_decode: reads exactly the K and V tiles that pie_attn_decode would
+ * read for this layer, batch and table - same work items, same order, same loads - and discards them.
+ * Waits for it and returns the kernel's duration in *out_ms (events around the launch on `stream`): the rate
+ * at which this access pattern can stream from HBM at all. */
+int pie_attn_stream_probe_sync(pie_pool* pool, int32_t layer, const int32_t* d_block_table, int32_t max_blocks,
+                               const int32_t* d_ctx_lens, int32_t batch, void* stream, float* out_ms);
+
 /* ---- the pipeline ---------------------------------------------------------- */
 
 /* One decode step over all layers.  h_prefetch: the n_prefetch host-homed handles this batch touches, in

@@ -152,6 +152,7 @@ int launch_attn_resolve(const pie_pool* p, const int32_t* d_table, const int32_t
 int launch_attn_decode(const pie_pool* p, int32_t layer, const void* d_q, int32_t max_blocks, const int32_t* d_ctx,
                        int32_t batch, void* d_out, hipStream_t s, hipEvent_t k_start = nullptr,
                        hipEvent_t k_end = nullptr, int32_t ticket_index = -1);
+int launch_stream_probe(const pie_pool* p, int32_t layer, int32_t max_blocks, int32_t batch, hipStream_t s);
 size_t attn_plan_ints(const pie_config& c);
 size_t attn_workspace_floats(const pie_config& c);
 bool attn_config_supported(const pie_config& c);

@@ -779,6 +779,63 @@ void k_attn_decode_mfma(const AttnArgs a) {
   }
 }
 
+// Calibration: reads exactly the K and V tiles the decode kernel reads for the planned items, in the same
+// order and with the same loads (units by ticket, wave w takes blocks w, w + kWaves, ..., two blocks in
+// flight), and does nothing with them but fold them into a word nobody looks at.  Its rate is what this
+// access pattern can stream at; the decode kernel is measured against it as well as against the HBM peak.
+template <int NL>                                 // 1 KiB loads per tile
+__global__ __launch_bounds__(kWaves * 64) void k_stream_probe(const AttnArgs a, size_t tile_bytes, uint32_t* sink) {
+  __shared__ uint32_t s_ticket;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const uint32_t n_kv = (uint32_t)a.n_kv_heads;
+  const uint32_t n_units = (uint32_t)a.hdr[0] * n_kv;
+  const size_t v_off = a.block_bytes / 2;
+  const int32_t bpi = a.part_tokens / kBlockTokens;
+  const int32_t my_n = (bpi + kWaves - 1 - wave) / kWaves;
+  u32x4 acc = {0, 0, 0, 0};
+  uint32_t unit = blockIdx.x;
+  while (unit < n_units) {                       // every workgroup ends on a ticket past the last unit
+    const uint32_t item = unit / n_kv;
+    const uint2 rec = a.items[item];
+    int32_t my_slot = -1;
+    if (lane < my_n) my_slot = a.slots[(size_t)item * bpi + wave + kWaves * lane];
+    const int32_t ctx_u = (int32_t)rec.y, tok0 = (int32_t)(rec.x >> 16) * a.part_tokens;
+    const int32_t tok1 = min(ctx_u, tok0 + a.part_tokens);
+    const int32_t jb1 = tok1 > 0 ? (tok1 + kBlockTokens - 1) / kBlockTokens : 0;
+    const int32_t n_it = (jb1 - tok0 / kBlockTokens - wave + kWaves - 1) / kWaves;
+    const size_t head_off = (size_t)(unit % n_kv) * tile_bytes + (size_t)lane * 16;
+    u32x4 ta[2 * NL], tb[2 * NL];
+    auto load = [&](u32x4 (&t)[2 * NL], int32_t it) {
+      int32_t slot = __shfl(my_slot, it, 64);
+      slot = slot < 0 ? 0 : slot;
+      const char* kp = a.kv_layer + (size_t)slot * a.block_bytes + head_off;
+#pragma unroll
+      for (int i = 0; i < NL; ++i) t[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kp + (size_t)i * 1024));
+#pragma unroll
+      for (int i = 0; i < NL; ++i)
+        t[NL + i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kp + v_off + (size_t)i * 1024));
+    };
+    auto fold = [&](u32x4 (&t)[2 * NL]) {
+#pragma unroll
+      for (int i = 0; i < 2 * NL; ++i) acc ^= t[i];
+    };
+    if (n_it > 0) load(ta, 0);
+    for (int32_t it = 0; it < n_it; it += 2) {
+      if (it + 1 < n_it) load(tb, it + 1);
+      fold(ta);
+      if (it + 1 < n_it) {
+        if (it + 2 < n_it) load(ta, it + 2);
+        fold(tb);
+      }
+    }
+    if (threadIdx.x == 0) s_ticket = gridDim.x + atomicAdd(a.counter, 1u);
+    __syncthreads();
+    unit = s_ticket;
+    __syncthreads();
+  }
+  if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9e3779b9u) *sink = 1;   // keeps the loads alive
+}
+
 // fp32 caches.  One workgroup per (item, query head); wave w takes blocks w, w + kWaves, ...  Lane
 // (quad, row) = (lane / 16, lane % 16): for K it holds token `row` of the block and the 4-dim vectors
 // 4 i + quad; for V it holds dim 16 n + row and the tokens 4 quad .. 4 quad + 3.
@@ -1144,6 +1201,33 @@ int launch_attn_decode(const pie_pool* p, int32_t layer, const void* d_q, int32_
                    : launch_mfma<BF16, 64, true>(p, a, batch, c.n_q_heads, s, k_start, k_end);
     default: return PIE_EINVAL;
   }
+}
+
+// The calibration kernel over the same planning state (launch_attn_plan and launch_attn_resolve first).
+int launch_stream_probe(const pie_pool* p, int32_t layer, int32_t max_blocks, int32_t batch, hipStream_t s) {
+  const pie_config& c = p->cfg;
+  if (max_blocks <= 0 || layer < 0 || layer >= c.n_layers) return PIE_EINVAL;
+  const int32_t part = part_tokens_of(p);
+  AttnArgs a = {};
+  a.kv_layer = p->d_kv + (size_t)layer * p->d_layer_stride;
+  a.slots = plan_slots(p, layer & 1);
+  a.items = plan_items(p);
+  a.hdr = plan_hdr(p);
+  a.counter = plan_counters(p) + layer;
+  a.block_bytes = p->block_bytes;
+  a.n_kv_heads = c.n_kv_heads;
+  a.part_tokens = part;
+  const size_t tile_bytes = (size_t)kBlockTokens * c.head_dim * p->elem_bytes;
+  uint32_t* sink = p->d_err + 1;                  // a spare word of the error page
+  const int grid = p->n_cu * 2;
+  switch (tile_bytes / 1024) {
+    case 2: hipLaunchKernelGGL((k_stream_probe<2>), dim3(grid), dim3(kWaves * 64), 0, s, a, tile_bytes, sink); break;
+    case 4: hipLaunchKernelGGL((k_stream_probe<4>), dim3(grid), dim3(kWaves * 64), 0, s, a, tile_bytes, sink); break;
+    case 8: hipLaunchKernelGGL((k_stream_probe<8>), dim3(grid), dim3(kWaves * 64), 0, s, a, tile_bytes, sink); break;
+    default: return PIE_EINVAL;
+  }
+  PIE_HIP(hipGetLastError());
+  return PIE_OK;
 }
 
 }  // namespace pie

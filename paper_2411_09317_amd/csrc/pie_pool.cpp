@@ -716,6 +716,32 @@ int pie_attn_decode(pie_pool* p, int32_t layer, const void* d_q, const int32_t* 
   return compute_epilogue(p, layer, s);
 }
 
+static int elapsed(hipEvent_t a, hipEvent_t b, float* ms);
+
+int pie_attn_stream_probe_sync(pie_pool* p, int32_t layer, const int32_t* d_block_table, int32_t max_blocks,
+                          const int32_t* d_ctx_lens, int32_t batch, void* stream, float* out_ms) {
+  if (!p || !out_ms) return PIE_EINVAL;
+  *out_ms = 0.f;
+  int rc = check_batch_args(p, layer, d_block_table, d_block_table, max_blocks, d_ctx_lens, batch);
+  if (rc) return rc;
+  if (!p->device) return PIE_ESTATE;
+  if (batch == 0) return PIE_OK;
+  hipStream_t s = (hipStream_t)stream;
+  bool stage_valid = false;
+  if ((rc = compute_prologue(p, layer, s, &stage_valid))) return rc;
+  const int r = layer & 1;
+  if ((rc = launch_attn_plan(p, d_ctx_lens, batch, max_blocks, s))) return rc;
+  if ((rc = launch_attn_resolve(p, d_block_table, d_ctx_lens, batch, max_blocks, r == 0, stage_valid, r == 1,
+                                stage_valid, s)))
+    return rc;
+  PIE_HIP(hipEventRecord(p->lev[layer].k_start, s));
+  if ((rc = launch_stream_probe(p, layer, max_blocks, batch, s))) return rc;
+  PIE_HIP(hipEventRecord(p->lev[layer].k_end, s));
+  if ((rc = compute_epilogue(p, layer, s))) return rc;
+  PIE_HIP(hipEventSynchronize(p->lev[layer].k_end));
+  return elapsed(p->lev[layer].k_start, p->lev[layer].k_end, out_ms);
+}
+
 int pie_prefetch_list(pie_pool* p, const int32_t* h_block_table, int32_t max_blocks, const int32_t* h_ctx_lens,
                       int32_t batch, int32_t* out_prefetch, int32_t* out_n_prefetch, int32_t* out_dirty,
                       int32_t* out_n_dirty) {

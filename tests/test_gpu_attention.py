@@ -254,3 +254,16 @@ def test_batch_at_the_planning_limit_and_contexts_on_partition_edges():
         lib.set_attn_partition(part)
         check(run_attn(lib, case, table), A.dense_attention(*H.dense_f64(case, 0), case.ctx_lens), w.dtype)
     lib.close()
+
+
+def test_stream_probe_runs_on_the_same_plan_and_leaves_no_trace():
+    w = I.Workload("probe", 2, 4, 8, 2, 128, I.DTYPE_BF16, ctx_lo=100, ctx_hi=900, value_scale=0.5, seed=39)
+    case = I.make_case(w)
+    lib, mod, table = GH.make_pools(case, int(case.n_blocks.sum()), 2, 2, fill=H.nan_fill(w.dtype))
+    before = run_attn(lib, case, table, 1)
+    tb = torch.from_numpy(table).to(GH.DEV)
+    cl = torch.from_numpy(case.ctx_lens).to(GH.DEV)
+    ms = lib.attn_stream_probe(1, tb, cl)
+    assert ms > 0.0 and lib.check_errors() == 0
+    assert np.array_equal(run_attn(lib, case, table, 1), before)
+    lib.close()
