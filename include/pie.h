@@ -234,12 +234,16 @@ int pie_attn_stream_probe_sync(pie_pool* pool, int32_t layer, const int32_t* d_b
 
 /* One decode step over all layers.  h_prefetch: the n_prefetch host-homed handles this batch touches, in
  * any order - the host cannot read the device block table, so the caller names them (pie_prefetch_list
- * computes the list from a host copy of the table, ordered by host slot so that the copies are contiguous).  h_dirty: the n_dirty of those that receive
- * this step's token (host-homed tail blocks).  For l = 0..L-1: layer l+1's blocks are prefetched on
- * swap_in_stream while layer l runs (append, then attention) on compute_stream; layer l's dirty blocks are
- * written back on swap_out_stream afterwards.
+ * computes the list from a host copy of the table, ordered by host slot so that the copies are contiguous).
+ * h_dirty: the n_dirty of those that receive this step's token (host-homed tail blocks).
+ * The new token's rows go into the GPU-homed tail blocks of all layers first, in one launch.  Then, for
+ * l = 0..L-1: layer l runs on compute_stream once its staged blocks are present; layer l+1's blocks are
+ * prefetched on swap_in_stream into the other staging region meanwhile, and the token's rows for host-homed
+ * tails are written into their staged copies on that stream, right behind the copy; layer l's dirty blocks
+ * are written back on swap_out_stream after the layer.
  * d_q_all, d_out_all: [L][batch][n_q_heads][head_dim]; d_k_new, d_v_new: [L][batch][n_kv_heads][head_dim]
- * (NULL skips the append). */
+ * (NULL skips the append).  Argument errors are detected before anything is enqueued; a HIP error in the
+ * middle (PIE_EHIP) leaves the step partly enqueued. */
 int pie_step(pie_pool* pool, const void* d_q_all, const void* d_k_new, const void* d_v_new,
              const int32_t* d_block_table, int32_t max_blocks, const int32_t* d_ctx_lens, int32_t batch,
              int32_t n_prefetch, const int32_t* h_prefetch, int32_t n_dirty, const int32_t* h_dirty,

@@ -78,3 +78,11 @@ def test_table_invariants(n, gpu, host, on_host, t):
     assert all(b - a >= 1.0 - 1e-12 for a, b in zip(starts, starts[1:]))
     assert [x.layer for x in r.records] == [k for _ in range(7) for k in range(n)]
     assert r.stall == pytest.approx(sum(x.t_start - x.t_begin for x in r.records))
+
+
+def test_two_layers_in_cpu_memory_is_the_most_the_example_hides():
+    """The example's choice of two CPU layers is the optimum for its timing: with t_swap = 2 t_compute the
+    protocol runs without any wait for 0, 1 and 2 layers in CPU memory, and waits from 3 on."""
+    def stall(m):
+        return LF.simulate(N, N - m, m + 2, list(range(N - m, N)), 10, t_compute=1.0, t_in=RATIO, t_out=RATIO).stall
+    assert [stall(m) == 0.0 for m in range(0, 6)] == [True, True, True, False, False, False]
