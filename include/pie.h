@@ -303,11 +303,11 @@ int pie_controller_update(pie_pool* pool, pie_controller* ctl, double throughput
  * The paper's own unit of swapping is a whole layer's KV cache.  pie_layer_sched is its swapping control as
  * pure host logic: a mapping table logical layer -> (state, GPU layer slot, CPU layer slot), at most one
  * swap-in and one swap-out in flight, and at the beginning of each layer's computation
- *   - a swap-out of the coldest layer on the GPU (the one whose next access is farthest: the layer that just
- *     finished) if the previous swap-out has completed and a CPU slot is free - unless every layer in CPU
- *     memory is colder still;
  *   - a swap-in of the hottest layer in CPU memory (the one accessed soonest) if the previous swap-in has
  *     completed and a GPU slot is free;
+ *   - then a swap-out of the coldest layer on the GPU (the one whose next access is farthest: the layer that
+ *     just finished) if the previous swap-out has completed, no GPU slot is free (a swap-out makes room for
+ *     the next swap-in) and a CPU slot is free - unless every layer in CPU memory is colder still;
  *   - before that, the presence check: a layer that is not physically on the GPU is waited for, and brought
  *     back at once if it is not even on its way.
  * Moves update the table in two phases: starting a move names the destination slot (state MOVING_*);
@@ -330,6 +330,7 @@ typedef struct pie_layer_pool pie_layer_pool;
 #define PIE_LAYER_SKIP_NO_SLOT        2   /* no free slot on the destination */
 #define PIE_LAYER_SKIP_COLDER_ON_HOST 3   /* every layer in CPU memory is colder than the candidate */
 #define PIE_LAYER_SKIP_NONE           4   /* no candidate */
+#define PIE_LAYER_SKIP_ROOM_LEFT      5   /* a GPU slot is free: no layer has to leave */
 
 typedef struct {
   int32_t state;       /* PIE_LAYER_* */
@@ -362,6 +363,14 @@ int pie_layer_sched_present(pie_layer_sched* s, int32_t layer, pie_layer_action*
 int pie_layer_sched_policy(pie_layer_sched* s, int32_t layer, pie_layer_action* out);
 /* The mapping table: n_layers entries. */
 int pie_layer_sched_table(pie_layer_sched* s, pie_layer_entry* out);
+/* Adaptive expansion in layers (Section 3.4.2: start with every layer on the GPU, put more layers into
+ * swapping while computation does not wait, move one back when it does): how many of the GPU layer slots
+ * may be in use, 1 .. the count given at creation (PIE_EINVAL if the CPU slots cannot back it: the layers
+ * that do not fit need one each, plus the two in flight).  Call between tokens.  Taking slots away retires free
+ * slots, highest first, now or as completed swap-outs free them; while more are occupied than allowed the
+ * swap-out exception is not applied (a layer has to leave).  Giving slots back re-enables retired ones,
+ * lowest first; the next swap-ins fill them. */
+int pie_layer_sched_set_gpu_slots(pie_layer_sched* s, int32_t n_gpu_slots);
 
 /* pie_layer_pool runs that protocol on the GPU.  `pool` provides the GPU layer slots: a device pool created
  * with n_stage_blocks = n_host_blocks = 0 whose n_layers is the number of GPU layer slots; a layer's image is
@@ -386,6 +395,8 @@ int pie_layer_pool_destroy(pie_layer_pool* lp);
 int pie_layer_step(pie_layer_pool* lp, const void* d_q_all, const void* d_k_new, const void* d_v_new,
                    const int32_t* d_block_table, int32_t max_blocks, const int32_t* d_ctx_lens, int32_t batch,
                    void* d_out_all, void* compute_stream, void* swap_in_stream, void* swap_out_stream);
+/* pie_layer_sched_set_gpu_slots for the pool's protocol.  Call between steps. */
+int pie_layer_pool_set_gpu_slots(pie_layer_pool* lp, int32_t n_gpu_slots);
 /* Waits for the moves in flight and completes them in the table. */
 int pie_layer_pool_settle_sync(pie_layer_pool* lp);
 /* Where a logical layer's image is now: *out_where = PIE_WHERE_*, *out_ptr its device or host address.

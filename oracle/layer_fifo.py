@@ -14,8 +14,12 @@ Section 3.3 (the protocol run at the beginning of every layer's computation):
   * before computing layer k, if it is not physically present on the GPU, wait
     until it has been moved back completely.
 
-Readings where the text is silent: the two checks are made swap-out first, then
-swap-in (the order does not change the worked example); "coldness" is the
+Readings where the text is silent: the swap-in check is made first, then the
+swap-out check, and a swap-out is only started when no GPU slot is free - its
+purpose is to make room for the next swap-in (in the worked example the freed
+space of layer 1 takes layer 8 while layer 3 starts to leave: both orders give
+the example's trace, but only this one lets the layers drain back onto the GPU
+when slots are added); "coldness" is the
 number of layer computations until the next access, (j - k) mod n for layer j
 while layer k computes; a layer in flight in either direction is neither a
 swap-out candidate nor counted as "in CPU memory"; a swap-out's GPU slot is
@@ -23,6 +27,15 @@ released when the copy has completed (phase two), a swap-in's CPU slot
 likewise; a layer that is needed while it is neither present nor on its way is
 brought back at once (waiting for the link and, if necessary, for a slot), and
 that wait is counted as stall.
+
+Adaptive expansion in the paper's own unit (Section 3.4.2: start with all layers
+on the GPU, put more layers into swapping while computation does not wait, move
+one back when it does): the number of GPU layer slots in use can be changed
+between tokens (set_gpu_slots).  Taking a slot away retires a free slot, or the
+next one that a completed swap-out frees; while more GPU slots are occupied than
+allowed, the swap-out exception ("everything in CPU memory is colder") is not
+applied, since the point is to move a layer out.  Giving a slot back puts a
+retired slot on the free list; the next swap-in fills it.
 
 Time is in arbitrary units; one layer computes in t_compute, one layer moves
 in t_in / t_out.  Layers are numbered 0 .. n-1 here (the paper's 1 .. n).
@@ -58,7 +71,7 @@ class Record:
     t_start: float                  # when its computation started (after any wait)
     out_started: Optional[int] = None
     in_started: Optional[int] = None
-    out_skipped: Optional[str] = None      # "busy" | "no_slot" | "colder_on_host" | "none"
+    out_skipped: Optional[str] = None      # "busy" | "no_slot" | "colder_on_host" | "room_left" | "none"
     in_skipped: Optional[str] = None       # "busy" | "no_slot" | "none"
     forced_in: bool = False
 
@@ -92,6 +105,33 @@ class LayerFifo:
                 self.table[j] = Entry(GPU, gpu_slot=self.free_gpu.pop(0))
         self.moving_in: Optional[int] = None         # at most one swap-in and one swap-out in flight
         self.moving_out: Optional[int] = None
+        self.n_gpu_total = n_gpu_slots
+        self.n_host_total = n_host_slots
+        self.n_enabled = n_gpu_slots                 # GPU slots in use or on the free list
+        self.target = n_gpu_slots                    # how many are allowed
+        self.retired: List[int] = []
+
+    # ---- changing the number of GPU layer slots ------------------------------
+    def _rebalance(self):
+        while self.n_enabled > self.target and self.free_gpu:
+            self.retired.append(self.free_gpu.pop())         # highest free slot
+            self.retired.sort()
+            self.n_enabled -= 1
+        while self.n_enabled < self.target and self.retired:
+            self.free_gpu.append(self.retired.pop(0))        # lowest retired slot
+            self.free_gpu.sort()
+            self.n_enabled += 1
+
+    def set_gpu_slots(self, n: int):
+        # the layers that do not fit the GPU slots need a CPU slot each, plus the two in flight
+        if n < 1 or n > self.n_gpu_total or self.n - n + 2 > self.n_host_total:
+            raise ValueError("slot count")
+        self.target = n
+        self._rebalance()
+
+    @property
+    def oversubscribed(self) -> bool:
+        return self.n_enabled > self.target
 
     # ---- phase two of a move -------------------------------------------------
     def complete_in(self, now: float):
@@ -110,6 +150,7 @@ class LayerFifo:
         self.free_gpu.sort()
         e.gpu_slot, e.state, e.t_out_done = None, HOST, now
         self.moving_out = None
+        self._rebalance()
         return j
 
     # ---- phase one -------------------------------------------------------------
@@ -139,11 +180,14 @@ class LayerFifo:
 
 
 def simulate(n_layers: int, n_gpu_slots: int, n_host_slots: int, on_host: List[int], n_tokens: int,
-             t_compute: float = 1.0, t_in: float = 2.0, t_out: float = 2.0) -> Result:
+             t_compute: float = 1.0, t_in: float = 2.0, t_out: float = 2.0, gpu_slots_for_token=None) -> Result:
+    """gpu_slots_for_token: optional callable (token index, stall of the previous token) -> number of GPU
+    layer slots allowed from this token on (None = unchanged); called at every token boundary."""
     f = LayerFifo(n_layers, n_gpu_slots, n_host_slots, on_host)
     res = Result()
     now = 0.0
     in_done_at = out_done_at = None
+    stall_prev = 0.0
 
     def retire(t):
         nonlocal in_done_at, out_done_at
@@ -156,6 +200,12 @@ def simulate(n_layers: int, n_gpu_slots: int, n_host_slots: int, on_host: List[i
             in_done_at = None
 
     for token in range(n_tokens):
+        retire(now)
+        if gpu_slots_for_token is not None:
+            want = gpu_slots_for_token(token, res.stall - stall_prev)
+            if want is not None:
+                f.set_gpu_slots(want)
+        stall_prev = res.stall
         for k in range(n_layers):
             retire(now)
             rec = Record(token, k, now, now)
@@ -169,7 +219,7 @@ def simulate(n_layers: int, n_gpu_slots: int, n_host_slots: int, on_host: List[i
                     if f.moving_in is not None:
                         now = max(now, in_done_at)
                         retire(now)
-                    if not f.free_gpu:
+                    while not f.free_gpu:                   # a freed slot may be retired: then another layer goes
                         if f.moving_out is None:
                             victim = f.coldest_on_gpu(k)
                             f.start_out(victim, now)
@@ -185,22 +235,6 @@ def simulate(n_layers: int, n_gpu_slots: int, n_host_slots: int, on_host: List[i
                 assert f.table[k].state == GPU
             res.stall += now - rec.t_begin
             rec.t_start = now
-            # swap-out of the coldest layer on the GPU
-            if f.moving_out is not None:
-                rec.out_skipped = "busy"
-            else:
-                cand = f.coldest_on_gpu(k)
-                on_host_now = [j for j, x in f.table.items() if x.state == HOST]
-                if cand is None:
-                    rec.out_skipped = "none"
-                elif all(f.distance(j, k) > f.distance(cand, k) for j in on_host_now):
-                    rec.out_skipped = "colder_on_host"      # also when nothing is in CPU memory at all
-                elif not f.free_host:
-                    rec.out_skipped = "no_slot"
-                else:
-                    f.start_out(cand, now)
-                    out_done_at = now + t_out
-                    rec.out_started = cand
             # swap-in of the hottest layer in CPU memory
             if f.moving_in is not None:
                 rec.in_skipped = "busy"
@@ -214,9 +248,53 @@ def simulate(n_layers: int, n_gpu_slots: int, n_host_slots: int, on_host: List[i
                     f.start_in(cand, now)
                     in_done_at = now + t_in
                     rec.in_started = cand
+            # swap-out of the coldest layer on the GPU
+            if f.moving_out is not None:
+                rec.out_skipped = "busy"
+            else:
+                cand = f.coldest_on_gpu(k)
+                on_host_now = [j for j, x in f.table.items() if x.state == HOST]
+                if cand is None:
+                    rec.out_skipped = "none"
+                elif not f.oversubscribed and all(f.distance(j, k) > f.distance(cand, k) for j in on_host_now):
+                    rec.out_skipped = "colder_on_host"      # also when nothing is in CPU memory at all
+                elif f.free_gpu:
+                    rec.out_skipped = "room_left"           # a GPU slot is free: nothing has to leave
+                elif not f.free_host:
+                    rec.out_skipped = "no_slot"
+                else:
+                    f.start_out(cand, now)
+                    out_done_at = now + t_out
+                    rec.out_started = cand
             away = sum(1 for x in f.table.values() if x.state != GPU)
             res.max_away = max(res.max_away, away)
             res.records.append(rec)
             now += t_compute
     res.table = f.table
     return res
+
+
+def simulate_adaptive(n_layers: int, n_host_slots: int, n_tokens: int, t_compute: float = 1.0, t_in: float = 2.0,
+                      t_out: float = 2.0, k_up: int = 4, k_down: int = 2, probe_period: int = 64):
+    """Adaptive expansion over the protocol: all layers start on the GPU; after every token the controller of
+    oracle.controller_sim (level = layers meant to live in CPU memory) sees whether computation waited, and
+    the number of GPU layer slots follows its level.  The throughput signal is 1 / token time x n / (n - m):
+    more layers in CPU memory mean proportionally larger per-layer caches (Section 3.1).
+    Returns (levels per token, Result)."""
+    from .controller_sim import AdaptiveExpansion, Observation
+    ctl = AdaptiveExpansion(units=n_layers, k_max=n_host_slots - 2, k_up=k_up, k_down=k_down, probe_period=probe_period)
+    levels: List[int] = []
+    state = {"t_token": None}
+
+    def hook(token, stall_last):
+        if token > 0:
+            t_token = n_layers * t_compute + stall_last
+            m = ctl.k
+            per_layer = stall_last / n_layers
+            ctl.observe(Observation([t_compute] * n_layers, [0.0] * n_layers, [per_layer] * n_layers, 0.0,
+                                    (1.0 / t_token) * n_layers / (n_layers - m)))
+        levels.append(ctl.k)
+        return n_layers - ctl.k
+
+    res = simulate(n_layers, n_layers, n_host_slots, [], n_tokens, t_compute, t_in, t_out, gpu_slots_for_token=hook)
+    return levels, res

@@ -34,7 +34,7 @@ SYMBOLS = [
     "pie_controller_observe", "pie_controller_level", "pie_controller_update", "pie_last_hip_error", "pie_strerror",
     "pie_version",
     "pie_layer_sched_create", "pie_layer_sched_destroy", "pie_layer_sched_complete", "pie_layer_sched_present",
-    "pie_layer_sched_policy", "pie_layer_sched_table", "pie_layer_pool_bytes_required", "pie_layer_pool_create",
+    "pie_layer_sched_policy", "pie_layer_sched_table", "pie_layer_sched_set_gpu_slots", "pie_layer_pool_set_gpu_slots", "pie_layer_pool_bytes_required", "pie_layer_pool_create",
     "pie_layer_pool_destroy", "pie_layer_step", "pie_layer_pool_settle_sync", "pie_layer_pool_address",
     "pie_layer_pool_table", "pie_layer_pool_stats",
 ]
@@ -345,7 +345,7 @@ class Controller:
 
 LAYER_GPU, LAYER_HOST, LAYER_MOVING_OUT, LAYER_MOVING_IN = 0, 1, 2, 3
 WAIT_NONE, WAIT_IN, WAIT_OUT = 0, 1, 2
-SKIP_NOT, SKIP_BUSY, SKIP_NO_SLOT, SKIP_COLDER_ON_HOST, SKIP_NONE = 0, 1, 2, 3, 4
+SKIP_NOT, SKIP_BUSY, SKIP_NO_SLOT, SKIP_COLDER_ON_HOST, SKIP_NONE, SKIP_ROOM_LEFT = 0, 1, 2, 3, 4, 5
 
 
 class LayerEntry(C.Structure):
@@ -391,6 +391,9 @@ class LayerSched:
         _check(_lib.pie_layer_sched_table(self._h, arr), "layer_sched_table")
         return [(e.state, e.gpu_slot, e.host_slot) for e in arr]
 
+    def set_gpu_slots(self, n: int):
+        _check(_lib.pie_layer_sched_set_gpu_slots(self._h, C.c_int32(n)), "layer_sched_set_gpu_slots")
+
     def close(self):
         if self._h:
             _lib.pie_layer_sched_destroy(self._h)
@@ -429,6 +432,9 @@ class LayerPool:
 
     def settle(self):
         _check(_lib.pie_layer_pool_settle_sync(self._h), "layer_pool_settle")
+
+    def set_gpu_slots(self, n: int):
+        _check(_lib.pie_layer_pool_set_gpu_slots(self._h, C.c_int32(n)), "layer_pool_set_gpu_slots")
 
     def table(self) -> List[Tuple[int, int, int]]:
         arr = (LayerEntry * self.n_layers)()

@@ -8,7 +8,8 @@
 // pie_layer_sched is the protocol as pure host logic (no GPU): the caller reports completed moves and asks,
 // per layer, what to wait for and what to start.  pie_layer_pool drives it over a pool whose "layers" are
 // the GPU's physical layer slots, with whole-layer copy-engine transfers.  Readings where the text is
-// silent: swap-out is considered before swap-in; coldness is the number of layer computations until the
+// silent: swap-in is considered before swap-out, and a swap-out starts only when no GPU slot is free (it
+// exists to make room for the next swap-in); coldness is the number of layer computations until the
 // next access, (j - k) mod n while layer k computes; layers in flight are neither candidates nor counted as
 // "in CPU memory"; a slot is released when the copy that leaves it has completed; a layer that is needed
 // while it is neither present nor on its way is brought back at once.
@@ -24,6 +25,23 @@ struct pie_layer_sched {
   std::vector<pie_layer_entry> table;
   std::vector<int32_t> free_gpu, free_host;      // kept ascending; lowest slot first
   int32_t moving_in = -1, moving_out = -1;
+  // Adaptive expansion in layers (Section 3.4.2): how many GPU layer slots may be in use.  Slots beyond the
+  // target are retired as they become free; while more are occupied than allowed, a layer has to leave.
+  int32_t n_gpu_total = 0, n_host_total = 0, n_enabled = 0, target = 0;
+  std::vector<int32_t> retired;                  // ascending
+
+  void rebalance() {
+    while (n_enabled > target && !free_gpu.empty()) {
+      give_back(retired, free_gpu.back());       // the highest free slot
+      free_gpu.pop_back();
+      --n_enabled;
+    }
+    while (n_enabled < target && !retired.empty()) {
+      give_back(free_gpu, take_lowest(retired));
+      ++n_enabled;
+    }
+  }
+  bool oversubscribed() const { return n_enabled > target; }
 
   int32_t distance(int32_t j, int32_t k) const { return ((j - k) % n + n) % n; }
 
@@ -94,6 +112,8 @@ int pie_layer_sched_create(int32_t n_layers, int32_t n_gpu_slots, int32_t n_host
   pie_layer_sched* s = new (std::nothrow) pie_layer_sched();
   if (!s) return PIE_ENOMEM;
   s->n = n_layers;
+  s->n_gpu_total = s->n_enabled = s->target = n_gpu_slots;
+  s->n_host_total = n_host_slots;
   for (int32_t i = 0; i < n_gpu_slots; ++i) s->free_gpu.push_back(i);
   for (int32_t i = 0; i < n_host_slots; ++i) s->free_host.push_back(i);
   s->table.resize(n_layers);
@@ -134,7 +154,17 @@ int pie_layer_sched_complete(pie_layer_sched* s, int32_t which) {
     e.gpu_slot = -1;
     e.state = PIE_LAYER_HOST;
     s->moving_out = -1;
+    s->rebalance();
   }
+  return PIE_OK;
+}
+
+int pie_layer_sched_set_gpu_slots(pie_layer_sched* s, int32_t n_gpu_slots) {
+  if (!s || n_gpu_slots < 1 || n_gpu_slots > s->n_gpu_total) return PIE_EINVAL;
+  // the layers that do not fit the GPU slots need a CPU slot each, plus the two in flight
+  if (s->n - n_gpu_slots + 2 > s->n_host_total) return PIE_EINVAL;
+  s->target = n_gpu_slots;
+  s->rebalance();
   return PIE_OK;
 }
 
@@ -179,25 +209,6 @@ int pie_layer_sched_policy(pie_layer_sched* s, int32_t k, pie_layer_action* a) {
   if (s->table[k].state != PIE_LAYER_GPU) return PIE_ESTATE;
   clear_action(a);
   a->gpu_slot = s->table[k].gpu_slot;
-  // swap-out of the coldest layer on the GPU
-  if (s->moving_out >= 0) {
-    a->out_skipped = PIE_LAYER_SKIP_BUSY;
-  } else {
-    const int32_t cand = s->coldest_on_gpu(k);
-    if (cand < 0) {
-      a->out_skipped = PIE_LAYER_SKIP_NONE;
-    } else {
-      bool all_colder = true;                                // also when nothing is in CPU memory at all
-      for (int32_t j = 0; j < s->n; ++j)
-        if (s->table[j].state == PIE_LAYER_HOST && s->distance(j, k) <= s->distance(cand, k)) all_colder = false;
-      if (all_colder)
-        a->out_skipped = PIE_LAYER_SKIP_COLDER_ON_HOST;
-      else if (s->free_host.empty())
-        a->out_skipped = PIE_LAYER_SKIP_NO_SLOT;
-      else
-        s->start_out(cand, a);
-    }
-  }
   // swap-in of the hottest layer in CPU memory
   if (s->moving_in >= 0) {
     a->in_skipped = PIE_LAYER_SKIP_BUSY;
@@ -209,6 +220,27 @@ int pie_layer_sched_policy(pie_layer_sched* s, int32_t k, pie_layer_action* a) {
       a->in_skipped = PIE_LAYER_SKIP_NO_SLOT;
     else
       s->start_in(cand, a);
+  }
+  // swap-out of the coldest layer on the GPU
+  if (s->moving_out >= 0) {
+    a->out_skipped = PIE_LAYER_SKIP_BUSY;
+  } else {
+    const int32_t cand = s->coldest_on_gpu(k);
+    if (cand < 0) {
+      a->out_skipped = PIE_LAYER_SKIP_NONE;
+    } else {
+      bool all_colder = true;                                // also when nothing is in CPU memory at all
+      for (int32_t j = 0; j < s->n; ++j)
+        if (s->table[j].state == PIE_LAYER_HOST && s->distance(j, k) <= s->distance(cand, k)) all_colder = false;
+      if (all_colder && !s->oversubscribed())
+        a->out_skipped = PIE_LAYER_SKIP_COLDER_ON_HOST;
+      else if (!s->free_gpu.empty())
+        a->out_skipped = PIE_LAYER_SKIP_ROOM_LEFT;           // a GPU slot is free: nothing has to leave
+      else if (s->free_host.empty())
+        a->out_skipped = PIE_LAYER_SKIP_NO_SLOT;
+      else
+        s->start_out(cand, a);
+    }
   }
   return PIE_OK;
 }
@@ -349,6 +381,11 @@ int pie_layer_pool_destroy(pie_layer_pool* lp) {
 int pie_layer_pool_table(pie_layer_pool* lp, pie_layer_entry* out) {
   if (!lp) return PIE_EINVAL;
   return pie_layer_sched_table(lp->sched, out);
+}
+
+int pie_layer_pool_set_gpu_slots(pie_layer_pool* lp, int32_t n_gpu_slots) {
+  if (!lp) return PIE_EINVAL;
+  return pie_layer_sched_set_gpu_slots(lp->sched, n_gpu_slots);
 }
 
 int pie_layer_pool_settle_sync(pie_layer_pool* lp) {

@@ -138,7 +138,7 @@ def test_worked_example_schedule_on_hardware():
     out = torch.empty_like(q)
     try:
         layer_mb = lp.layer_bytes / 1e6
-        t_swap_us = 40.0 + layer_mb / 50e3 * 1e6               # measured copy-engine model: 40 us + 50 GB/s
+        t_swap_us = 40.0 + layer_mb / 33e3 * 1e6               # copy engines with both directions busy: 40 us + 33 GB/s
         inner.set_layer_compute_us(t_swap_us / 1.7)
         tokens = 8
         for _ in range(tokens):
@@ -152,8 +152,62 @@ def test_worked_example_schedule_on_hardware():
         assert n / 2 - 0.75 <= per_token <= n / 1.7 + 0.5, per_token
         assert abs(st.n_swap_in - st.n_swap_out) <= 2
         away = sum(1 for s, _, _ in lp.table() if s != B.LAYER_GPU)
-        assert away == 4                                       # two in CPU memory, two in flight
+        assert away in (3, 4)                                  # two in CPU memory, one or two in flight
     finally:
+        lp.close()
+        inner.close()
+        ref.close()
+
+
+def test_adaptive_expansion_in_layers_on_hardware():
+    """Section 3.4.2 in the paper's own unit: every layer starts on the GPU; a controller that only sees whether
+    computation waited takes GPU layer slots away one at a time and gives one back when it did.  Outputs stay
+    bit-identical throughout; the run overshoots, waits, and settles where nothing waits."""
+    n, host = 9, 6
+    w = I.Workload("lfifo3", n, 8, 8, 8, 128, I.DTYPE_F16, ctx_lo=1500, ctx_hi=2048, value_scale=0.5, seed=53)
+    case, ref, inner, lp, table = build(n, n, host, [], w)
+    cs, si, so = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    q = GH.to_dev(case.q, w.dtype)
+    d_table = torch.from_numpy(table).to(GH.DEV)
+    d_ctx = torch.from_numpy(case.ctx_lens).to(GH.DEV)
+    out_ref, out = torch.empty_like(q), torch.empty_like(q)
+    none = np.zeros(0, dtype=np.int32)
+    ctl = B.Controller(n, host - 2, k_up=3, k_down=2, probe_period=1000)
+    try:
+        ref.step(q, None, None, d_table, d_ctx, none, none, out_ref, cs, si, so)
+        ref.sync()
+        t_swap_us = 40.0 + lp.layer_bytes / 33e3              # copy engines with both directions busy
+        t_layer_us = t_swap_us / 1.7
+        inner.set_layer_compute_us(t_layer_us)
+        levels, stalls, level, prev_stall = [], [], 0, 0.0
+        import time
+        for token in range(60):
+            levels.append(level)
+            t0 = time.perf_counter()
+            lp.step(q, None, None, d_table, d_ctx, out, cs, si, so)
+            inner.sync()
+            dt_ms = (time.perf_counter() - t0) * 1e3
+            assert torch.equal(out.view(torch.int16), out_ref.view(torch.int16)), token
+            st = lp.stats()
+            stall = st.stall_ms - prev_stall
+            prev_stall = st.stall_ms
+            stalls.append(stall)
+            tc = (dt_ms - stall) / n
+            new = ctl.observe([tc] * n, [0.0] * n, [stall / n] * n, 0.0, (1.0 / dt_ms) * n / (n - level))
+            if new != level:
+                lp.set_gpu_slots(n - new)
+                level = new
+        assert inner.check_errors() == 0
+        assert levels[:3] == [0, 0, 0] and max(levels) >= 2, levels
+        assert all(abs(b - a) <= 1 for a, b in zip(levels, levels[1:])), levels
+        assert len(set(levels[-12:])) == 1 and levels[-1] >= 1, levels
+        token_ms = n * t_layer_us / 1e3
+        assert sum(stalls[-10:]) <= 0.02 * 10 * token_ms, (levels, stalls[-10:])
+        lp.settle()
+        away = sum(1 for s, _, _ in lp.table() if s != B.LAYER_GPU)
+        assert away >= levels[-1]
+    finally:
+        ctl.close()
         lp.close()
         inner.close()
         ref.close()

@@ -8,10 +8,10 @@ from paper_2411_09317_amd import binding as B
 
 STATE = {LF.GPU: B.LAYER_GPU, LF.HOST: B.LAYER_HOST, LF.MOVING_OUT: B.LAYER_MOVING_OUT, LF.MOVING_IN: B.LAYER_MOVING_IN}
 SKIP = {None: B.SKIP_NOT, "busy": B.SKIP_BUSY, "no_slot": B.SKIP_NO_SLOT, "colder_on_host": B.SKIP_COLDER_ON_HOST,
-        "none": B.SKIP_NONE}
+        "none": B.SKIP_NONE, "room_left": B.SKIP_ROOM_LEFT}
 
 
-def run_library(n, gpu, host, on_host, n_tokens, t_compute, t_in, t_out):
+def run_library(n, gpu, host, on_host, n_tokens, t_compute, t_in, t_out, slots_for_token=None):
     """Drives the library's protocol with clocks instead of a GPU: a move started at t completes at t + t_in / t_out."""
     s = B.LayerSched(n, gpu, host, on_host)
     now, in_done, out_done = 0.0, None, None
@@ -34,6 +34,9 @@ def run_library(n, gpu, host, on_host, n_tokens, t_compute, t_in, t_out):
             in_done = t + t_in
 
     for token in range(n_tokens):
+        retire(now)
+        if slots_for_token is not None and slots_for_token(token) is not None:
+            s.set_gpu_slots(slots_for_token(token))
         for k in range(n):
             retire(now)
             t_begin, forced = now, False
@@ -100,3 +103,30 @@ def test_argument_and_state_errors():
         s.policy(3)                                  # not present
     assert e.value.code == B.ESTATE
     s.close()
+
+
+SCHEDULES = [
+    # all layers on the GPU at first, then slots are taken away and given back between tokens
+    (9, 9, 6, [], 14, 2.0, {1: 8, 3: 7, 6: 6, 8: 7, 10: 9, 12: 5}),
+    (12, 12, 8, [], 16, 1.3, {0: 10, 2: 8, 5: 6, 9: 12, 11: 7}),
+    (6, 5, 7, [5], 10, 0.6, {2: 3, 4: 1, 7: 5}),
+]
+
+
+@pytest.mark.parametrize("n,gpu,host,on_host,tokens,t,sched", SCHEDULES)
+def test_changing_the_number_of_gpu_slots_matches_the_oracle(n, gpu, host, on_host, tokens, t, sched):
+    ref = LF.simulate(n, gpu, host, on_host, tokens, t_compute=1.0, t_in=t, t_out=t,
+                      gpu_slots_for_token=lambda token, stall: sched.get(token))
+    got, stall, table = run_library(n, gpu, host, on_host, tokens, 1.0, t, t, slots_for_token=lambda token: sched.get(token))
+    for g, r in zip(got, ref.records):
+        assert g[:6] == (r.token, r.layer, r.t_begin, r.t_start, -1 if r.out_started is None else r.out_started,
+                         -1 if r.in_started is None else r.in_started)
+        assert g[8] == r.forced_in
+    assert stall == pytest.approx(ref.stall)
+    for j, (state, gs, hs) in enumerate(table):
+        e = ref.table[j]
+        assert state == STATE[e.state]
+        assert gs == (-1 if e.gpu_slot is None else e.gpu_slot) and hs == (-1 if e.host_slot is None else e.host_slot)
+    # with fewer slots allowed than layers, that many layers are away from the GPU at the end
+    last = sched[max(sched)]
+    assert sum(1 for st, _, _ in table if st != B.LAYER_GPU) >= n - last

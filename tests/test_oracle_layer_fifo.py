@@ -86,3 +86,31 @@ def test_two_layers_in_cpu_memory_is_the_most_the_example_hides():
     def stall(m):
         return LF.simulate(N, N - m, m + 2, list(range(N - m, N)), 10, t_compute=1.0, t_in=RATIO, t_out=RATIO).stall
     assert [stall(m) == 0.0 for m in range(0, 6)] == [True, True, True, False, False, False]
+
+
+def test_adaptive_expansion_finds_the_examples_two_layers_from_all_on_gpu():
+    """Section 3.4.2 on the example's timing: start with every layer on the GPU, add a layer to swapping after
+    k_up tokens without a wait, take one back after k_down tokens with waits.  The run overshoots to three
+    layers, waits, and settles on two - the example's own choice and the most its timing hides."""
+    levels, res = LF.simulate_adaptive(N, 6, 80, t_compute=1.0, t_in=RATIO, t_out=RATIO, k_up=4, k_down=2,
+                                       probe_period=1000)
+    assert levels[:4] == [0, 0, 0, 0]
+    assert all(abs(b - a) <= 1 for a, b in zip(levels, levels[1:]))
+    assert max(levels) == M + 1 and levels[-40:] == [M] * 40
+    # the waits all belong to the tokens spent at three layers (and the one that drains the third)
+    waits = {}
+    for r in res.records:
+        waits[r.token] = waits.get(r.token, 0.0) + (r.t_start - r.t_begin)
+    assert all(w == 0.0 for t, w in waits.items() if levels[t] <= M and (t == 0 or levels[t - 1] <= M))
+    # a faster link carries more: with t_swap = t_compute the same rule goes to the limit of the CPU slots
+    levels, res = LF.simulate_adaptive(N, 6, 80, t_compute=1.0, t_in=1.0, t_out=1.0)
+    assert levels[-1] == 4 and res.stall == 0.0
+
+
+def test_layers_drain_back_when_every_gpu_slot_is_available():
+    """With a GPU slot for every layer, the layers in CPU memory come back one by one and nothing leaves any
+    more: a swap-out is only there to make room."""
+    r = LF.simulate(N, N, 6, [N - 2, N - 1], 4)
+    assert [x.in_started for x in r.records if x.in_started is not None] == [N - 2, N - 1]
+    assert all(x.out_started is None for x in r.records)
+    assert all(e.state == LF.GPU for e in r.table.values()) and r.stall == 0.0
