@@ -299,7 +299,7 @@ def main():
     args = parse()
     if args.gpus != 1:
         print(f"bench.py measures one GPU; --gpus {args.gpus} is not supported in this build "
-              "(the path shards by sequence with no exchange step; see DESIGN.md)", file=sys.stderr)
+              "(the path would shard by sequence, each GPU with its own pools, host link and controller, no exchange step)", file=sys.stderr)
         sys.exit(2)
     import torch
     from paper_2411_09317_amd import binding as B
