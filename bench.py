@@ -57,6 +57,14 @@ def parse():
     ap.add_argument("--t-other-us", type=float, default=0.0,
                     help="experiments only: keep the compute stream busy this long after each layer's attention, standing "
                          "for the rest of a transformer layer (default 0 = the measured path)")
+    ap.add_argument("--serve", type=int, default=0,
+                    help="experiment instead of the benchmark line: serve this many synthetic requests (Poisson arrivals, "
+                         "iteration-level scheduling) on a GPU pool of --serve-gpu-blocks blocks per layer at the expansion "
+                         "levels in --serve-levels and with the controller; prints its own JSON line")
+    ap.add_argument("--serve-gpu-blocks", type=int, default=16384)
+    ap.add_argument("--serve-levels", default="0,1,2,4,8", help="budget levels; one level = 1/64 of the GPU pool")
+    ap.add_argument("--serve-load", type=float, default=0.8,
+                    help="arrival rate of the latency legs as a share of the level-0 saturated request rate")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run a plain elementwise copy of this many MiB (a known-size reference for HBM counters)")
     return ap.parse_args()
@@ -166,7 +174,13 @@ def adaptive_leg(w, dw, streams, n_steps, units, k_max):
     ctl = B.Controller(units, k_max)
     dw.pool.set_host_fraction(0.0, dw.order, streams[1])
     dw.pool.sync()
-    dw.pool.set_timing(True)
+    none = np.zeros(0, dtype=np.int32)
+    cost = {}
+    for name, mode in (("off", B.TIMING_OFF), ("device_clock", B.TIMING_CLOCK), ("events", B.TIMING_EVENTS)):
+        dw.pool.set_timing(mode)                   # what the monitoring itself costs, nothing on the host
+        timed_steps(dw, streams, 2, none, none)
+        cost[name] = timed_steps(dw, streams, 10, none, none) / 10 * 1e3
+    dw.pool.set_timing(B.TIMING_CLOCK)
     level, traj = 0, []
     for step in range(n_steps):
         pf, dirty = dw.pool.prefetch_list(dw.table, dw.ctx_lens)
@@ -188,7 +202,11 @@ def adaptive_leg(w, dw, streams, n_steps, units, k_max):
     ctl.close()
     levels = [t[0] for t in traj]
     tail = levels[len(levels) // 2:]
-    return {"units": units, "k_max": k_max, "steps": n_steps, "final_level": k, "ceiling": ceiling,
+    return {"units": units, "k_max": k_max, "steps": n_steps, "monitoring": "device clock",
+            "monitoring_overhead": {"ms_per_step_unmonitored": cost["off"],
+                                    "device_clock": cost["device_clock"] / cost["off"] - 1.0,
+                                    "events": cost["events"] / cost["off"] - 1.0},
+            "final_level": k, "ceiling": ceiling,
             "final_host_fraction": k / units, "level_min_second_half": min(tail), "level_max_second_half": max(tail),
             "levels": levels, "ms_per_step_last": traj[-1][1]}
 
@@ -295,6 +313,68 @@ def cpu_baseline(dw, n_seqs, n_layers):
             "gpu_vs_oracle_rowwise_rel_err": rel}
 
 
+def serving_mode(args):
+    """Expansion turned into batch size: a request stream served at fixed budget levels and by the controller,
+    first saturated (every request waiting from the start: throughput), then at a share of the level-0
+    request rate (latency split into queueing and decoding)."""
+    import torch
+    from paper_2411_09317_amd import binding as B
+    from paper_2411_09317_amd import inputs as I
+    from paper_2411_09317_amd import serving as S
+    w = I.scaled(I.CONFIGS[args.workload], batch=0)
+    n_gpu, units = args.serve_gpu_blocks, 64
+    unit = n_gpu // units
+    levels = [int(x) for x in args.serve_levels.split(",")]
+    k_max = max(levels + [16])
+    out_lo, out_hi = 64, 256
+    max_blocks = (w.ctx_hi + out_hi + w.block_tokens - 1) // w.block_tokens
+    max_batch = 1024
+    pool = B.Pool(w.n_layers, w.n_q_heads, w.n_kv_heads, w.head_dim, w.block_tokens, w.dtype, n_gpu, unit * k_max,
+                  unit * k_max, max_batch=max_batch, max_blocks_per_seq=max_blocks)
+    from paper_2411_09317_amd import workload as WL
+    img = pool.gpu_image()
+    for l in range(w.n_layers):                                  # "prompts already in the cache": finite random values
+        layer = img[l].view(-1).view(WL.TORCH_DT[w.dtype])
+        layer.copy_((torch.randn(layer.numel(), device=img.device, dtype=torch.float32) * w.value_scale).to(layer.dtype))
+    pool.host_image().zero_()
+    if args.t_other_us:
+        pool.set_layer_compute_us(args.t_other_us)
+
+    def stream(rate):
+        a, p, o = I.draw_requests(w, args.serve, rate, out_lo, out_hi)
+        return [S.Request(i, float(a[i]), int(p[i]), int(o[i])) for i in range(args.serve)]
+
+    def run(level, rate, adaptive=False):
+        bud = S.BlockBudget(n_gpu, unit, k_max)
+        ctl = None
+        if adaptive:
+            ctl = B.Controller(units, k_max)
+        else:
+            bud.set_level(level)
+        t0 = time.perf_counter()
+        r = S.serve(pool, w, stream(rate), bud, max_batch, max_blocks, controller=ctl,
+                    progress=lambda it, now, done: print(f"#   iteration {it}: {done} requests done, {now:.1f} s",
+                                                         file=sys.stderr, flush=True))
+        r["wall_s"] = round(time.perf_counter() - t0, 2)
+        r["mode"] = "adaptive" if adaptive else f"level {level}"
+        if ctl:
+            ctl.close()
+        print(f"# serve {r['mode']} rate {rate:.3g}/s: {r['tokens_per_s']:.0f} tok/s, batch {r['mean_batch']:.1f}, "
+              f"{r['ms_per_iteration']:.2f} ms/iter, latency {r['latency_s_mean']:.2f} s", file=sys.stderr, flush=True)
+        return r
+
+    res = {"experiment": "serving", "workload": f"{w.name} shape, {w.n_layers} layers, GPU pool {n_gpu} blocks per layer "
+           f"({n_gpu * w.block_bytes * w.n_layers / 1e9:.1f} GB), one level = {unit} host blocks per layer",
+           "requests": args.serve, "prompt": f"{w.ctx_dist} [{w.ctx_lo},{w.ctx_hi}]", "output": f"uniform [{out_lo},{out_hi}]",
+           "t_other_us": args.t_other_us, "data": "synthetic"}
+    res["saturated"] = [run(k, 1e9) for k in levels] + [run(0, 1e9, adaptive=True)]
+    base = res["saturated"][0]
+    rate = args.serve_load * base["requests"] / base["makespan_s"]
+    res["at_load"] = {"requests_per_s": rate, "runs": [run(0, rate), run(0, rate, adaptive=True)]}
+    pool.close()
+    print(json.dumps(res))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -307,6 +387,8 @@ def main():
     from paper_2411_09317_amd import workload as WL
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
+    if args.serve:
+        return serving_mode(args)
     w = I.CONFIGS[args.workload]
     if args.ctx_fixed:
         w = I.scaled(w, name=w.name + "-fixedctx", ctx_dist="fixed", ctx_lo=args.ctx_fixed, ctx_hi=args.ctx_fixed)

@@ -256,8 +256,23 @@ int pie_prefetch_list(pie_pool* pool, const int32_t* h_block_table, int32_t max_
                       const int32_t* h_ctx_lens, int32_t batch,
                       int32_t* out_prefetch, int32_t* out_n_prefetch, int32_t* out_dirty, int32_t* out_n_dirty);
 
-/* Turns per-layer event timing in pie_step on (1) or off (0, default). */
-int pie_set_timing(pie_pool* pool, int32_t on);
+/* How pie_step monitors itself (the per-layer times the adaptive expansion needs, Section 3.4.2).
+ *   PIE_TIMING_OFF    nothing is measured (default).
+ *   PIE_TIMING_EVENTS HIP events around every piece of work.  Exact for every stream, but an event between
+ *                     two kernels keeps them from running back to back: about 4 us per event, four events
+ *                     per layer on the compute stream.
+ *   PIE_TIMING_CLOCK  the kernels note their own first and last moment (device wall clock, atomic min / max
+ *                     or words of their own that one kernel per step folds), and a one-thread kernel behind
+ *                     each copy on the swap streams notes when it ended.  Nothing is put between the compute
+ *                     stream's kernels.  A layer's compute time then runs from the start of its decode kernel
+ *                     to the end of its last kernel; a copy's time from the moment everything it had to wait
+ *                     for was done (the copy before it on its stream, the compute that frees its staging
+ *                     region) to its end.
+ * pie_get_layer_times and pie_get_stats read whichever the last step used. */
+#define PIE_TIMING_OFF    0
+#define PIE_TIMING_EVENTS 1
+#define PIE_TIMING_CLOCK  2
+int pie_set_timing(pie_pool* pool, int32_t mode);
 
 /* Waits for everything the pool has enqueued on the streams it has seen. */
 int pie_pool_sync(pie_pool* pool);

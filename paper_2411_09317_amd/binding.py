@@ -21,6 +21,7 @@ OK, EINVAL, ENOMEM, ESTATE, EHIP = 0, -1, -2, -3, -4
 GPU, HOST = 0, 1
 SWAP_AUTO, SWAP_DMA, SWAP_KERNEL = 0, 1, 2
 DEVERR_BAD_HANDLE, DEVERR_NOT_PRESENT = 1, 2
+TIMING_OFF, TIMING_EVENTS, TIMING_CLOCK = 0, 1, 2
 
 # every symbol include/pie.h declares
 SYMBOLS = [
@@ -272,8 +273,9 @@ class Pool:
                              _stream_ptr(swap_out_stream)), "step")
 
     # ---- control ---------------------------------------------------------------------------
-    def set_timing(self, on: bool):
-        _check(_lib.pie_set_timing(self._h, C.c_int32(1 if on else 0)), "set_timing")
+    def set_timing(self, mode):
+        """False / TIMING_OFF, True / TIMING_EVENTS, or TIMING_CLOCK (kernels note their own times)."""
+        _check(_lib.pie_set_timing(self._h, C.c_int32(int(mode))), "set_timing")
 
     def sync(self):
         _check(_lib.pie_pool_sync(self._h), "pool_sync")

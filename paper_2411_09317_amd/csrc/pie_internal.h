@@ -27,6 +27,20 @@ constexpr int kMapPatchPairs = 448;   // (handle, slot) pairs passed by value pe
 constexpr int kSwapPairs = 448;       // (src slot, dst slot) pairs passed by value per gather launch
 constexpr uint32_t kAlign = 256;
 
+// The clock table of monitoring by device clock: one row of kClockRow 64-bit words per layer, one more row
+// whose first word is the moment the step began, then kClockWgs pairs of words per layer for the decode
+// kernel's workgroups.  Values are ticks of the device's wall clock.
+constexpr int kClockRow = 8;
+constexpr int kClockKernelStart = 0;  // first workgroup of the layer's decode kernel started
+constexpr int kClockKernelEnd = 1;    // last workgroup of it ended
+constexpr int kClockLayerEnd = 2;     // last compute-stream work of the layer ended (decode, reduction, stand-in)
+constexpr int kClockInStart = 3;      // (not stamped: a copy's start follows from what it waited for)
+constexpr int kClockInEnd = 4;        // the layer's swap-in: its copy has ended
+constexpr int kClockOutStart = 5;     // (not stamped)
+constexpr int kClockOutEnd = 6;       // the layer's write-back has ended
+constexpr int kClockGrid = 7;         // workgroups of the decode kernel that wrote per-workgroup words (0: none)
+constexpr int kClockWgs = 2048;       // per-workgroup (first, last moment) pairs per layer, after the rows
+
 struct Home {
   int32_t where = -1;  // PIE_WHERE_* or -1 = unallocated
   int32_t slot = -1;
@@ -69,6 +83,7 @@ struct pie_pool {
   int32_t* d_plan = nullptr;    // attention planning state: header, ticket counters, items, resolved tables
   int32_t n_cu = 256;           // compute units of the device
   uint32_t* d_err = nullptr;    // device error flags
+  unsigned long long* d_clock = nullptr;   // clock table: (n_layers + 1) rows of kClockRow words
   char* h_kv = nullptr;         // host pool base (host address)
   char* h_kv_dev = nullptr;     // same memory as seen from the device
 
@@ -105,13 +120,13 @@ struct pie_pool {
   int32_t swap_wgs = 64;          // workgroups of the gather / scatter kernel
   float layer_compute_us = 0.f;   // stand-in for the rest of a layer's compute in pie_step (0 = none)
   int32_t wall_clock_khz = 100000;
-  bool timing = false;
+  int32_t timing = 0;             // PIE_TIMING_*
   uint32_t last_err_flags = 0;    // device error flags seen by pie_check_errors_sync so far
 
   // timing of the last step
   std::vector<pie::LayerEvents> lev;
   hipEvent_t ev_step_start = nullptr;
-  bool step_timed = false;
+  int32_t step_timed = 0;         // the timing mode the last step ran with
   uint64_t bytes_in = 0, bytes_out = 0;
 };
 
@@ -132,7 +147,9 @@ inline char* h_block(const pie_pool* p, int32_t layer, int32_t slot) {
 }
 
 // kernel launchers (pie_kernels.hip)
-int launch_busy(double us, int wall_clock_khz, hipStream_t s);
+int launch_busy(double us, int wall_clock_khz, hipStream_t s, unsigned long long* clock_row = nullptr);
+int launch_stamp(unsigned long long* slot, hipStream_t s);
+int launch_clock_fold(unsigned long long* rows, int32_t n_layers, hipStream_t s);
 int launch_map_fill(int32_t* d_map, int32_t n, int32_t value, hipStream_t s);
 int launch_map_patch(int32_t* d_map, const MapPatch& patch, hipStream_t s);
 int launch_zero_u32(uint32_t* d, int32_t n, hipStream_t s);
@@ -146,12 +163,14 @@ constexpr int32_t kAppendStaged = 3;      // staged copies only; GPU-homed tails
 int launch_kv_append(const pie_pool* p, int32_t layer, int32_t n_layers, const void* d_k, const void* d_v,
                      const int32_t* d_table, int32_t max_blocks, const int32_t* d_ctx, int32_t batch,
                      int32_t mode, hipStream_t s);
-int launch_attn_plan(const pie_pool* p, const int32_t* d_ctx, int32_t batch, int32_t max_blocks, hipStream_t s);
+int launch_attn_plan(const pie_pool* p, const int32_t* d_ctx, int32_t batch, int32_t max_blocks, hipStream_t s,
+                     bool reset_clock = false);
 int launch_attn_resolve(const pie_pool* p, const int32_t* d_table, const int32_t* d_ctx, int32_t batch,
                         int32_t max_blocks, bool region0, bool valid0, bool region1, bool valid1, hipStream_t s);
 int launch_attn_decode(const pie_pool* p, int32_t layer, const void* d_q, int32_t max_blocks, const int32_t* d_ctx,
                        int32_t batch, void* d_out, hipStream_t s, hipEvent_t k_start = nullptr,
-                       hipEvent_t k_end = nullptr, int32_t ticket_index = -1);
+                       hipEvent_t k_end = nullptr, int32_t ticket_index = -1,
+                       unsigned long long* clock_row = nullptr);
 int launch_stream_probe(const pie_pool* p, int32_t layer, int32_t max_blocks, int32_t batch, hipStream_t s);
 size_t attn_plan_ints(const pie_config& c);
 size_t attn_workspace_floats(const pie_config& c);

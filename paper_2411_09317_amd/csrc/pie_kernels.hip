@@ -37,21 +37,81 @@ __global__ void k_map_patch(int32_t* __restrict__ map, const MapPatch patch) {
 
 // Occupies a stream for about `ticks` ticks of the constant wall clock: one wave that sleeps and looks at
 // the clock.  max_iter bounds the loop, so the wave exits whatever the clock does.
-__global__ void k_busy(unsigned long long ticks, uint32_t max_iter) {
+__global__ void k_busy(unsigned long long ticks, uint32_t max_iter, unsigned long long* clock) {
   const unsigned long long t0 = wall_clock64();
   for (uint32_t i = 0; i < max_iter; ++i) {
     if (wall_clock64() - t0 >= ticks) break;
     __builtin_amdgcn_s_sleep(16);
   }
+  if (clock && threadIdx.x == 0) atomicMax(&clock[kClockLayerEnd], wall_clock64());
 }
 
-int launch_busy(double us, int wall_clock_khz, hipStream_t s) {
+// ---- device-clock time stamps ---------------------------------------------------------------------------
+// With monitoring by device clock a layer's kernels note when they ran, read from the constant-rate wall
+// clock all compute units share; nothing is recorded between kernels, so they stay back to back.  Each layer
+// has a row of 64-bit words (kClock*).  Atomics on one address cost about 8 ns each and all of it shows in
+// the kernel's duration, so the persistent decode kernel's workgroups write their first and last moment to
+// words of their own (kClockWgs pairs per layer) and k_clock_fold, once per step, folds them into the row;
+// kernels with few workgroups, or few that matter, use atomic min / max on the row directly.  Work on the
+// swap streams is bracketed by k_stamp.
+__global__ void k_stamp(unsigned long long* slot) {
+  if (threadIdx.x == 0) *slot = wall_clock64();
+}
+
+// One workgroup per layer: row[KernelStart / KernelEnd] take in the per-workgroup pairs (row[kClockGrid] of
+// them), and row[LayerEnd] is at least the kernel's end.
+__global__ __launch_bounds__(256) void k_clock_fold(unsigned long long* __restrict__ rows,
+                                                    const unsigned long long* __restrict__ per_wg) {
+  __shared__ unsigned long long s_lo[256], s_hi[256];
+  unsigned long long* row = rows + (size_t)blockIdx.x * kClockRow;
+  const unsigned long long* wg = per_wg + (size_t)blockIdx.x * kClockWgs * 2;
+  unsigned long long n = row[kClockGrid];
+  n = n > (unsigned long long)kClockWgs ? (unsigned long long)kClockWgs : n;
+  unsigned long long lo = ~0ull, hi = 0ull;
+  for (unsigned long long i = threadIdx.x; i < n; i += 256) {
+    const unsigned long long a = wg[2 * i], b = wg[2 * i + 1];
+    lo = a < lo ? a : lo;
+    hi = b > hi ? b : hi;
+  }
+  s_lo[threadIdx.x] = lo;
+  s_hi[threadIdx.x] = hi;
+  __syncthreads();
+  for (int w = 128; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w) {
+      s_lo[threadIdx.x] = s_lo[threadIdx.x + w] < s_lo[threadIdx.x] ? s_lo[threadIdx.x + w] : s_lo[threadIdx.x];
+      s_hi[threadIdx.x] = s_hi[threadIdx.x + w] > s_hi[threadIdx.x] ? s_hi[threadIdx.x + w] : s_hi[threadIdx.x];
+    }
+    __syncthreads();
+  }
+  if (threadIdx.x == 0) {
+    const unsigned long long ks = row[kClockKernelStart], ke = row[kClockKernelEnd], le = row[kClockLayerEnd];
+    const unsigned long long start = s_lo[0] < ks ? s_lo[0] : ks, end = s_hi[0] > ke ? s_hi[0] : ke;
+    row[kClockKernelStart] = start;
+    row[kClockKernelEnd] = end;
+    row[kClockLayerEnd] = le > end ? le : end;
+  }
+}
+
+int launch_clock_fold(unsigned long long* rows, int32_t n_layers, hipStream_t s) {
+  hipLaunchKernelGGL(k_clock_fold, dim3(n_layers), dim3(256), 0, s, rows,
+                     rows + ((size_t)n_layers + 1) * kClockRow);
+  PIE_HIP(hipGetLastError());
+  return PIE_OK;
+}
+
+int launch_stamp(unsigned long long* slot, hipStream_t s) {
+  hipLaunchKernelGGL(k_stamp, dim3(1), dim3(64), 0, s, slot);
+  PIE_HIP(hipGetLastError());
+  return PIE_OK;
+}
+
+int launch_busy(double us, int wall_clock_khz, hipStream_t s, unsigned long long* clock) {
   if (!(us > 0.0)) return PIE_OK;
   const unsigned long long ticks = (unsigned long long)(us * 1e-3 * (double)wall_clock_khz);
   // an iteration takes at least the sleep's 16 x 64 clocks, i.e. well over 0.1 us: 16 iterations per us plus
   // slack always reach the deadline first
   const uint32_t max_iter = (uint32_t)(us * 16.0) + 4096u;
-  hipLaunchKernelGGL(k_busy, dim3(1), dim3(64), 0, s, ticks, max_iter);
+  hipLaunchKernelGGL(k_busy, dim3(1), dim3(64), 0, s, ticks, max_iter, clock);
   PIE_HIP(hipGetLastError());
   return PIE_OK;
 }
@@ -440,11 +500,13 @@ __device__ __forceinline__ int32_t clamp_ctx(int32_t ctx, int32_t max_blocks) {
 // [part * part_tokens, min((part + 1) * part_tokens, context)).  hdr[0] = number of items.  Full items
 // (part_tokens tokens) come first, then one shorter item per sequence whose length is not a multiple of
 // part_tokens (or is <= 0, so that its output is still written), longest first.  Also zeroes the ticket
-// counters of all layers.
+// counters of all layers and, if a clock table is given, resets its rows and notes the time in the row
+// after the last.
 __global__ __launch_bounds__(256) void k_attn_plan(const int32_t* __restrict__ ctx, int32_t batch, int32_t part_tokens,
                                                    int32_t max_blocks, uint2* __restrict__ items,
                                                    int32_t* __restrict__ hdr, uint32_t* __restrict__ counters,
-                                                   int32_t n_counters, uint32_t* __restrict__ err) {
+                                                   int32_t n_counters, uint32_t* __restrict__ err,
+                                                   unsigned long long* __restrict__ clock) {
   __shared__ int32_t s_off[kMaxPlanBatch];   // first full item of the sequence
   __shared__ int32_t s_nf[kMaxPlanBatch];
   __shared__ int32_t s_ctx[kMaxPlanBatch];  // context length, clamped to [0, what the table can name]
@@ -461,6 +523,15 @@ __global__ __launch_bounds__(256) void k_attn_plan(const int32_t* __restrict__ c
     s_rem[b] = (rem > 0 || c <= 0) ? rem : -1;
   }
   for (int32_t i = threadIdx.x; i < n_counters; i += blockDim.x) counters[i] = 0;
+  if (clock) {                                   // one row per launch: min / max slots to their neutral values
+    for (int32_t i = threadIdx.x; i < n_counters; i += blockDim.x) {
+      clock[(size_t)i * kClockRow + kClockKernelStart] = ~0ull;
+      clock[(size_t)i * kClockRow + kClockKernelEnd] = 0ull;
+      clock[(size_t)i * kClockRow + kClockLayerEnd] = 0ull;
+      clock[(size_t)i * kClockRow + kClockGrid] = 0ull;
+    }
+    if (threadIdx.x == 0) clock[(size_t)n_counters * kClockRow] = wall_clock64();   // the step begins
+  }
   __syncthreads();
   if (threadIdx.x == 0) {
     int32_t off = 0, n_short = 0;
@@ -537,6 +608,8 @@ struct AttnArgs {
   float scale_log2e;
   int32_t max_blocks, n_kv_heads, group, part_tokens, n_parts;
   int32_t max_items;         // entries the item list has room for (batch x n_parts)
+  unsigned long long* clock;    // this launch's row of the clock table, or NULL
+  unsigned long long* clock_wg; // with it: a (first, last moment) pair per workgroup, or NULL (atomics on the row)
 };
 
 // LDS floats the MFMA kernel needs for `group` query heads per kv head
@@ -582,6 +655,15 @@ void k_attn_decode_mfma(const AttnArgs a) {
   // stream ends, and the merge of the current unit runs behind those loads.
   uint32_t unit = blockIdx.x;
   uint32_t next = gridDim.x + blockIdx.x;
+  if (a.clock && threadIdx.x == 0) {
+    const unsigned long long t = wall_clock64();
+    if (a.clock_wg) {
+      a.clock_wg[2 * blockIdx.x] = t;
+      if (blockIdx.x == 0) a.clock[kClockGrid] = gridDim.x;
+    } else {
+      atomicMin(&a.clock[kClockKernelStart], t);
+    }
+  }
 
   // record and this wave's slot list of unit u; entries beyond the planned items are never used
   auto fetch_meta = [&](uint32_t u, uint2& r, int32_t& sl) {
@@ -777,6 +859,11 @@ void k_attn_decode_mfma(const AttnArgs a) {
     __syncthreads();                             // all have read the ticket before it is overwritten
     fetch_meta(next, rec_next, my_slot_next);    // consumed when this unit's stream ends
   }
+  if (a.clock && threadIdx.x == 0) {
+    const unsigned long long t = wall_clock64();
+    if (a.clock_wg) a.clock_wg[2 * blockIdx.x + 1] = t;
+    else atomicMax(&a.clock[kClockKernelEnd], t);
+  }
 }
 
 // Calibration: reads exactly the K and V tiles the decode kernel reads for the planned items, in the same
@@ -848,6 +935,7 @@ __global__ __launch_bounds__(kWaves * 64) void k_attn_decode_f32(const AttnArgs 
 
   const int32_t item = blockIdx.x;
   if (item >= a.hdr[0]) return;                   // uniform over the workgroup
+  if (a.clock && threadIdx.x == 0) atomicMin(&a.clock[kClockKernelStart], wall_clock64());
   const int32_t hq = blockIdx.y;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int row = lane & 15, quad = lane >> 4;
@@ -954,6 +1042,7 @@ __global__ __launch_bounds__(kWaves * 64) void k_attn_decode_f32(const AttnArgs 
       w[2 + dim] = A;
     }
   }
+  if (a.clock && threadIdx.x == 0) atomicMax(&a.clock[kClockKernelEnd], wall_clock64());
 }
 
 // Reduction over the partitions of one (sequence, query head): out = sum_s 2^(m_s - M) acc_s / sum_s 2^(m_s - M) l_s.
@@ -1017,6 +1106,10 @@ __global__ __launch_bounds__(256) void k_attn_reduce(const AttnArgs a, int32_t n
     }
     store_elem<E>(a.out, row * HD + dim, Lt > 0.f ? At / Lt : 0.f);
   }
+  // the last workgroups dispatched are the last to end, to within a few of them: those of the last sequence
+  // and one per 16 sequences note the time
+  if (a.clock && threadIdx.x == 0 && (b == (int32_t)gridDim.y - 1 || (hq == 0 && (b & 15) == 15)))
+    atomicMax(&a.clock[kClockLayerEnd], wall_clock64());
 }
 
 // ---- dispatch ----------------------------------------------------------------------------------------
@@ -1073,10 +1166,11 @@ static int32_t part_tokens_of(const pie_pool* p) {
   return part;
 }
 
-int launch_attn_plan(const pie_pool* p, const int32_t* d_ctx, int32_t batch, int32_t max_blocks, hipStream_t s) {
+int launch_attn_plan(const pie_pool* p, const int32_t* d_ctx, int32_t batch, int32_t max_blocks, hipStream_t s,
+                     bool reset_clock) {
   if (batch > kMaxPlanBatch || batch > p->cfg.max_batch || max_blocks > p->cfg.max_blocks_per_seq) return PIE_EINVAL;
   hipLaunchKernelGGL(k_attn_plan, dim3(1), dim3(256), 0, s, d_ctx, batch, part_tokens_of(p), max_blocks, plan_items(p),
-                     plan_hdr(p), plan_counters(p), p->cfg.n_layers, p->d_err);
+                     plan_hdr(p), plan_counters(p), p->cfg.n_layers, p->d_err, reset_clock ? p->d_clock : nullptr);
   PIE_HIP(hipGetLastError());
   return PIE_OK;
 }
@@ -1110,8 +1204,8 @@ int launch_attn_resolve(const pie_pool* p, const int32_t* d_table, const int32_t
 }
 
 template <typename E, int HD, bool SPLIT>
-static int launch_mfma(const pie_pool* p, const AttnArgs& a, int32_t batch, int32_t n_q_heads, hipStream_t s,
-                       hipEvent_t e0, hipEvent_t e1) {
+static int launch_mfma(const pie_pool* p, AttnArgs a, int32_t layer_row, int32_t batch, int32_t n_q_heads,
+                       hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
   const size_t lds = mfma_lds_floats<HD>(a.group) * sizeof(float);
   // as many workgroups as fit on the GPU at once; the ticket counter hands out the work
   static int wgs_per_cu[kMaxGroup + 1] = {};
@@ -1125,6 +1219,8 @@ static int launch_mfma(const pie_pool* p, const AttnArgs& a, int32_t batch, int3
     wgs_per_cu[a.group] = n;
   }
   const int grid = p->n_cu * wgs_per_cu[a.group];
+  if (a.clock && grid <= kClockWgs)
+    a.clock_wg = p->d_clock + ((size_t)p->cfg.n_layers + 1) * kClockRow + (size_t)layer_row * kClockWgs * 2;
   if (e0) PIE_HIP(hipEventRecord(e0, s));
   hipLaunchKernelGGL((k_attn_decode_mfma<E, HD, SPLIT>), dim3(grid), dim3(kWaves * 64), lds, s, a);
   PIE_HIP(hipGetLastError());
@@ -1155,7 +1251,7 @@ static int launch_f32(const AttnArgs& a, int32_t batch, int32_t n_q_heads, int32
 // same batch, table width and context lengths.
 int launch_attn_decode(const pie_pool* p, int32_t layer, const void* d_q, int32_t max_blocks, const int32_t* d_ctx,
                        int32_t batch, void* d_out, hipStream_t s, hipEvent_t k_start, hipEvent_t k_end,
-                       int32_t ticket_index) {
+                       int32_t ticket_index, unsigned long long* clock_row) {
   const pie_config& c = p->cfg;
   if (((uintptr_t)d_q | (uintptr_t)d_out) % 16) return PIE_EINVAL;
   if (max_blocks <= 0) return PIE_EINVAL;
@@ -1187,18 +1283,21 @@ int launch_attn_decode(const pie_pool* p, int32_t layer, const void* d_q, int32_
   a.part_tokens = part;
   a.n_parts = n_parts;
   a.max_items = batch * n_parts;
+  a.clock = clock_row;
+  a.clock_wg = nullptr;         // set by the launcher of a persistent grid that fits the per-workgroup words
   const bool hd128 = c.head_dim == 128;
+  const int32_t row = clock_row ? (int32_t)((clock_row - p->d_clock) / kClockRow) : 0;
   switch (c.dtype) {
     case PIE_DTYPE_F32: {
       return hd128 ? launch_f32<128>(a, batch, c.n_q_heads, a.max_items, s, k_start, k_end)
                    : launch_f32<64>(a, batch, c.n_q_heads, a.max_items, s, k_start, k_end);
     }
     case PIE_DTYPE_F16:
-      return hd128 ? launch_mfma<F16, 128, false>(p, a, batch, c.n_q_heads, s, k_start, k_end)
-                   : launch_mfma<F16, 64, false>(p, a, batch, c.n_q_heads, s, k_start, k_end);
+      return hd128 ? launch_mfma<F16, 128, false>(p, a, row, batch, c.n_q_heads, s, k_start, k_end)
+                   : launch_mfma<F16, 64, false>(p, a, row, batch, c.n_q_heads, s, k_start, k_end);
     case PIE_DTYPE_BF16:
-      return hd128 ? launch_mfma<BF16, 128, true>(p, a, batch, c.n_q_heads, s, k_start, k_end)
-                   : launch_mfma<BF16, 64, true>(p, a, batch, c.n_q_heads, s, k_start, k_end);
+      return hd128 ? launch_mfma<BF16, 128, true>(p, a, row, batch, c.n_q_heads, s, k_start, k_end)
+                   : launch_mfma<BF16, 64, true>(p, a, row, batch, c.n_q_heads, s, k_start, k_end);
     default: return PIE_EINVAL;
   }
 }

@@ -41,7 +41,7 @@ static bool config_ok(const pie_config* c) {
 
 struct Layout {
   size_t block_bytes, d_layer_stride, h_layer_stride;
-  size_t off_map0, off_map1, off_ws, off_plan, off_err, d_total, h_total;
+  size_t off_map0, off_map1, off_ws, off_plan, off_err, off_clock, d_total, h_total;
   size_t ws_floats;
 };
 
@@ -59,6 +59,8 @@ static Layout layout_of(const pie_config& c) {
   l.off_ws = off; off = align_up(off + l.ws_floats * 4, kAlign);
   l.off_plan = off; off = align_up(off + attn_plan_ints(c) * 4, kAlign);
   l.off_err = off; off += kAlign;
+  l.off_clock = off;
+  off = align_up(off + (((size_t)c.n_layers + 1) * kClockRow + (size_t)c.n_layers * kClockWgs * 2) * 8, kAlign);
   l.d_total = off;
   l.h_total = l.h_layer_stride * c.n_layers;
   return l;
@@ -241,8 +243,20 @@ struct StagedAppend {
   int32_t max_blocks, batch;
 };
 
+// A moment on a stream noted for the step's timing: by an event, by a device-clock stamp, or not at all.
+struct Mark {
+  hipEvent_t ev = nullptr;
+  unsigned long long* clk = nullptr;
+};
+
+static int note(const Mark& m, hipStream_t s) {
+  if (m.ev) PIE_HIP(hipEventRecord(m.ev, s));
+  if (m.clk) return launch_stamp(m.clk, s);
+  return PIE_OK;
+}
+
 static int swap_in_impl(pie_pool* p, int32_t layer, int32_t n, const int32_t* handles, hipStream_t s,
-                        bool validated, hipEvent_t t0, hipEvent_t t1, const StagedAppend* job = nullptr) {
+                        bool validated, const Mark& t0, const Mark& t1, const StagedAppend* job = nullptr) {
   const int r = layer & 1;
   if (!validated) {
     if (layer < 0 || layer >= p->cfg.n_layers) return PIE_EINVAL;
@@ -269,9 +283,9 @@ static int swap_in_impl(pie_pool* p, int32_t layer, int32_t n, const int32_t* ha
   if ((rc = order_after(s, p->ev_out[r], p->ev_out_rec[r], on_host))) return rc;
   if ((rc = order_after(s, p->ev_migrate, p->ev_migrate_rec, on_host))) return rc;
   if (job && (rc = order_after(s, p->ev_map, p->ev_map_rec, on_host))) return rc;   // the append reads the map
-  if (t0) PIE_HIP(hipEventRecord(t0, s));
+  if ((rc = note(t0, s))) return rc;
   if ((rc = copy_blocks(p, 0, layer, src, dst, cp, s))) return rc;
-  if (t1) PIE_HIP(hipEventRecord(t1, s));
+  if ((rc = note(t1, s))) return rc;
   if (job && (rc = launch_kv_append(p, layer, 1, job->d_k, job->d_v, job->d_table, job->max_blocks, job->d_ctx,
                                     job->batch, kAppendStaged, s)))
     return rc;
@@ -283,7 +297,7 @@ static int swap_in_impl(pie_pool* p, int32_t layer, int32_t n, const int32_t* ha
 }
 
 static int swap_out_impl(pie_pool* p, int32_t layer, int32_t n, const int32_t* handles, hipStream_t s,
-                         hipEvent_t t0, hipEvent_t t1) {
+                         const Mark& t0, const Mark& t1) {
   if (layer < 0 || layer >= p->cfg.n_layers) return PIE_EINVAL;
   std::vector<uint8_t> seen;
   int rc = check_handles(p, n, handles, PIE_WHERE_HOST, seen);
@@ -303,9 +317,9 @@ static int swap_out_impl(pie_pool* p, int32_t layer, int32_t n, const int32_t* h
   const bool on_host = n > 0 && cp.path == PIE_SWAP_DMA;
   if ((rc = order_after(s, p->ev_in[r], p->ev_in_rec[r], on_host))) return rc;
   if ((rc = order_after(s, p->ev_read[r], p->ev_read_rec[r], on_host))) return rc;
-  if (t0) PIE_HIP(hipEventRecord(t0, s));
+  if ((rc = note(t0, s))) return rc;
   if ((rc = copy_blocks(p, 1, layer, src, dst, cp, s))) return rc;
-  if (t1) PIE_HIP(hipEventRecord(t1, s));
+  if ((rc = note(t1, s))) return rc;
   PIE_HIP(hipEventRecord(p->ev_out[r], s));
   p->ev_out_rec[r] = true;
   p->bytes_out += (uint64_t)n * p->block_bytes;
@@ -403,6 +417,7 @@ int pie_pool_init(const pie_config* cfg, void* d_base, size_t d_bytes, void* h_p
     p->ws_floats = l.ws_floats;
     p->d_plan = (int32_t*)(base + l.off_plan);
     p->d_err = (uint32_t*)(base + l.off_err);
+    p->d_clock = (unsigned long long*)(base + l.off_clock);
     int rc = PIE_OK;
     {
       int dev = 0, n_cu = 0;
@@ -446,6 +461,7 @@ int pie_pool_init(const pie_config* cfg, void* d_base, size_t d_bytes, void* h_p
     if ((rc = launch_map_fill(p->d_map[0], p->n_handles, -1, nullptr))) return fail(rc);
     if ((rc = launch_map_fill(p->d_map[1], p->n_handles, -1, nullptr))) return fail(rc);
     if ((rc = launch_zero_u32(p->d_err, kAlign / 4, nullptr))) return fail(rc);
+    if ((rc = launch_zero_u32((uint32_t*)p->d_clock, (cfg->n_layers + 1) * kClockRow * 2, nullptr))) return fail(rc);
     err = hipStreamSynchronize(nullptr);
     if (err != hipSuccess) { g_last_hip_error = (int)err; return fail(PIE_EHIP); }
   }
@@ -577,12 +593,12 @@ int pie_block_address(pie_pool* p, int32_t where, int32_t layer, int32_t slot, v
 
 int pie_swap_in(pie_pool* p, int32_t layer, int32_t n, const int32_t* handles, void* stream) {
   if (!p) return PIE_EINVAL;
-  return swap_in_impl(p, layer, n, handles, (hipStream_t)stream, false, nullptr, nullptr);
+  return swap_in_impl(p, layer, n, handles, (hipStream_t)stream, false, Mark(), Mark());
 }
 
 int pie_swap_out(pie_pool* p, int32_t layer, int32_t n, const int32_t* handles, void* stream) {
   if (!p) return PIE_EINVAL;
-  return swap_out_impl(p, layer, n, handles, (hipStream_t)stream, nullptr, nullptr);
+  return swap_out_impl(p, layer, n, handles, (hipStream_t)stream, Mark(), Mark());
 }
 
 int pie_migrate(pie_pool* p, int32_t n, const int32_t* handles, int32_t to_where, void* stream) {
@@ -803,21 +819,31 @@ int pie_step(pie_pool* p, const void* d_q_all, const void* d_k_new, const void* 
   const int32_t L = p->cfg.n_layers;
   const size_t q_stride = (size_t)batch * p->cfg.n_q_heads * p->cfg.head_dim * p->elem_bytes;
   const size_t kv_stride = (size_t)batch * p->cfg.n_kv_heads * p->cfg.head_dim * p->elem_bytes;
-  const bool timed = p->timing;
+  // Monitoring: by events (one recorded before and after every piece of work, which keeps the compute
+  // stream's kernels from running back to back) or by the device clock (the kernels note their own times).
+  const bool timed = p->timing == PIE_TIMING_EVENTS, clocked = p->timing == PIE_TIMING_CLOCK;
+  auto clock_row = [&](int32_t l) { return clocked ? p->d_clock + (size_t)l * kClockRow : nullptr; };
+  // by device clock only the end of a copy is stamped (a stamp is a kernel launch the copies behind it wait
+  // for); when it began follows from what it had to wait for
+  auto mark = [&](hipEvent_t ev, int32_t l, int word) {
+    Mark m;
+    if (timed) m.ev = ev;
+    if (clocked && (word == kClockInEnd || word == kClockOutEnd)) m.clk = p->d_clock + (size_t)l * kClockRow + word;
+    return m;
+  };
   p->bytes_in = p->bytes_out = 0;
-  p->step_timed = false;
+  p->step_timed = 0;
   note_stream(p, cs);
-  if (timed) {
-    PIE_HIP(hipEventRecord(p->ev_step_start, cs));
+  if (timed) PIE_HIP(hipEventRecord(p->ev_step_start, cs));
+  if (timed || clocked)
     for (auto& le : p->lev) le.in_used = le.out_used = false;
-  }
   // The prefetch list is the same for every layer, so both staging regions' slot assignments are known now:
   // publish them, send the map changes, and plan the attention work once for the whole step.
   publish_stage_list(p, 0, n_prefetch, h_prefetch);
   if (L > 1) publish_stage_list(p, 1, n_prefetch, h_prefetch);
   if ((rc = wait_if(cs, p->ev_migrate, p->ev_migrate_rec))) return rc;
   if ((rc = flush_map(p, cs))) return rc;
-  if ((rc = launch_attn_plan(p, d_ctx_lens, batch, max_blocks, cs))) return rc;
+  if ((rc = launch_attn_plan(p, d_ctx_lens, batch, max_blocks, cs, clocked))) return rc;
   if ((rc = launch_attn_resolve(p, d_block_table, d_ctx_lens, batch, max_blocks, true, true, L > 1, true, cs)))
     return rc;
   // The new token's rows of every layer go into the GPU-homed tail blocks with one launch up front.  The
@@ -841,10 +867,10 @@ int pie_step(pie_pool* p, const void* d_q_all, const void* d_k_new, const void* 
   }
   // layer 0's blocks have no earlier layer to hide behind
   if (n_prefetch > 0) {
-    if ((rc = swap_in_impl(p, 0, n_prefetch, h_prefetch, is, true, timed ? p->lev[0].in_start : nullptr,
-                           timed ? p->lev[0].in_end : nullptr, job_for(0))))
+    if ((rc = swap_in_impl(p, 0, n_prefetch, h_prefetch, is, true, mark(p->lev[0].in_start, 0, kClockInStart),
+                           mark(p->lev[0].in_end, 0, kClockInEnd), job_for(0))))
       return rc;
-    p->lev[0].in_used = timed;
+    p->lev[0].in_used = timed || clocked;
   }
   for (int32_t l = 0; l < L; ++l) {
     // the presence check: the layer's staged blocks have arrived (migrations and map updates were waited
@@ -853,9 +879,11 @@ int pie_step(pie_pool* p, const void* d_q_all, const void* d_k_new, const void* 
     if (timed) PIE_HIP(hipEventRecord(p->lev[l].attn_start, cs));
     if ((rc = launch_attn_decode(p, l, (const char*)d_q_all + l * q_stride, max_blocks, d_ctx_lens, batch,
                                  (char*)d_out_all + l * q_stride, cs, timed ? p->lev[l].k_start : nullptr,
-                                 timed ? p->lev[l].k_end : nullptr)))
+                                 timed ? p->lev[l].k_end : nullptr, -1, clock_row(l))))
       return rc;
-    if (p->layer_compute_us > 0.f && (rc = launch_busy(p->layer_compute_us, p->wall_clock_khz, cs))) return rc;
+    if (p->layer_compute_us > 0.f &&
+        (rc = launch_busy(p->layer_compute_us, p->wall_clock_khz, cs, clock_row(l))))
+      return rc;
     if (timed) PIE_HIP(hipEventRecord(p->lev[l].attn_end, cs));
     if (n_prefetch > 0) {
       // the next user of this staging region (layer l + 2's prefetch, this layer's write-back) waits for it
@@ -867,28 +895,30 @@ int pie_step(pie_pool* p, const void* d_q_all, const void* d_k_new, const void* 
       // and runs behind this one.  It is enqueued after this layer's kernels because a copy-engine
       // transfer makes the host wait for layer l - 1 here (see order_after): the compute stream must
       // already hold this layer's work then.
-      if ((rc = swap_in_impl(p, l + 1, n_prefetch, h_prefetch, is, true, timed ? p->lev[l + 1].in_start : nullptr,
-                             timed ? p->lev[l + 1].in_end : nullptr, job_for(l + 1))))
+      if ((rc = swap_in_impl(p, l + 1, n_prefetch, h_prefetch, is, true,
+                             mark(p->lev[l + 1].in_start, l + 1, kClockInStart),
+                             mark(p->lev[l + 1].in_end, l + 1, kClockInEnd), job_for(l + 1))))
         return rc;
-      p->lev[l + 1].in_used = timed;
+      p->lev[l + 1].in_used = timed || clocked;
     }
     if (n_dirty > 0 && d_k_new) {
-      if ((rc = swap_out_impl(p, l, n_dirty, h_dirty, os, timed ? p->lev[l].out_start : nullptr,
-                              timed ? p->lev[l].out_end : nullptr)))
+      if ((rc = swap_out_impl(p, l, n_dirty, h_dirty, os, mark(p->lev[l].out_start, l, kClockOutStart),
+                              mark(p->lev[l].out_end, l, kClockOutEnd))))
         return rc;
-      p->lev[l].out_used = timed;
+      p->lev[l].out_used = timed || clocked;
     }
   }
+  if (clocked && (rc = launch_clock_fold(p->d_clock, L, cs))) return rc;
   // later migrations wait for the step's compute work
   PIE_HIP(hipEventRecord(p->ev_compute, cs));
   p->ev_compute_rec = true;
-  p->step_timed = timed;
+  p->step_timed = p->timing;
   return PIE_OK;
 }
 
-int pie_set_timing(pie_pool* p, int32_t on) {
-  if (!p) return PIE_EINVAL;
-  p->timing = on != 0;
+int pie_set_timing(pie_pool* p, int32_t mode) {
+  if (!p || mode < PIE_TIMING_OFF || mode > PIE_TIMING_CLOCK) return PIE_EINVAL;
+  p->timing = mode;
   return PIE_OK;
 }
 
@@ -902,9 +932,54 @@ static int elapsed(hipEvent_t a, hipEvent_t b, float* ms) {
   return PIE_OK;
 }
 
+// The clock table of the last step, copied to the host (the step's streams are waited for first).
+static int read_clock(pie_pool* p, std::vector<unsigned long long>& t) {
+  int rc = pie_pool_sync(p);
+  if (rc) return rc;
+  t.resize(((size_t)p->cfg.n_layers + 1) * kClockRow);
+  PIE_HIP(hipMemcpy(t.data(), p->d_clock, t.size() * sizeof(unsigned long long), hipMemcpyDeviceToHost));
+  return PIE_OK;
+}
+
+static int layer_times_from_clock(pie_pool* p, float* t_attn, float* t_kernel, float* t_in, float* t_out,
+                                  float* t_stall, float* step_ms) {
+  std::vector<unsigned long long> t;
+  int rc = read_clock(p, t);
+  if (rc) return rc;
+  const int32_t L = p->cfg.n_layers;
+  const double per_ms = (double)p->wall_clock_khz;
+  auto at = [&](int32_t l, int w) { return t[(size_t)l * kClockRow + w]; };
+  auto span = [&](unsigned long long a, unsigned long long b) { return b > a ? (float)((double)(b - a) / per_ms) : 0.f; };
+  const unsigned long long step_start = at(L, 0);
+  for (int32_t l = 0; l < L; ++l) {
+    if (t_attn) t_attn[l] = span(at(l, kClockKernelStart), at(l, kClockLayerEnd));
+    if (t_kernel) t_kernel[l] = span(at(l, kClockKernelStart), at(l, kClockKernelEnd));
+    // A swap-in starts when the one before it on its stream has ended and the staging region is free, i.e.
+    // the layer two back has been computed; a write-back when its layer has been computed and the one
+    // before it has ended.
+    if (t_in) {
+      unsigned long long from = l >= 2 ? at(l - 2, kClockLayerEnd) : step_start;
+      if (l >= 1 && p->lev[l - 1].in_used && at(l - 1, kClockInEnd) > from) from = at(l - 1, kClockInEnd);
+      t_in[l] = p->lev[l].in_used ? span(from, at(l, kClockInEnd)) : 0.f;
+    }
+    if (t_out) {
+      unsigned long long from = at(l, kClockLayerEnd);
+      if (l >= 1 && p->lev[l - 1].out_used && at(l - 1, kClockOutEnd) > from) from = at(l - 1, kClockOutEnd);
+      t_out[l] = p->lev[l].out_used ? span(from, at(l, kClockOutEnd)) : 0.f;
+    }
+    if (t_stall) {
+      const unsigned long long free_at = l == 0 ? step_start : at(l - 1, kClockLayerEnd);
+      t_stall[l] = p->lev[l].in_used ? span(free_at, at(l, kClockInEnd)) : 0.f;
+    }
+  }
+  if (step_ms) *step_ms = span(step_start, at(L - 1, kClockLayerEnd));
+  return PIE_OK;
+}
+
 int pie_get_layer_times(pie_pool* p, float* t_attn, float* t_kernel, float* t_in, float* t_out, float* t_stall) {
   if (!p) return PIE_EINVAL;
   if (!p->device || !p->step_timed) return PIE_ESTATE;
+  if (p->step_timed == PIE_TIMING_CLOCK) return layer_times_from_clock(p, t_attn, t_kernel, t_in, t_out, t_stall, nullptr);
   const int32_t L = p->cfg.n_layers;
   int rc;
   for (int32_t l = 0; l < L; ++l) {
@@ -957,7 +1032,9 @@ int pie_get_stats(pie_pool* p, pie_stats* out) {
   if (p->device && p->step_timed) {
     const int32_t n = p->cfg.n_layers;
     std::vector<float> a(n), i(n), o(n), s(n);
-    int rc = pie_get_layer_times(p, a.data(), nullptr, i.data(), o.data(), s.data());
+    const bool clocked = p->step_timed == PIE_TIMING_CLOCK;
+    int rc = clocked ? layer_times_from_clock(p, a.data(), nullptr, i.data(), o.data(), s.data(), &out->step_ms)
+                     : pie_get_layer_times(p, a.data(), nullptr, i.data(), o.data(), s.data());
     if (rc) return rc;
     for (int32_t l = 0; l < n; ++l) {
       out->attn_ms += a[l];
@@ -965,7 +1042,7 @@ int pie_get_stats(pie_pool* p, pie_stats* out) {
       out->swap_out_ms += o[l];
       out->stall_ms += s[l];
     }
-    if ((rc = elapsed(p->ev_step_start, p->lev[n - 1].attn_end, &out->step_ms))) return rc;
+    if (!clocked && (rc = elapsed(p->ev_step_start, p->lev[n - 1].attn_end, &out->step_ms))) return rc;
   }
   out->device_error_flags = p->last_err_flags;
   return PIE_OK;

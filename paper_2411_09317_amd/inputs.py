@@ -95,6 +95,17 @@ def draw_ctx_lens(w: Workload) -> np.ndarray:
     return ctx.astype(np.int32)
 
 
+def draw_requests(w: Workload, n: int, rate_per_s: float, out_lo: int, out_hi: int):
+    """A seeded request stream: Poisson arrivals (exponential gaps, `rate_per_s` requests per second), prompt
+    lengths from the workload's context-length distribution, output lengths uniform in [out_lo, out_hi].
+    Returns (arrival seconds float64[n], prompt_len int32[n], output_len int32[n])."""
+    g = rng_for(w, 5)
+    arrival = np.cumsum(g.exponential(1.0 / rate_per_s, size=n))
+    prompt = draw_ctx_lens(scaled(w, batch=n, seed=w.seed + 7919))
+    output = g.integers(out_lo, out_hi + 1, size=n).astype(np.int32)
+    return arrival, prompt, output
+
+
 def blocks_needed(ctx_lens: np.ndarray, block_tokens: int) -> np.ndarray:
     return (ctx_lens.astype(np.int64) + block_tokens - 1) // block_tokens
 

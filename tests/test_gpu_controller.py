@@ -44,7 +44,7 @@ def test_controller_grows_while_swaps_stay_hidden_and_gives_back_when_they_do_no
     streams = (torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream())
     ctl = B.Controller(UNITS, K_MAX, rho=RHO)
     try:
-        dw.pool.set_timing(True)
+        dw.pool.set_timing(B.TIMING_CLOCK)
         dw.pool.set_layer_compute_us(3000.0)
         level, trace = drive(dw, ctl, streams, 70, 0)
         levels = [t[0] for t in trace]

@@ -259,3 +259,45 @@ def test_step_argument_checks():
         lib.step(q, None, None, tb, cl, pf[:2], pf[2:3], out)        # dirty block not among the prefetched
     assert e.value.code == B.ESTATE
     lib.close()
+
+
+@pytest.mark.parametrize("path", [B.SWAP_DMA, B.SWAP_KERNEL])
+def test_monitoring_by_device_clock_agrees_with_events_and_changes_no_result(path):
+    """The two ways of timing a step measure the same things (loosely: the runs differ, and events add gaps),
+    and neither changes an output bit."""
+    w = I.Workload("clock", 4, 12, 16, 4, 128, I.DTYPE_F16, ctx_lo=1500, ctx_hi=2500, value_scale=0.5, host_fraction=0.2, seed=53)
+    case = host_tails(I.make_case(w))
+    n = int(case.n_blocks.sum())
+    lib, mod, table = GH.make_pools(case, n, n // 3, n // 3, upto_ctx=case.ctx_lens - 1)
+    lib.set_swap_path(path)
+    lib.set_layer_compute_us(150.0)
+    streams = (torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream())
+    res = {}
+    for mode in (B.TIMING_OFF, B.TIMING_EVENTS, B.TIMING_CLOCK, B.TIMING_EVENTS, B.TIMING_CLOCK):
+        got, pf, dirty = run_step(lib, case, table, streams, timing=mode)
+        if mode == B.TIMING_OFF:
+            with pytest.raises(B.PieError) as e:
+                lib.layer_times()
+            assert e.value.code == B.ESTATE
+            base = got
+            continue
+        assert np.array_equal(got, base)
+        st = lib.stats()
+        res[mode] = (lib.layer_times(), st.step_ms, st.attn_ms, st.swap_in_ms, st.stall_ms)
+    assert lib.check_errors() == 0
+    (le, step_e, attn_e, in_e, stall_e), (lc, step_c, attn_c, in_c, stall_c) = res[B.TIMING_EVENTS], res[B.TIMING_CLOCK]
+    for key in ("attn", "kernel", "swap_in", "swap_out"):
+        assert (lc[key] > 0).all() and (le[key] > 0).all(), key
+        # with the gather kernel on the swap stream the decode kernel's last workgroups may have to wait for a
+        # compute unit, differently from run to run: only the copy-engine path is compared closely
+        if path == B.SWAP_DMA:
+            assert np.allclose(lc[key], le[key], rtol=0.5, atol=0.04), (key, lc[key], le[key])
+        else:
+            assert (lc[key] < 5.0).all(), (key, lc[key])
+    assert (lc["attn"] >= 0.150).all() and (lc["attn"] >= lc["kernel"]).all()     # the stand-in is part of a layer
+    assert (lc["stall"] >= 0).all() and lc["stall"][0] > 0                        # layer 0's prefetch hides behind nothing
+    assert step_c >= attn_c * 0.99
+    if path == B.SWAP_DMA:
+        assert step_c == pytest.approx(step_e, rel=0.5)
+        assert in_c == pytest.approx(in_e, rel=0.5, abs=0.05)
+    lib.close()
