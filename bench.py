@@ -56,7 +56,8 @@ def parse():
                          "(GPU layer slots = layers - m, CPU slots = m + 2); adds 'layer_fifo'")
     ap.add_argument("--t-other-us", type=float, default=0.0,
                     help="experiments only: keep the compute stream busy this long after each layer's attention, standing "
-                         "for the rest of a transformer layer (default 0 = the measured path)")
+                         "for the rest of a transformer layer (default 0 = the measured path; -1 = the time to read the "
+                         "layer's weights once at the rate the stream probe measures on this workload)")
     ap.add_argument("--serve", type=int, default=0,
                     help="experiment instead of the benchmark line: serve this many synthetic requests (Poisson arrivals, "
                          "iteration-level scheduling) on a GPU pool of --serve-gpu-blocks blocks per layer at the expansion "
@@ -407,10 +408,15 @@ def main():
     dw.pool.set_swap_path(args.swap_path)
     if args.swap_wgs:
         dw.pool.set_swap_workgroups(args.swap_wgs)
-    if args.t_other_us:
-        dw.pool.set_layer_compute_us(args.t_other_us)
     streams = (torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream())
     none = np.zeros(0, dtype=np.int32)
+    timed_steps(dw, streams, 1, none, none)       # first touch of everything
+    probe_ms = float(np.mean([dw.pool.attn_stream_probe(l % w.n_layers, dw.d_table, dw.d_ctx, streams[0])
+                              for l in range(2 * min(w.n_layers, 8))][2:]))
+    if args.t_other_us < 0:                       # the rest of a layer as the time to stream its weights once
+        args.t_other_us = w.layer_weight_bytes / (dw.kv_bytes_per_layer / probe_ms) * 1e3
+    if args.t_other_us:
+        dw.pool.set_layer_compute_us(args.t_other_us)
 
     if args.calib_copy_mib:
         n = args.calib_copy_mib * (1 << 20) // 4
@@ -430,8 +436,6 @@ def main():
     p10, p50, p90 = step_distribution(dw, streams, min(args.steps, 20), none, none)
     assert dw.pool.check_errors() == 0
     k_ms = float(np.mean(prof["kernel"]))
-    probe_ms = float(np.mean([dw.pool.attn_stream_probe(l % w.n_layers, dw.d_table, dw.d_ctx, streams[0])
-                              for l in range(2 * min(w.n_layers, 8))][2:]))
     bytes_layer = dw.kv_bytes_per_layer
     achieved = bytes_layer / (k_ms * 1e-3) / 1e9
     elem = {0: "f32", 1: "f16", 2: "bf16"}[w.dtype]
@@ -444,7 +448,7 @@ def main():
                                f"[{w.ctx_lo},{w.ctx_hi}], all KV GPU-resident",
                    "context_tokens": int(dw.ctx_lens.sum()), "kv_bytes_per_layer": bytes_layer,
                    "kv_blocks_per_layer": dw.total_blocks, "attn_partition_tokens": args.partition or 512,
-                   "t_other_us": args.t_other_us,
+                   "t_other_us": args.t_other_us, "layer_weight_bytes": w.layer_weight_bytes,
                    "build_s": round(t_build, 1)},
         "roofline": {"bound": "hbm", "kernel": "k_attn_decode_mfma", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,

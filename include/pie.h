@@ -109,6 +109,7 @@ typedef struct {
   uint64_t bytes_in;            /* host -> GPU bytes moved by the last pie_step */
   uint64_t bytes_out;
   uint32_t device_error_flags;  /* PIE_DEVERR_* collected by pie_check_errors_sync calls so far */
+  uint32_t first_layer_prestaged; /* 1: the last pie_step found layer 0's host blocks already staged by the step before */
 } pie_stats;
 
 #define PIE_DEVERR_BAD_HANDLE   1u  /* a block-table entry outside [0, n_handles) inside a sequence's context */
@@ -255,6 +256,13 @@ int pie_step(pie_pool* pool, const void* d_q_all, const void* d_k_new, const voi
 int pie_prefetch_list(pie_pool* pool, const int32_t* h_block_table, int32_t max_blocks,
                       const int32_t* h_ctx_lens, int32_t batch,
                       int32_t* out_prefetch, int32_t* out_n_prefetch, int32_t* out_dirty, int32_t* out_n_dirty);
+
+/* pie_step ends by bringing layer 0's host blocks in again, behind its last layer, for the step that follows
+ * (the paper's swapping runs around the layer loop, token after token: Section 3.3's worked example); the
+ * next pie_step uses them if it is given the same prefetch list and none of those blocks was freed, moved or
+ * swapped in between, else it copies as usual.  On by default; 0 turns it off.  Whoever writes into the
+ * host pool's memory directly between two steps must turn it off or call pie_swap_in for layer 0 afterwards. */
+int pie_set_cross_step_prefetch(pie_pool* pool, int32_t on);
 
 /* How pie_step monitors itself (the per-layer times the adaptive expansion needs, Section 3.4.2).
  *   PIE_TIMING_OFF    nothing is measured (default).

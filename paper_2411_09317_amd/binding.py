@@ -30,7 +30,7 @@ SYMBOLS = [
     "pie_migrate", "pie_set_host_fraction", "pie_set_swap_path", "pie_set_attn_partition", "pie_set_swap_workgroups",
     "pie_set_layer_compute_us",
     "pie_kv_append", "pie_attn_decode", "pie_attn_stream_probe_sync",
-    "pie_step", "pie_prefetch_list", "pie_set_timing", "pie_pool_sync", "pie_get_stats", "pie_get_layer_times",
+    "pie_step", "pie_prefetch_list", "pie_set_timing", "pie_set_cross_step_prefetch", "pie_pool_sync", "pie_get_stats", "pie_get_layer_times",
     "pie_check_errors_sync", "pie_controller_create", "pie_controller_destroy", "pie_controller_config",
     "pie_controller_observe", "pie_controller_level", "pie_controller_update", "pie_last_hip_error", "pie_strerror",
     "pie_version",
@@ -61,7 +61,7 @@ class PieStats(C.Structure):
                 ("host_fraction", C.c_float), ("expansion_simple", C.c_float), ("expansion_staged", C.c_float),
                 ("step_ms", C.c_float), ("attn_ms", C.c_float), ("swap_in_ms", C.c_float), ("swap_out_ms", C.c_float),
                 ("stall_ms", C.c_float), ("bytes_in", C.c_uint64), ("bytes_out", C.c_uint64),
-                ("device_error_flags", C.c_uint32)]
+                ("device_error_flags", C.c_uint32), ("first_layer_prestaged", C.c_uint32)]
 
 
 def _load():
@@ -273,6 +273,9 @@ class Pool:
                              _stream_ptr(swap_out_stream)), "step")
 
     # ---- control ---------------------------------------------------------------------------
+    def set_cross_step_prefetch(self, on: bool):
+        _check(_lib.pie_set_cross_step_prefetch(self._h, C.c_int32(1 if on else 0)), "set_cross_step_prefetch")
+
     def set_timing(self, mode):
         """False / TIMING_OFF, True / TIMING_EVENTS, or TIMING_CLOCK (kernels note their own times)."""
         _check(_lib.pie_set_timing(self._h, C.c_int32(int(mode))), "set_timing")

@@ -127,6 +127,14 @@ struct pie_pool {
   std::vector<pie::LayerEvents> lev;
   hipEvent_t ev_step_start = nullptr;
   int32_t step_timed = 0;         // the timing mode the last step ran with
+  // the first layer's blocks staged ahead, behind the previous step's last layer
+  bool cross_step_prefetch = true;
+  bool pre_valid = false;         // region 0 holds layer 0's blocks of stage_list[0], nothing has changed since
+  int32_t pre_timed = 0;          // timing mode that copy was issued under
+  bool step_pre_hit = false;      // the last step found them there
+  int32_t step_pre_timed = 0;
+  int32_t pre_idx = 0, step_pre_idx = 0;
+  hipEvent_t ev_pre_end[2] = {nullptr, nullptr};
   uint64_t bytes_in = 0, bytes_out = 0;
 };
 

@@ -255,9 +255,13 @@ static int note(const Mark& m, hipStream_t s) {
   return PIE_OK;
 }
 
+// skip_copy: the region already holds exactly these blocks of this layer (brought in behind the previous
+// step's last layer); only the ordering, the staged append and the completion event are enqueued.
 static int swap_in_impl(pie_pool* p, int32_t layer, int32_t n, const int32_t* handles, hipStream_t s,
-                        bool validated, const Mark& t0, const Mark& t1, const StagedAppend* job = nullptr) {
+                        bool validated, const Mark& t0, const Mark& t1, const StagedAppend* job = nullptr,
+                        bool skip_copy = false) {
   const int r = layer & 1;
+  p->pre_valid = false;
   if (!validated) {
     if (layer < 0 || layer >= p->cfg.n_layers) return PIE_EINVAL;
     if (n < 0 || (n > 0 && !handles)) return PIE_EINVAL;
@@ -276,6 +280,8 @@ static int swap_in_impl(pie_pool* p, int32_t layer, int32_t n, const int32_t* ha
     dst[i] = stage_slot(p, r, i);
   }
   const CopyPlan cp = plan_copy(p, src, dst);
+  // (also when the copy itself is skipped: a wait enqueued on this stream would make the copy-engine
+  // transfers that follow on it block the host)
   const bool on_host = n > 0 && cp.path == PIE_SWAP_DMA;
   // the region may still be read by compute or written back
   int rc;
@@ -283,16 +289,18 @@ static int swap_in_impl(pie_pool* p, int32_t layer, int32_t n, const int32_t* ha
   if ((rc = order_after(s, p->ev_out[r], p->ev_out_rec[r], on_host))) return rc;
   if ((rc = order_after(s, p->ev_migrate, p->ev_migrate_rec, on_host))) return rc;
   if (job && (rc = order_after(s, p->ev_map, p->ev_map_rec, on_host))) return rc;   // the append reads the map
-  if ((rc = note(t0, s))) return rc;
-  if ((rc = copy_blocks(p, 0, layer, src, dst, cp, s))) return rc;
-  if ((rc = note(t1, s))) return rc;
+  if (!skip_copy) {
+    if ((rc = note(t0, s))) return rc;
+    if ((rc = copy_blocks(p, 0, layer, src, dst, cp, s))) return rc;
+    if ((rc = note(t1, s))) return rc;
+  }
   if (job && (rc = launch_kv_append(p, layer, 1, job->d_k, job->d_v, job->d_table, job->max_blocks, job->d_ctx,
                                     job->batch, kAppendStaged, s)))
     return rc;
   // phase two happens when this event completes
   PIE_HIP(hipEventRecord(p->ev_in[r], s));
   p->ev_in_rec[r] = true;
-  p->bytes_in += (uint64_t)n * p->block_bytes;
+  if (!skip_copy) p->bytes_in += (uint64_t)n * p->block_bytes;
   return PIE_OK;
 }
 
@@ -447,6 +455,10 @@ int pie_pool_init(const pie_config* cfg, void* d_base, size_t d_bytes, void* h_p
     }
     hipError_t err = hipEventCreate(&p->ev_step_start);
     if (err != hipSuccess) { g_last_hip_error = (int)err; return fail(PIE_EHIP); }
+    for (hipEvent_t* e : {&p->ev_pre_end[0], &p->ev_pre_end[1]}) {
+      err = hipEventCreate(e);
+      if (err != hipSuccess) { g_last_hip_error = (int)err; return fail(PIE_EHIP); }
+    }
     p->lev.resize(cfg->n_layers);
     for (auto& le : p->lev) {
       hipEvent_t* tev[] = {&le.attn_start, &le.attn_end, &le.k_start, &le.k_end,
@@ -481,7 +493,7 @@ int pie_pool_destroy(pie_pool* p) {
   if (p->device) {
     for (hipStream_t s : p->streams_seen) (void)hipStreamSynchronize(s);
     hipEvent_t evs[] = {p->ev_in[0], p->ev_in[1], p->ev_read[0], p->ev_read[1], p->ev_out[0], p->ev_out[1],
-                        p->ev_compute, p->ev_migrate, p->ev_map, p->ev_step_start};
+                        p->ev_compute, p->ev_migrate, p->ev_map, p->ev_step_start, p->ev_pre_end[0], p->ev_pre_end[1]};
     for (hipEvent_t e : evs)
       if (e) (void)hipEventDestroy(e);
     for (auto& le : p->lev) {
@@ -831,6 +843,14 @@ int pie_step(pie_pool* p, const void* d_q_all, const void* d_k_new, const void* 
     if (clocked && (word == kClockInEnd || word == kClockOutEnd)) m.clk = p->d_clock + (size_t)l * kClockRow + word;
     return m;
   };
+  // Region 0 may already hold layer 0's blocks: the previous step brought them in behind its last layer.
+  bool pre_hit = p->pre_valid && n_prefetch > 0 && p->region_layer[0] == 0 &&
+                 (int32_t)p->stage_list[0].size() == n_prefetch;
+  for (int32_t i = 0; pre_hit && i < n_prefetch; ++i) pre_hit = p->stage_list[0][i] == h_prefetch[i];
+  p->pre_valid = false;
+  p->step_pre_hit = pre_hit;
+  p->step_pre_timed = pre_hit ? p->pre_timed : 0;
+  p->step_pre_idx = p->pre_idx;                  // which of the two time marks that copy wrote
   p->bytes_in = p->bytes_out = 0;
   p->step_timed = 0;
   note_stream(p, cs);
@@ -868,9 +888,9 @@ int pie_step(pie_pool* p, const void* d_q_all, const void* d_k_new, const void* 
   // layer 0's blocks have no earlier layer to hide behind
   if (n_prefetch > 0) {
     if ((rc = swap_in_impl(p, 0, n_prefetch, h_prefetch, is, true, mark(p->lev[0].in_start, 0, kClockInStart),
-                           mark(p->lev[0].in_end, 0, kClockInEnd), job_for(0))))
+                           mark(p->lev[0].in_end, 0, kClockInEnd), job_for(0), pre_hit)))
       return rc;
-    p->lev[0].in_used = timed || clocked;
+    p->lev[0].in_used = (timed || clocked) && !pre_hit;
   }
   for (int32_t l = 0; l < L; ++l) {
     // the presence check: the layer's staged blocks have arrived (migrations and map updates were waited
@@ -908,11 +928,30 @@ int pie_step(pie_pool* p, const void* d_q_all, const void* d_k_new, const void* 
       p->lev[l].out_used = timed || clocked;
     }
   }
+  // The next step will most likely touch the same host blocks: bring layer 0's in now, behind this step's
+  // last layer, into the region the layer before last has just left (the staged append of the next token's
+  // rows waits for the next step).  If anything about those blocks changes first, the copy is repeated.
+  if (p->cross_step_prefetch && n_prefetch > 0 && L >= 2) {
+    Mark m1;                                     // two marks in turn: the step that uses the copy reads its mark
+    p->pre_idx ^= 1;                             // after this step has written the other one
+    if (timed) m1.ev = p->ev_pre_end[p->pre_idx];
+    if (clocked) m1.clk = p->d_clock + (size_t)L * kClockRow + 1 + p->pre_idx;
+    if ((rc = swap_in_impl(p, 0, n_prefetch, h_prefetch, is, true, Mark(), m1, nullptr))) return rc;
+    p->pre_valid = true;
+    p->pre_timed = p->timing;
+  }
   if (clocked && (rc = launch_clock_fold(p->d_clock, L, cs))) return rc;
   // later migrations wait for the step's compute work
   PIE_HIP(hipEventRecord(p->ev_compute, cs));
   p->ev_compute_rec = true;
   p->step_timed = p->timing;
+  return PIE_OK;
+}
+
+int pie_set_cross_step_prefetch(pie_pool* p, int32_t on) {
+  if (!p) return PIE_EINVAL;
+  p->cross_step_prefetch = on != 0;
+  if (!on) p->pre_valid = false;
   return PIE_OK;
 }
 
@@ -970,6 +1009,9 @@ static int layer_times_from_clock(pie_pool* p, float* t_attn, float* t_kernel, f
     if (t_stall) {
       const unsigned long long free_at = l == 0 ? step_start : at(l - 1, kClockLayerEnd);
       t_stall[l] = p->lev[l].in_used ? span(free_at, at(l, kClockInEnd)) : 0.f;
+      // a first layer staged by the step before: what was left of that copy when this step began
+      if (l == 0 && p->step_pre_hit && p->step_pre_timed == PIE_TIMING_CLOCK)
+        t_stall[0] = span(step_start, at(L, 1 + p->step_pre_idx));
     }
   }
   if (step_ms) *step_ms = span(step_start, at(L - 1, kClockLayerEnd));
@@ -1009,6 +1051,9 @@ int pie_get_layer_times(pie_pool* p, float* t_attn, float* t_kernel, float* t_in
       if (p->lev[l].in_used &&
           (rc = elapsed(l == 0 ? p->ev_step_start : p->lev[l - 1].attn_end, p->lev[l].in_end, &ms)))
         return rc;
+      if (l == 0 && p->step_pre_hit && p->step_pre_timed == PIE_TIMING_EVENTS &&
+          (rc = elapsed(p->ev_step_start, p->ev_pre_end[p->step_pre_idx], &ms)))
+        return rc;
       t_stall[l] = ms > 0.f ? ms : 0.f;
     }
   }
@@ -1045,6 +1090,7 @@ int pie_get_stats(pie_pool* p, pie_stats* out) {
     if (!clocked && (rc = elapsed(p->ev_step_start, p->lev[n - 1].attn_end, &out->step_ms))) return rc;
   }
   out->device_error_flags = p->last_err_flags;
+  out->first_layer_prestaged = p->step_pre_hit ? 1u : 0u;
   return PIE_OK;
 }
 

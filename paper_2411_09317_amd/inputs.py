@@ -42,6 +42,7 @@ class Workload:
     value_scale: float = 1.0
     host_fraction: float = 0.0
     seed: int = 0
+    ffn_dim: int = 0                   # MLP width of the public architecture the shape is taken from (0: none)
 
     @property
     def elem_bytes(self) -> int:
@@ -55,19 +56,27 @@ class Workload:
     def kv_bytes_per_token_layer(self) -> int:
         return 2 * self.n_kv_heads * self.head_dim * self.elem_bytes
 
+    @property
+    def layer_weight_bytes(self) -> int:
+        """Bytes of one transformer layer's weights for this shape at the cache's element size: query and
+        output projections (hidden x hidden), key and value projections (hidden x kv width), and a gated MLP
+        of three hidden x ffn_dim matrices."""
+        hidden, kv = self.n_q_heads * self.head_dim, self.n_kv_heads * self.head_dim
+        return (2 * hidden * hidden + 2 * hidden * kv + 3 * hidden * self.ffn_dim) * self.elem_bytes
+
 
 # The five workloads the build is measured and parity-tested on.
 CONFIGS: Dict[str, Workload] = {
     "cfg1": Workload("cfg1", 1, 4, 8, 8, 64, DTYPE_F32, ctx_dist="uniform", ctx_lo=64, ctx_hi=256,
                      value_scale=1.0, host_fraction=0.25, seed=0),
     "cfg2": Workload("cfg2", 32, 64, 32, 32, 128, DTYPE_F16, ctx_dist="uniform", ctx_lo=1024, ctx_hi=2048,
-                     value_scale=0.5, host_fraction=0.0, seed=1),
+                     value_scale=0.5, host_fraction=0.0, seed=1, ffn_dim=11008),
     "cfg3": Workload("cfg3", 32, 64, 32, 32, 128, DTYPE_F16, ctx_dist="uniform", ctx_lo=1024, ctx_hi=2048,
-                     value_scale=0.5, host_fraction=0.30, seed=2),
+                     value_scale=0.5, host_fraction=0.30, seed=2, ffn_dim=11008),
     "cfg4": Workload("cfg4", 32, 256, 32, 8, 128, DTYPE_BF16, ctx_dist="lognormal", ctx_lo=128, ctx_hi=4096,
-                     ctx_median=1024, ctx_sigma=0.7, value_scale=0.5, host_fraction=0.0, seed=3),
+                     ctx_median=1024, ctx_sigma=0.7, value_scale=0.5, host_fraction=0.0, seed=3, ffn_dim=14336),
     "cfg5": Workload("cfg5", 80, 32, 64, 8, 128, DTYPE_BF16, ctx_dist="fixed", ctx_lo=32768, ctx_hi=32768,
-                     value_scale=0.5, host_fraction=0.0, seed=4),
+                     value_scale=0.5, host_fraction=0.0, seed=4, ffn_dim=28672),
 }
 
 

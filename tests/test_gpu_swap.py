@@ -232,10 +232,11 @@ def test_two_steps_in_a_row_and_timing_stats():
         assert_images_equal(lib, mod, staging=False)
         st = lib.stats()
         lt = lib.layer_times()
-        assert st.bytes_in == len(pf) * lib.block_bytes * w.n_layers
+        # every layer's blocks, and layer 0's once more for the step that follows
+        assert st.bytes_in == len(pf) * lib.block_bytes * (w.n_layers + 1 - st.first_layer_prestaged)
         assert st.bytes_out == len(dirty) * lib.block_bytes * w.n_layers
         assert st.step_ms > 0 and st.attn_ms > 0 and st.swap_in_ms > 0
-        assert (lt["attn"] > 0).all() and (lt["swap_in"] > 0).all() and (lt["stall"] >= 0).all()
+        assert (lt["attn"] > 0).all() and (lt["swap_in"][st.first_layer_prestaged:] > 0).all() and (lt["stall"] >= 0).all()
         assert st.step_ms >= st.attn_ms * 0.99
     assert lib.check_errors() == 0
     lib.close()
@@ -270,6 +271,7 @@ def test_monitoring_by_device_clock_agrees_with_events_and_changes_no_result(pat
     n = int(case.n_blocks.sum())
     lib, mod, table = GH.make_pools(case, n, n // 3, n // 3, upto_ctx=case.ctx_lens - 1)
     lib.set_swap_path(path)
+    lib.set_cross_step_prefetch(False)          # every step alike: all layers' copies inside the step
     lib.set_layer_compute_us(150.0)
     streams = (torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream())
     res = {}
@@ -300,4 +302,64 @@ def test_monitoring_by_device_clock_agrees_with_events_and_changes_no_result(pat
     if path == B.SWAP_DMA:
         assert step_c == pytest.approx(step_e, rel=0.5)
         assert in_c == pytest.approx(in_e, rel=0.5, abs=0.05)
+    lib.close()
+
+
+@pytest.mark.parametrize("path", [B.SWAP_DMA, B.SWAP_KERNEL])
+def test_first_layer_staged_behind_the_previous_step(path):
+    """Consecutive tokens with the same host blocks: from the second step on layer 0's blocks are already in
+    their staging region (brought in behind the previous step's last layer), results and pool bytes stay those
+    of the model, and anything that changes a staged block makes the next step copy again."""
+    w = I.scaled(W, n_layers=4)
+    case = I.make_case(w)
+    c = case.ctx_lens.astype(np.int64)
+    base = np.where((c - 1) % 16 >= 3, c, ((c - 1) // 16) * 16).astype(np.int32)   # base-3 .. base share a block
+    for b in range(0, w.batch, 2):
+        case.host_mask[b][(int(base[b]) - 1) // 16] = True                           # host-homed tails
+    n = int(case.n_blocks.sum())
+    case.ctx_lens = base
+    lib, mod, table = GH.make_pools(case, n, n, n, upto_ctx=base - 4)
+    lib.set_swap_path(path)
+    streams = (torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream())
+    L, bb = w.n_layers, lib.block_bytes
+
+    def one(ctx, expect_hit, timing):
+        case.ctx_lens = ctx
+        got, pf, dirty = run_step(lib, case, table, streams, timing=timing)
+        ref = mod.step(case.q, *new_token_rows(case), table, case.ctx_lens)
+        assert GH.rowwise_rel_err(got, ref) <= 2e-3
+        for l in range(L):
+            assert GH.rowwise_rel_err(got[l], A.dense_attention(*H.dense_f64(case, l), case.ctx_lens)) <= 2e-3
+        assert_images_equal(lib, mod, staging=False)
+        st = lib.stats()
+        assert st.first_layer_prestaged == (1 if expect_hit else 0)
+        assert len(dirty) > 0
+        return st, pf
+
+    for i, timing in enumerate((B.TIMING_OFF, B.TIMING_CLOCK, B.TIMING_CLOCK, B.TIMING_EVENTS, B.TIMING_EVENTS)):
+        st, pf = one(base - 3 + min(i, 3), expect_hit=i > 0, timing=timing)
+        assert st.bytes_in == len(pf) * bb * (L + (0 if i > 0 else 1))
+        if timing:
+            lt = lib.layer_times()
+            assert lt["swap_in"][0] == 0 and (lt["swap_in"][1:] > 0).all()
+            assert 0 <= lt["stall"][0] < 5.0 and st.stall_ms >= lt["stall"][0]
+    # a staged block moves to the GPU pool: the next step must not trust the region
+    lib.migrate([int(pf[0])], B.GPU, streams[1])
+    lib.sync()
+    mod.migrate([int(pf[0])], B.GPU)
+    st, pf2 = one(base, expect_hit=False, timing=B.TIMING_OFF)
+    assert len(pf2) == len(pf) - 1
+    st, _ = one(base, expect_hit=True, timing=B.TIMING_OFF)
+    # a block is freed and its handle comes back in another host slot
+    lib.set_cross_step_prefetch(False)
+    st, _ = one(base, expect_hit=False, timing=B.TIMING_OFF)
+    assert st.bytes_in == len(pf2) * bb * L
+    st, _ = one(base, expect_hit=False, timing=B.TIMING_OFF)
+    lib.set_cross_step_prefetch(True)
+    st, _ = one(base, expect_hit=False, timing=B.TIMING_OFF)
+    st, _ = one(base, expect_hit=True, timing=B.TIMING_OFF)
+    lib.swap_in(0, pf2[:-1], streams[1])                              # someone else uses region 0 in between
+    mod.swap_in(0, pf2[:-1].tolist())
+    st, _ = one(base, expect_hit=False, timing=B.TIMING_OFF)
+    assert lib.check_errors() == 0
     lib.close()
