@@ -8,7 +8,8 @@ back).  The headline number is decode tokens/s on the Llama-2-7B-shaped fp16
 workload with all KV resident (inputs already in HBM).  The same line carries
 the roofline of the attention kernel, the float64 oracle timed on the host's
 cores on a sample, and the swap leg: 30 % of every sequence's blocks in pinned
-host memory, reporting host-link GB/s, kernel-latency inflation and stall.
+host memory, reporting host-link GB/s, kernel-latency inflation and stall; and
+a second, short leg with 0.5 % on the host, below the fraction the link can hide.
 
 Prints ONE JSON line.
 """
@@ -40,6 +41,8 @@ def parse():
     ap.add_argument("--partition", type=int, default=0, help="attention partition size in tokens (0 = library default)")
     ap.add_argument("--swap-fraction", type=float, default=0.30)
     ap.add_argument("--swap-steps", type=int, default=3)
+    ap.add_argument("--below-knee-fraction", type=float, default=0.005,
+                    help="host-resident fraction of the second, short swap leg (below link rate / attention rate)")
     ap.add_argument("--swap-path", type=int, default=0)
     ap.add_argument("--swap-wgs", type=int, default=0, help="workgroups of the gather / scatter kernel (0 = library default)")
     ap.add_argument("--no-swap", action="store_true")
@@ -483,6 +486,11 @@ def main():
         result["swap"].update({"migrate_s": round(t_mig, 2), "swap_path": args.swap_path,
                                "host_link_measured_peak_GBps": measured_link_peak()})
         dw.pool.migrate(hs, B.GPU, streams[1])
+        dw.pool.sync()
+        # the same path below the link's knee: what the swaps cost when every transfer hides behind a layer
+        result["swap_below_knee"] = fixed_fraction_leg(w, dw, streams, args.below_knee_fraction, 10, base_kernel_ms,
+                                                       base_step_ms, achieved)
+        dw.pool.set_host_fraction(0.0, dw.order, streams[1])
         dw.pool.sync()
 
     # ---- optional: fixed-fraction sweep and the adaptive controller ---------------------------------------
