@@ -18,7 +18,14 @@ Pinned by (see tests/test_oracle_*.py):
   controller_sim.AdaptiveExpansion  - the closed-form fixed point of the
       transparency condition, the worked example's m = 4, start-at-zero,
       shrink-after-slowdown, spike tolerance, plateau.
-  fifo_sim.simulate                 - the worked example's four-layer trace,
-      queue length and residence time.
+  layer_fifo.simulate               - the worked example's four-layer trace,
+      queue length and residence time, the tight swap constraint, the largest
+      number of CPU layers its timing hides.
+  layout.element_index              - bijection, vector contents, hand-worked
+      positions.
+  serving_sim.simulate              - a hand-worked three-request stream
+      (tests/test_serving_host.py); the scheduling rules themselves are this
+      build's reading of an engine the paper inherits: parity unpinned beyond
+      that example.
 Absolute throughput numbers: parity unpinned (the paper prints none for this path).
 """

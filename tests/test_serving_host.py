@@ -9,6 +9,7 @@ given up.
 import numpy as np
 import pytest
 
+from oracle import serving_sim
 from oracle.pool_model import GPU, HOST, PoolModel
 from paper_2411_09317_amd import inputs as I
 from paper_2411_09317_amd import serving as S
@@ -195,3 +196,49 @@ def test_argument_checks():
     sc = S.Scheduler(store(8, 2), T, bud, 4, 2)
     with pytest.raises(ValueError):
         sc.submit(S.Request(0, 0.0, 40, 8))                          # 3 blocks over its life, rows hold 2
+
+
+@pytest.mark.parametrize("levels", [lambda it: 0, lambda it: 2, lambda it: 2 if it < 40 else 0,
+                                    lambda it: (it // 25) % 3])
+def test_scheduler_agrees_with_the_counting_model_iteration_by_iteration(levels):
+    """The product scheduler over a block store against a model that only counts: same batch in every
+    iteration, same blocks held and promised, same admission and last iteration for every request - also
+    while the budget level moves up and down."""
+    rng = np.random.Generator(np.random.PCG64(5))
+    n = 150
+    arrival = np.sort(rng.integers(0, 120, size=n)).tolist()
+    prompt = rng.integers(10, 200, size=n).tolist()
+    output = rng.integers(1, 40, size=n).tolist()
+    trace, adm, fin = serving_sim.simulate(arrival, prompt, output, 64, 16, levels, T, max_batch=24)
+    st = store(64, 2 * 16 + 64)
+    bud = S.BlockBudget(64, 16, 2)
+    sc = S.Scheduler(st, T, bud, 24, 16)
+    for i in range(n):
+        sc.submit(S.Request(i, float(arrival[i]), prompt[i], output[i]))
+    now, got = 0, []
+    while not sc.idle:
+        bud.set_level(levels(now))
+        sc.admit(float(now))
+        sc.promote()
+        if not sc.running:
+            now = int(sc.waiting[0].arrival)
+            continue
+        got.append((now, [r.rid for r in sc.running], sc.blocks_in_use, sc.reserved))
+        sc.complete_iteration(float(now))
+        now += 1
+    assert got == trace
+    assert [int(r.admitted) for r in sorted(sc.done, key=lambda r: r.rid)] == adm
+    assert [int(r.finished) for r in sorted(sc.done, key=lambda r: r.rid)] == fin
+
+
+def test_counting_model_on_a_hand_worked_stream():
+    """4 blocks of 16 tokens, no expansion.  A (20 + 12 tokens: 2 blocks over its life) runs iterations 0-11;
+    B (40 + 8: 3 blocks) does not fit beside it and starts at 12; C (10 + 6: 1 block) arrived at 0 too but waits
+    behind B, joins it at 12 (3 + 1 = 4 blocks) and ends at 17; B ends at 19."""
+    trace, adm, fin = serving_sim.simulate([0, 0, 0], [20, 40, 10], [12, 8, 6], 4, 2, lambda it: 0, 16)
+    assert adm == [0, 12, 12] and fin == [11, 19, 17]
+    assert [t[1] for t in trace[:12]] == [[0]] * 12 and trace[12][1] == [1, 2] and trace[18][1] == [1]
+    assert trace[0][2:] == (2, 2) and trace[12][2:] == (4, 4)      # 21 tokens -> 2 blocks; 41 -> 3, 11 -> 1
+    # one unit of 2 host blocks more: all three at once, 6 blocks promised
+    trace, adm, fin = serving_sim.simulate([0, 0, 0], [20, 40, 10], [12, 8, 6], 4, 2, lambda it: 1, 16)
+    assert adm == [0, 0, 0] and fin == [11, 7, 5] and trace[0][1:] == ([0, 1, 2], 6, 6)
