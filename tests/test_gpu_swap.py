@@ -363,3 +363,22 @@ def test_first_layer_staged_behind_the_previous_step(path):
     st, _ = one(base, expect_hit=False, timing=B.TIMING_OFF)
     assert lib.check_errors() == 0
     lib.close()
+
+
+def test_device_clock_with_the_fp32_kernel():
+    """The fp32 kernel has no persistent grid: its workgroups fold their times into the layer's row directly."""
+    w = I.scaled(W, dtype=I.DTYPE_F32, n_q_heads=8, n_kv_heads=8, head_dim=64, n_layers=3)
+    case = host_tails(I.make_case(w))
+    n = int(case.n_blocks.sum())
+    lib, mod, table = GH.make_pools(case, n, n, n, upto_ctx=case.ctx_lens - 1)
+    streams = (torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream())
+    base, _, _ = run_step(lib, case, table, streams, timing=B.TIMING_OFF)
+    for _ in range(2):
+        got, pf, dirty = run_step(lib, case, table, streams, timing=B.TIMING_CLOCK)
+        assert np.array_equal(got, base)
+        lt, st = lib.layer_times(), lib.stats()
+        assert (lt["kernel"] > 0).all() and (lt["kernel"] < 5.0).all() and (lt["attn"] >= lt["kernel"]).all()
+        assert (lt["swap_in"][st.first_layer_prestaged:] > 0).all() and (lt["swap_out"] > 0).all()
+        assert st.step_ms >= lt["attn"].sum() * 0.99 and st.step_ms < 50.0
+    assert lib.check_errors() == 0
+    lib.close()
