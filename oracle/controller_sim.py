@@ -5,7 +5,7 @@ The paper gives the rules in prose and no constants; this is the reading taken:
 
   * The amount of swapping is an integer level k; the host-resident fraction is
     f = k / units (one unit = one layer's worth when units = n_layers, the
-    paper's "one layer at a time").  The run starts at k = 0.
+    paper moves a single layer per decision).  The run starts at k = 0.
   * After every decode step the controller is shown, per layer, the attention
     time, the swap-in time and the time compute waited for a swap, plus the
     link utilisation and the step's throughput.
