@@ -46,6 +46,7 @@ class Request:
     finished: float = -1.0
     generated: int = 0
     handles: List[int] = field(default_factory=list)
+    row: Optional[np.ndarray] = None      # its block-table row, kept up to date as blocks are added
 
     @property
     def ctx(self) -> int:
@@ -124,6 +125,8 @@ class Scheduler:
             self.reserved += need
             r.admitted = now
             r.handles = self._alloc((r.ctx + self.T - 1) // self.T)
+            r.row = np.full(self.max_blocks, -1, dtype=np.int32)
+            r.row[:len(r.handles)] = r.handles
             self.running.append(r)
             n += 1
         return n
@@ -156,11 +159,10 @@ class Scheduler:
     # ---- one iteration ---------------------------------------------------------------------------
     def tables(self):
         """Block table int32 [batch][max_blocks] (-1 = unused) and context lengths int32 [batch]."""
-        table = np.full((len(self.running), self.max_blocks), -1, dtype=np.int32)
-        ctx = np.zeros(len(self.running), dtype=np.int32)
-        for b, r in enumerate(self.running):
-            table[b, :len(r.handles)] = r.handles
-            ctx[b] = r.ctx
+        if not self.running:
+            return np.zeros((0, self.max_blocks), dtype=np.int32), np.zeros(0, dtype=np.int32)
+        table = np.stack([r.row for r in self.running])
+        ctx = np.fromiter((r.ctx for r in self.running), dtype=np.int32, count=len(self.running))
         return table, ctx
 
     def complete_iteration(self, now: float) -> int:
@@ -175,14 +177,15 @@ class Scheduler:
                 self.store.block_free(r.handles)
                 self.on_host.difference_update(r.handles)
                 self.reserved -= self.lifetime_blocks(r)
-                r.handles = []
+                r.handles, r.row = [], None
                 self.done.append(r)
             else:
                 still.append(r)
         self.running = still
         for r in self.running:                 # after the frees, so that a freed GPU slot is reused at once
             if (r.ctx + self.T - 1) // self.T > len(r.handles):
-                r.handles += self._alloc(1)
+                r.row[len(r.handles)] = (h := self._alloc(1))[0]
+                r.handles += h
         return n
 
     @property
