@@ -58,6 +58,20 @@ struct MapPatch {  // by-value kernel argument
   int32_t slot[kMapPatchPairs];
 };
 
+constexpr int kMaxLayerChunks = 512;  // chunks one layer can hold
+
+struct ChunkList {  // by-value kernel argument
+  int32_t n;
+  int32_t chunk[kMaxLayerChunks];
+};
+
+// Where one layer's blocks are when they are not in the pool's own [layer][slot] layout.
+struct LayerView {
+  char* kv_base;        // base of the memory its slots index
+  const int32_t* map;   // device: handle -> slot, -1 = none
+  int32_t n_handles, n_slots;
+};
+
 struct SwapPairs {  // by-value kernel argument
   int32_t n;
   int32_t src[kSwapPairs];
@@ -170,15 +184,17 @@ constexpr int32_t kAppendGpuHomed = 2;    // GPU-homed; host-homed tails are lef
 constexpr int32_t kAppendStaged = 3;      // staged copies only; GPU-homed tails were written before
 int launch_kv_append(const pie_pool* p, int32_t layer, int32_t n_layers, const void* d_k, const void* d_v,
                      const int32_t* d_table, int32_t max_blocks, const int32_t* d_ctx, int32_t batch,
-                     int32_t mode, hipStream_t s);
+                     int32_t mode, hipStream_t s, const LayerView* view = nullptr);
+int launch_chunk_map_fill(int32_t* d_map, int32_t n_handles, int32_t chunk_blocks, const ChunkList& list, hipStream_t s);
 int launch_attn_plan(const pie_pool* p, const int32_t* d_ctx, int32_t batch, int32_t max_blocks, hipStream_t s,
                      bool reset_clock = false);
 int launch_attn_resolve(const pie_pool* p, const int32_t* d_table, const int32_t* d_ctx, int32_t batch,
-                        int32_t max_blocks, bool region0, bool valid0, bool region1, bool valid1, hipStream_t s);
+                        int32_t max_blocks, bool region0, bool valid0, bool region1, bool valid1, hipStream_t s,
+                        const LayerView* view = nullptr);
 int launch_attn_decode(const pie_pool* p, int32_t layer, const void* d_q, int32_t max_blocks, const int32_t* d_ctx,
                        int32_t batch, void* d_out, hipStream_t s, hipEvent_t k_start = nullptr,
                        hipEvent_t k_end = nullptr, int32_t ticket_index = -1,
-                       unsigned long long* clock_row = nullptr);
+                       unsigned long long* clock_row = nullptr, const LayerView* view = nullptr);
 int launch_stream_probe(const pie_pool* p, int32_t layer, int32_t max_blocks, int32_t batch, hipStream_t s);
 size_t attn_plan_ints(const pie_config& c);
 size_t attn_workspace_floats(const pie_config& c);

@@ -127,6 +127,22 @@ int launch_zero_u32(uint32_t* d, int32_t n, hipStream_t s) {
   return launch_map_fill(reinterpret_cast<int32_t*>(d), n, 0, s);
 }
 
+// A layer whose blocks are spread over chunks of `chunk_blocks` consecutive slots: block h lives in slot
+// chunks[h / chunk_blocks] * chunk_blocks + h % chunk_blocks; blocks beyond the layer's chunks map to -1.
+__global__ void k_chunk_map_fill(int32_t* __restrict__ map, int32_t n_handles, int32_t chunk_blocks, const ChunkList list) {
+  const int32_t h = blockIdx.x * blockDim.x + threadIdx.x;
+  if (h >= n_handles) return;
+  const int32_t c = h / chunk_blocks;
+  map[h] = c < list.n ? list.chunk[c] * chunk_blocks + h % chunk_blocks : -1;
+}
+
+int launch_chunk_map_fill(int32_t* d_map, int32_t n_handles, int32_t chunk_blocks, const ChunkList& list, hipStream_t s) {
+  if (n_handles <= 0) return PIE_OK;
+  hipLaunchKernelGGL(k_chunk_map_fill, dim3((n_handles + 255) / 256), dim3(256), 0, s, d_map, n_handles, chunk_blocks, list);
+  PIE_HIP(hipGetLastError());
+  return PIE_OK;
+}
+
 int launch_map_patch(int32_t* d_map, const MapPatch& patch, hipStream_t s) {
   if (patch.n <= 0) return PIE_OK;
   hipLaunchKernelGGL(k_map_patch, dim3((patch.n + 255) / 256), dim3(256), 0, s, d_map, patch);
@@ -338,9 +354,10 @@ __global__ __launch_bounds__(256) void k_kv_append(const AppendArgs a) {
 // that leave staged copies alone make sense (staging regions hold one layer each).
 int launch_kv_append(const pie_pool* p, int32_t layer, int32_t n_layers, const void* d_k, const void* d_v,
                      const int32_t* d_table, int32_t max_blocks, const int32_t* d_ctx, int32_t batch,
-                     int32_t mode, hipStream_t s) {
+                     int32_t mode, hipStream_t s, const LayerView* view) {
   if (((uintptr_t)d_k | (uintptr_t)d_v) % 16) return PIE_EINVAL;
   if (n_layers < 1 || (n_layers > 1 && (mode == kAppendPresent || mode == kAppendStaged))) return PIE_EINVAL;
+  if (view && n_layers != 1) return PIE_EINVAL;
   AppendArgs a;
   a.kv_layer = p->d_kv + (size_t)layer * p->d_layer_stride;
   a.map = p->d_map[layer & 1];
@@ -361,6 +378,12 @@ int launch_kv_append(const pie_pool* p, int32_t layer, int32_t n_layers, const v
   a.block_tokens = p->cfg.block_tokens;
   a.elem_bytes = p->elem_bytes;
   a.mode = mode;
+  if (view) {                                    // the layer's blocks live elsewhere: all of them "GPU-homed" there
+    a.kv_layer = view->kv_base;
+    a.map = view->map;
+    a.n_handles = view->n_handles;
+    a.n_gpu_blocks = a.n_slots = view->n_slots;
+  }
   hipLaunchKernelGGL(k_kv_append, dim3(batch, n_layers), dim3(256), 0, s, a);
   PIE_HIP(hipGetLastError());
   return PIE_OK;
@@ -1176,7 +1199,8 @@ int launch_attn_plan(const pie_pool* p, const int32_t* d_ctx, int32_t batch, int
 }
 
 int launch_attn_resolve(const pie_pool* p, const int32_t* d_table, const int32_t* d_ctx, int32_t batch,
-                        int32_t max_blocks, bool region0, bool valid0, bool region1, bool valid1, hipStream_t s) {
+                        int32_t max_blocks, bool region0, bool valid0, bool region1, bool valid1, hipStream_t s,
+                        const LayerView* view) {
   (void)d_ctx;
   if (batch > p->cfg.max_batch || max_blocks > p->cfg.max_blocks_per_seq || max_blocks <= 0) return PIE_EINVAL;
   const int32_t part = part_tokens_of(p);
@@ -1196,6 +1220,12 @@ int launch_attn_resolve(const pie_pool* p, const int32_t* d_table, const int32_t
   a.blocks_per_item = part / kBlockTokens;
   a.stage_valid[0] = valid0 ? 1 : 0;
   a.stage_valid[1] = valid1 ? 1 : 0;
+  if (view) {                                    // one layer's own handle -> slot map, into the slot list of region 0
+    if (!region0 || region1) return PIE_EINVAL;
+    a.map[0] = view->map;
+    a.n_handles = view->n_handles;
+    a.n_gpu_blocks = a.n_slots = view->n_slots;
+  }
   // one workgroup per possible item; those past the planned count return at once
   const int32_t max_items = batch * ((max_blocks * kBlockTokens + part - 1) / part);
   hipLaunchKernelGGL(k_attn_resolve, dim3(max_items), dim3(64), 0, s, a);
@@ -1251,7 +1281,7 @@ static int launch_f32(const AttnArgs& a, int32_t batch, int32_t n_q_heads, int32
 // same batch, table width and context lengths.
 int launch_attn_decode(const pie_pool* p, int32_t layer, const void* d_q, int32_t max_blocks, const int32_t* d_ctx,
                        int32_t batch, void* d_out, hipStream_t s, hipEvent_t k_start, hipEvent_t k_end,
-                       int32_t ticket_index, unsigned long long* clock_row) {
+                       int32_t ticket_index, unsigned long long* clock_row, const LayerView* view) {
   const pie_config& c = p->cfg;
   if (((uintptr_t)d_q | (uintptr_t)d_out) % 16) return PIE_EINVAL;
   if (max_blocks <= 0) return PIE_EINVAL;
@@ -1263,8 +1293,8 @@ int launch_attn_decode(const pie_pool* p, int32_t layer, const void* d_q, int32_
   if ((size_t)batch * c.n_q_heads * n_parts * (c.head_dim + 2) > p->ws_floats) return PIE_ENOMEM;
 
   AttnArgs a;
-  a.kv_layer = p->d_kv + (size_t)layer * p->d_layer_stride;
-  a.slots = plan_slots(p, layer & 1);
+  a.kv_layer = view ? view->kv_base : p->d_kv + (size_t)layer * p->d_layer_stride;
+  a.slots = plan_slots(p, view ? 0 : (layer & 1));
   a.items = plan_items(p);
   a.hdr = plan_hdr(p);
   // one ticket counter per launch since the last planning kernel (by default the layer's)
