@@ -429,6 +429,71 @@ int pie_layer_pool_address(pie_layer_pool* lp, int32_t layer, int32_t* out_where
 int pie_layer_pool_table(pie_layer_pool* lp, pie_layer_entry* out);
 int pie_layer_pool_stats(pie_layer_pool* lp, pie_layer_stats* out);
 
+/* ---- layer caches that grow and shrink (Section 3.1: a / (n - m) per layer; Section 4.1: block manager) ----
+ *
+ * With m of n layers' caches kept in CPU memory, the GPU memory they leave goes to the layers that stay.  The
+ * paper reallocates a layer's cache as one piece when it is swapped back in; here the GPU memory is N chunks
+ * of chunk_blocks block slots, and a layer's cache is any list of chunks: block h of the layer lives in slot
+ * chunk[h / chunk_blocks] * chunk_blocks + h % chunk_blocks of that memory.  A resident layer is given more
+ * chunks where it is; a layer travels as one copy-engine transfer per chunk.
+ *
+ * pie_chunk_book is the bookkeeping as pure host logic.  Every layer starts resident with N / n chunks (layer
+ * j: chunks j N/n ...).  The target per layer is min(max_chunks_per_layer, N / (n - m)).  Free chunks go to
+ * resident layers below the target, lowest layer first, except what the GPU layer slots still to be filled
+ * will need; a layer entering the GPU takes the lowest free chunks, up to the target.  What is visible to a
+ * scheduler (chunks per layer usable in every layer) is the smallest list among the resident layers: growth
+ * shows when the reallocation is complete; a shrink lowers it at once. */
+typedef struct pie_chunk_book pie_chunk_book;
+int pie_chunk_book_create(int32_t n_layers, int32_t n_chunks, int32_t max_chunks_per_layer, pie_chunk_book** out);
+int pie_chunk_book_destroy(pie_chunk_book* book);
+/* Asks for m layers in CPU memory.  chunks_in_use: chunks of a layer's cache that still hold live blocks.
+ * PIE_ESTATE: the caches would have to shrink below that; what is visible has been lowered all the same
+ * (hidden first), nothing else has changed; ask again when the blocks above have been given up. */
+int pie_chunk_book_set_layers_on_cpu(pie_chunk_book* book, int32_t m, int32_t chunks_in_use);
+/* The layer's swap-out has completed: its chunks are free (and may go to resident layers at once). */
+int pie_chunk_book_left_gpu(pie_chunk_book* book, int32_t layer);
+/* The layer's swap-in starts: it takes chunks; *out_n_data = how many of them its data fills.  PIE_ENOMEM if
+ * fewer chunks are free than it carries or than are visible. */
+int pie_chunk_book_enters_gpu(pie_chunk_book* book, int32_t layer, int32_t* out_n_data);
+/* out_chunks needs room for max_chunks_per_layer entries; any out pointer may be NULL. */
+int pie_chunk_book_layer(pie_chunk_book* book, int32_t layer, int32_t* out_resident, int32_t* out_n_data,
+                         int32_t* out_n_chunks, int32_t* out_chunks);
+int pie_chunk_book_capacity(pie_chunk_book* book, int32_t* out_visible, int32_t* out_target, int32_t* out_free,
+                            int32_t* out_layers_on_cpu);
+
+/* pie_elastic_pool runs the layer-granular protocol (pie_layer_sched) over such caches on the GPU.  `pool`: a
+ * device pool with n_stage_blocks = n_host_blocks = 0 whose n_layers are the logical layers and whose
+ * n_gpu_blocks (a multiple of chunk_blocks) is a layer's cache while everything is on the GPU; its memory is
+ * the N = n_layers * n_gpu_blocks / chunk_blocks chunks.  Block tables hold block indices of a layer's cache
+ * (the same in every layer), below the visible capacity.  d_work (device, pie_elastic_bytes_required) holds
+ * the layers' block maps; h_pinned holds n_host_slots layer images of max_chunks_per_layer chunks.  The pool
+ * must outlive the elastic pool; its own block allocator and swaps are not used.  All ordering between
+ * streams is done on the host, as in pie_layer_step. */
+typedef struct pie_elastic_pool pie_elastic_pool;
+int pie_elastic_bytes_required(pie_pool* pool, int32_t chunk_blocks, int32_t max_chunks_per_layer,
+                               int32_t n_host_slots, size_t* d_bytes, size_t* h_bytes);
+int pie_elastic_create(pie_pool* pool, int32_t chunk_blocks, int32_t max_chunks_per_layer, int32_t n_host_slots,
+                       void* d_work, size_t d_bytes, void* h_pinned, size_t h_bytes, pie_elastic_pool** out);
+int pie_elastic_destroy(pie_elastic_pool* ep);
+/* Between steps: asks for m layers in CPU memory (needs m + 2 host slots).  blocks_in_use_end: highest live
+ * block index + 1.  Completes the moves in flight first.  PIE_ESTATE as pie_chunk_book_set_layers_on_cpu.  The
+ * layers then leave (or return) through the protocol during the following steps. */
+int pie_elastic_set_layers_on_cpu(pie_elastic_pool* ep, int32_t m, int32_t blocks_in_use_end, void* compute_stream);
+/* Blocks per layer a scheduler may use now, what they will be when the reallocation is complete, and m. */
+int pie_elastic_capacity(pie_elastic_pool* ep, int32_t* out_visible_blocks, int32_t* out_target_blocks,
+                         int32_t* out_layers_on_cpu);
+/* One decode step over the logical layers, in order; arguments as pie_layer_step. */
+int pie_elastic_step(pie_elastic_pool* ep, const void* d_q_all, const void* d_k_new, const void* d_v_new,
+                     const int32_t* d_block_table, int32_t max_blocks, const int32_t* d_ctx_lens, int32_t batch,
+                     void* d_out_all, void* compute_stream, void* swap_in_stream, void* swap_out_stream);
+int pie_elastic_settle_sync(pie_elastic_pool* ep, void* compute_stream);
+/* Where a layer is: PIE_WHERE_GPU with its chunk list (out_chunks: room for max_chunks_per_layer), or
+ * PIE_WHERE_HOST with the address of its image (*out_n_chunks chunks of data).  PIE_ESTATE while in flight. */
+int pie_elastic_layer(pie_elastic_pool* ep, int32_t layer, int32_t* out_where, int32_t* out_n_chunks,
+                      int32_t* out_chunks, void** out_host_ptr);
+int pie_elastic_table(pie_elastic_pool* ep, pie_layer_entry* out);
+int pie_elastic_stats(pie_elastic_pool* ep, pie_layer_stats* out);
+
 /* ---- diagnostics -------------------------------------------------------------- */
 int pie_last_hip_error(void);            /* hipError_t of the last PIE_EHIP on this thread, 0 if none */
 const char* pie_strerror(int code);      /* static string for a PIE_* code */

@@ -38,6 +38,11 @@ SYMBOLS = [
     "pie_layer_sched_policy", "pie_layer_sched_table", "pie_layer_sched_set_gpu_slots", "pie_layer_pool_set_gpu_slots", "pie_layer_pool_bytes_required", "pie_layer_pool_create",
     "pie_layer_pool_destroy", "pie_layer_step", "pie_layer_pool_settle_sync", "pie_layer_pool_address",
     "pie_layer_pool_table", "pie_layer_pool_stats",
+    "pie_chunk_book_create", "pie_chunk_book_destroy", "pie_chunk_book_set_layers_on_cpu", "pie_chunk_book_left_gpu",
+    "pie_chunk_book_enters_gpu", "pie_chunk_book_layer", "pie_chunk_book_capacity",
+    "pie_elastic_bytes_required", "pie_elastic_create", "pie_elastic_destroy", "pie_elastic_set_layers_on_cpu",
+    "pie_elastic_capacity", "pie_elastic_step", "pie_elastic_settle_sync", "pie_elastic_layer", "pie_elastic_table",
+    "pie_elastic_stats",
 ]
 
 
@@ -465,6 +470,138 @@ class LayerPool:
     def close(self):
         if self._h:
             _lib.pie_layer_pool_destroy(self._h)
+            self._h = C.c_void_p(0)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class ChunkBook:
+    """Which chunks of GPU memory each layer's cache holds (pure host logic inside the library)."""
+
+    def __init__(self, n_layers: int, n_chunks: int, max_chunks_per_layer: int):
+        self._h = C.c_void_p(0)
+        self.n_layers, self.k_cap = n_layers, max_chunks_per_layer
+        _check(_lib.pie_chunk_book_create(C.c_int32(n_layers), C.c_int32(n_chunks), C.c_int32(max_chunks_per_layer),
+                                          C.byref(self._h)), "chunk_book_create")
+
+    def set_layers_on_cpu(self, m: int, chunks_in_use: int) -> bool:
+        rc = _lib.pie_chunk_book_set_layers_on_cpu(self._h, C.c_int32(m), C.c_int32(chunks_in_use))
+        if rc == ESTATE:
+            return False
+        _check(rc, "chunk_book_set_layers_on_cpu")
+        return True
+
+    def left_gpu(self, layer: int):
+        _check(_lib.pie_chunk_book_left_gpu(self._h, C.c_int32(layer)), "chunk_book_left_gpu")
+
+    def enters_gpu(self, layer: int) -> Tuple[List[int], int]:
+        n_data = C.c_int32(0)
+        _check(_lib.pie_chunk_book_enters_gpu(self._h, C.c_int32(layer), C.byref(n_data)), "chunk_book_enters_gpu")
+        return self.layer(layer)[2], n_data.value
+
+    def layer(self, layer: int) -> Tuple[bool, int, List[int]]:
+        """(resident, chunks of data it carries, chunk ids it holds)."""
+        res, nd, nc = C.c_int32(0), C.c_int32(0), C.c_int32(0)
+        ch = np.zeros(self.k_cap, dtype=np.int32)
+        _check(_lib.pie_chunk_book_layer(self._h, C.c_int32(layer), C.byref(res), C.byref(nd), C.byref(nc), _ptr(ch)),
+               "chunk_book_layer")
+        return bool(res.value), nd.value, ch[:nc.value].tolist()
+
+    def capacity(self) -> Tuple[int, int, int, int]:
+        """(visible, target, free chunks, layers asked to be in CPU memory)."""
+        v, t, f, m = C.c_int32(0), C.c_int32(0), C.c_int32(0), C.c_int32(0)
+        _check(_lib.pie_chunk_book_capacity(self._h, C.byref(v), C.byref(t), C.byref(f), C.byref(m)), "chunk_book_capacity")
+        return v.value, t.value, f.value, m.value
+
+    def close(self):
+        if self._h:
+            _lib.pie_chunk_book_destroy(self._h)
+            self._h = C.c_void_p(0)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+class ElasticPool:
+    """The layer-granular protocol over layer caches made of chunks of a Pool's GPU memory."""
+
+    def __init__(self, pool: Pool, chunk_blocks: int, max_chunks_per_layer: int, n_host_slots: int):
+        import torch
+        self.pool, self.C, self.k_cap = pool, chunk_blocks, max_chunks_per_layer
+        self.n_layers = pool.cfg.n_layers
+        self.chunk_bytes = chunk_blocks * pool.block_bytes
+        self._h = C.c_void_p(0)
+        db, hb = C.c_size_t(0), C.c_size_t(0)
+        _check(_lib.pie_elastic_bytes_required(pool._h, C.c_int32(chunk_blocks), C.c_int32(max_chunks_per_layer),
+                                               C.c_int32(n_host_slots), C.byref(db), C.byref(hb)), "elastic_bytes")
+        self.d_work = torch.empty(max(db.value, 16), dtype=torch.uint8, device=pool.d_buf.device)
+        self.h_buf = torch.empty(max(hb.value, 1), dtype=torch.uint8, pin_memory=True)
+        _check(_lib.pie_elastic_create(pool._h, C.c_int32(chunk_blocks), C.c_int32(max_chunks_per_layer),
+                                       C.c_int32(n_host_slots), C.c_void_p(self.d_work.data_ptr()), C.c_size_t(db.value),
+                                       C.c_void_p(self.h_buf.data_ptr()), C.c_size_t(hb.value), C.byref(self._h)),
+               "elastic_create")
+
+    def set_layers_on_cpu(self, m: int, blocks_in_use_end: int, compute_stream=None) -> bool:
+        rc = _lib.pie_elastic_set_layers_on_cpu(self._h, C.c_int32(m), C.c_int32(blocks_in_use_end),
+                                                _stream_ptr(compute_stream))
+        if rc == ESTATE:
+            return False
+        _check(rc, "elastic_set_layers_on_cpu")
+        return True
+
+    def capacity(self) -> Tuple[int, int, int]:
+        """(visible blocks per layer, target blocks per layer, layers asked to be in CPU memory)."""
+        v, t, m = C.c_int32(0), C.c_int32(0), C.c_int32(0)
+        _check(_lib.pie_elastic_capacity(self._h, C.byref(v), C.byref(t), C.byref(m)), "elastic_capacity")
+        return v.value, t.value, m.value
+
+    def step(self, q_all, k_new, v_new, block_table, ctx_lens, out_all, compute_stream=None, swap_in_stream=None,
+             swap_out_stream=None):
+        _check(_lib.pie_elastic_step(self._h, _dptr(q_all), _dptr(k_new), _dptr(v_new), _dptr(block_table),
+                                     C.c_int32(block_table.shape[1]), _dptr(ctx_lens), C.c_int32(ctx_lens.shape[0]),
+                                     _dptr(out_all), _stream_ptr(compute_stream), _stream_ptr(swap_in_stream),
+                                     _stream_ptr(swap_out_stream)), "elastic_step")
+
+    def settle(self, compute_stream=None):
+        _check(_lib.pie_elastic_settle_sync(self._h, _stream_ptr(compute_stream)), "elastic_settle")
+
+    def table(self) -> List[Tuple[int, int, int]]:
+        arr = (LayerEntry * self.n_layers)()
+        _check(_lib.pie_elastic_table(self._h, arr), "elastic_table")
+        return [(e.state, e.gpu_slot, e.host_slot) for e in arr]
+
+    def layer_chunks(self, layer: int):
+        """The layer's cache as a list of uint8 torch tensors [chunk_blocks][block_bytes], one per chunk, aliasing
+        the memory where it is now (GPU chunks, or the chunks of data in its host image)."""
+        where, n, hp = C.c_int32(0), C.c_int32(0), C.c_void_p(0)
+        ch = np.zeros(self.k_cap, dtype=np.int32)
+        _check(_lib.pie_elastic_layer(self._h, C.c_int32(layer), C.byref(where), C.byref(n), _ptr(ch), C.byref(hp)),
+               "elastic_layer")
+        out = []
+        for i in range(n.value):
+            if where.value == GPU:
+                off = self.pool._d_off + int(ch[i]) * self.chunk_bytes
+                out.append(self.pool.d_buf[off: off + self.chunk_bytes].view(self.C, self.pool.block_bytes))
+            else:
+                off = hp.value - self.h_buf.data_ptr() + i * self.chunk_bytes
+                out.append(self.h_buf[off: off + self.chunk_bytes].view(self.C, self.pool.block_bytes))
+        return where.value, out
+
+    def stats(self) -> LayerStats:
+        s = LayerStats()
+        _check(_lib.pie_elastic_stats(self._h, C.byref(s)), "elastic_stats")
+        return s
+
+    def close(self):
+        if self._h:
+            _lib.pie_elastic_destroy(self._h)
             self._h = C.c_void_p(0)
 
     def __del__(self):

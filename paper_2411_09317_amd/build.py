@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpie.so")
-SOURCES = ["pie_pool.cpp", "pie_controller.cpp", "pie_layer_sched.cpp", "pie_kernels.hip"]
+SOURCES = ["pie_pool.cpp", "pie_controller.cpp", "pie_layer_sched.cpp", "pie_elastic.cpp", "pie_kernels.hip"]
 
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-ffp-contract=off",

@@ -1,0 +1,150 @@
+"""Layer caches that grow and shrink with the number of layers kept in CPU memory (pie_elastic_pool).
+
+Nine layers whose caches are seven chunks each while everything is on the GPU.  Two layers are asked to stay
+in CPU memory: the protocol moves layers out and in token after token, their chunks go to the layers that stay,
+and once that is complete nine chunks per layer are visible - the worked example's 9/7.  A sequence that joins
+then lives in blocks that did not exist before.  A shrink is refused while those blocks are in use (but hides
+them at once), succeeds when they are given up, and finally every layer returns to the GPU.  At every token the
+outputs are, bit for bit, those of a plain pool that holds all layers at the larger size, and at the end every
+layer's bytes are the reference's.
+"""
+import numpy as np
+import pytest
+import torch
+
+import gpu_helpers as GH
+import helpers as H
+from oracle import attention as A
+from oracle import layout as LY
+from paper_2411_09317_amd import binding as B
+from paper_2411_09317_amd import inputs as I
+
+pytestmark = pytest.mark.gpu
+
+N_LAYERS, C, K0, K_CAP, HOST_SLOTS = 9, 4, 7, 12, 4
+
+
+@pytest.mark.parametrize("dtype", [I.DTYPE_F16, I.DTYPE_BF16])
+def test_capacity_follows_the_layers_on_the_cpu_and_results_never_change(dtype):
+    n = N_LAYERS
+    w = I.Workload("elastic", n, 3, 8, 2, 128, dtype, ctx_lo=40, ctx_hi=130, value_scale=0.7, seed=61)
+    case = I.make_case(w)
+    nb = int(case.n_blocks.sum())
+    assert nb <= K0 * C - 1                                       # the three sequences fit the small caches
+    batch, max_blocks = 4, 10
+    mk = lambda blocks: B.Pool(n, w.n_q_heads, w.n_kv_heads, w.head_dim, 16, dtype, blocks, 0, 0, max_batch=batch,
+                               max_blocks_per_seq=max_blocks, device=GH.DEV)
+    ref, inner = mk(K_CAP * C), mk(K0 * C)
+    assert ref.block_alloc(B.GPU, K_CAP * C) == list(range(K_CAP * C))          # handle = slot = block index
+    table = np.full((batch, max_blocks), -1, dtype=np.int32)
+    i = 0
+    for b in range(3):
+        for j in range(int(case.n_blocks[b])):
+            table[b, j] = i
+            i += 1
+    late = [K0 * C + 1, K0 * C + 2]                               # blocks that exist only in the larger caches
+    table[3, :2] = late
+    sd = I.storage_numpy_dtype(dtype)
+    img = np.zeros((n, K0 * C, 2, w.n_kv_heads, 16, w.head_dim), dtype=sd)
+    for b in range(3):
+        n_tok = int(case.ctx_lens[b]) - 1
+        for j in range(int(case.n_blocks[b])):
+            lo, hi = j * 16, min((j + 1) * 16, n_tok)
+            if hi > lo:
+                img[:, table[b, j], 0, :, : hi - lo] = case.k_dense[b][:, lo:hi].transpose(0, 2, 1, 3)
+                img[:, table[b, j], 1, :, : hi - lo] = case.v_dense[b][:, lo:hi].transpose(0, 2, 1, 3)
+    phys = torch.from_numpy(LY.to_physical(img).view(np.uint8).copy()).to(GH.DEV)   # [L][K0 C][block_bytes]
+    ref.gpu_image().zero_()
+    ref.gpu_image()[:, : K0 * C].copy_(phys)
+    inner.gpu_image().copy_(phys)
+    ep = B.ElasticPool(inner, C, K_CAP, HOST_SLOTS)
+    cs, si, so = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    q_np = np.concatenate([case.q, I.to_storage(I.draw_values(w, (n, 1, w.n_q_heads, w.head_dim), 77), dtype)], axis=1)
+    q = GH.to_dev(q_np, dtype)
+    d_table = torch.from_numpy(table).to(GH.DEV)
+    ctx = np.concatenate([case.ctx_lens, [0]]).astype(np.int32)
+    none = np.zeros(0, dtype=np.int32)
+    token = [0]
+
+    def step():
+        t = token[0]
+        if t == 0:
+            k3, v3 = [np.stack([np.stack([d[b][l, case.ctx_lens[b] - 1] for b in range(3)]) for l in range(n)])
+                      for d in (case.k_dense, case.v_dense)]
+            extra = I.to_storage(I.draw_values(w, (2, n, 1, w.n_kv_heads, w.head_dim), 78), dtype)
+            k_new, v_new = np.concatenate([k3, extra[0]], axis=1), np.concatenate([v3, extra[1]], axis=1)
+        else:
+            k_new = I.to_storage(I.draw_values(w, (n, batch, w.n_kv_heads, w.head_dim), 100 + t), dtype)
+            v_new = I.to_storage(I.draw_values(w, (n, batch, w.n_kv_heads, w.head_dim), 200 + t), dtype)
+        dk, dv = GH.to_dev(k_new, dtype), GH.to_dev(v_new, dtype)
+        d_ctx = torch.from_numpy(ctx).to(GH.DEV)
+        out_ref, out = torch.empty_like(q), torch.full_like(q, float("nan"))
+        ref.step(q, dk, dv, d_table, d_ctx, none, none, out_ref, cs, si, so)
+        ref.sync()
+        ep.step(q, dk, dv, d_table, d_ctx, out, cs, si, so)
+        inner.sync()
+        assert inner.check_errors() == 0 and ref.check_errors() == 0
+        assert torch.equal(out.view(torch.int16), out_ref.view(torch.int16)), t
+        if t == 0:                                                # and the reference is the oracle's answer
+            from test_gpu_attention import check
+            for l in (0, 4, 8):
+                check(GH.from_dev(out[l, :3], dtype), A.dense_attention(*H.dense_f64(case, l), case.ctx_lens), dtype)
+        token[0] += 1
+        return out
+
+    def grow_context():
+        for b in range(3):
+            if (ctx[b] + 1 + 15) // 16 <= case.n_blocks[b]:
+                ctx[b] += 1
+
+    try:
+        assert ep.capacity() == (K0 * C, K0 * C, 0)
+        step()
+        grow_context()
+        # ---- two layers to the CPU: each cache grows to 63 // 7 = 9 chunks once they have left ----
+        assert ep.set_layers_on_cpu(2, nb, cs)
+        assert ep.capacity() == (K0 * C, 9 * C, 2)
+        seen = []
+        for _ in range(6):
+            step()
+            grow_context()
+            seen.append(ep.capacity()[0])
+            if seen[-1] == 9 * C:
+                break
+        assert seen[-1] == 9 * C and all(a <= b for a, b in zip(seen, seen[1:])), seen
+        st = ep.stats()
+        assert st.n_swap_out >= 2 and st.n_swap_in >= 0
+        # ---- a sequence joins in blocks beyond the old caches ----
+        for t in range(20):
+            ctx[3] = t + 1                                        # grows from its first token, crosses into its 2nd block
+            step()
+            grow_context()
+        assert ctx[3] == 20 and ep.stats().n_swap_in > 0
+        # ---- back to one layer on the CPU: 63 // 8 = 7 chunks; refused while the late sequence lives ----
+        assert ep.set_layers_on_cpu(1, late[-1] + 1, cs) is False
+        assert ep.capacity() == (K0 * C, 9 * C, 2)                # hidden at once, nothing else changed
+        step()
+        ctx[3] = 0                                                # the sequence ends; its blocks are given up
+        assert ep.set_layers_on_cpu(1, nb, cs)
+        assert ep.capacity() == (K0 * C, K0 * C, 1)
+        for _ in range(3):
+            step()
+            grow_context()
+        assert ep.set_layers_on_cpu(0, nb, cs)
+        for _ in range(4):
+            step()
+            grow_context()
+        ep.settle(cs)
+        inner.sync()
+        tbl = ep.table()
+        assert all(s == B.LAYER_GPU for s, _, _ in tbl)           # every layer is back
+        # every layer's first blocks, wherever its chunks are, hold the reference's bytes
+        for l in range(n):
+            where, chunks = ep.layer_chunks(l)
+            assert where == B.GPU and len(chunks) == K0
+            got = torch.cat([c.cpu() for c in chunks])[:nb]
+            assert torch.equal(got, ref.gpu_image()[l, :nb].cpu()), l
+    finally:
+        ep.close()
+        inner.close()
+        ref.close()
