@@ -57,6 +57,9 @@ def parse():
     ap.add_argument("--layer-fifo", type=int, default=0,
                     help="also run the paper's layer-granular protocol with this many layers starting in CPU memory "
                          "(GPU layer slots = layers - m, CPU slots = m + 2); adds 'layer_fifo'")
+    ap.add_argument("--elastic", type=int, default=0,
+                    help="also run the chunked layer caches with this many layers asked to stay in CPU memory: the "
+                         "caches of the others grow to a / (n - m); adds 'elastic'")
     ap.add_argument("--t-other-us", type=float, default=0.0,
                     help="experiments only: keep the compute stream busy this long after each layer's attention, standing "
                          "for the rest of a transformer layer (default 0 = the measured path; -1 = the time to read the "
@@ -317,6 +320,61 @@ def cpu_baseline(dw, n_seqs, n_layers):
             "gpu_vs_oracle_rowwise_rel_err": rel}
 
 
+def elastic_leg(w, dw, m, n_steps, t_other_us, base_step_ms, chunk_blocks=256):
+    """Layer caches made of chunks: m layers are asked to stay in CPU memory, the chunks they leave go to the
+    layers that stay (a / (n - m) per layer), and the steps are timed once that is complete."""
+    import torch
+    from paper_2411_09317_amd import binding as B
+    n = w.n_layers
+    k0 = (dw.total_blocks + chunk_blocks - 1) // chunk_blocks
+    k_cap = (n * k0) // (n - m)
+    inner = B.Pool(n, w.n_q_heads, w.n_kv_heads, w.head_dim, w.block_tokens, w.dtype, k0 * chunk_blocks, 0, 0,
+                   max_batch=w.batch, max_blocks_per_seq=dw.table.shape[1])
+    table = np.full_like(dw.table, -1)
+    table[dw.table >= 0] = np.arange(dw.total_blocks, dtype=np.int32)      # block indices of a layer's cache
+    inner.gpu_image()[:, : dw.total_blocks].view(torch.int16).copy_(
+        dw.pool.gpu_image()[:, : dw.total_blocks].view(torch.int16))
+    ep = B.ElasticPool(inner, chunk_blocks, k_cap, m + 2)
+    if t_other_us:
+        inner.set_layer_compute_us(t_other_us)
+    d_table = torch.from_numpy(table).to(dw.q.device)
+    streams = (torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream())
+    out = torch.empty_like(dw.q)
+    def run(k):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(k):
+            ep.step(dw.q, dw.k_new, dw.v_new, d_table, dw.d_ctx, out, *streams)
+        inner.sync()
+        return time.perf_counter() - t0
+    run(1)
+    resident_ms = run(n_steps) / n_steps * 1e3                       # everything on the GPU, through the block maps
+    ep.set_layers_on_cpu(m, dw.total_blocks, streams[0])
+    steps_to_visible = 0
+    while ep.capacity()[0] < ep.capacity()[1] and steps_to_visible < 4 * n:
+        run(1)
+        steps_to_visible += 1
+    s0 = ep.stats()
+    dt = run(n_steps)
+    s1 = ep.stats()
+    assert inner.check_errors() == 0
+    vis, tgt, _ = ep.capacity()
+    res = {"layers_on_cpu": m, "chunk_blocks": chunk_blocks, "chunk_MB": chunk_blocks * w.block_bytes / 1e6,
+           "chunks_per_layer_before": k0, "chunks_per_layer_after": vis // chunk_blocks,
+           "blocks_per_layer_before": k0 * chunk_blocks, "blocks_per_layer_visible": vis, "blocks_per_layer_target": tgt,
+           "expansion": vis / (k0 * chunk_blocks), "steps_until_visible": steps_to_visible,
+           "ms_per_step_all_resident": resident_ms, "ms_per_step": dt / n_steps * 1e3,
+           "tokens_per_s": w.batch * n_steps / dt, "inflation_e2e": dt / n_steps * 1e3 / base_step_ms - 1.0,
+           "swap_ins_per_step": (s1.n_swap_in - s0.n_swap_in) / n_steps,
+           "swap_outs_per_step": (s1.n_swap_out - s0.n_swap_out) / n_steps,
+           "forced_ins_per_step": (s1.n_forced_in - s0.n_forced_in) / n_steps,
+           "host_wait_ms_per_step": (s1.stall_ms - s0.stall_ms) / n_steps,
+           "link_GBps_in": (s1.bytes_in - s0.bytes_in) / dt / 1e9, "link_GBps_out": (s1.bytes_out - s0.bytes_out) / dt / 1e9}
+    ep.close()
+    inner.close()
+    return res
+
+
 def serving_mode(args):
     """Expansion turned into batch size: a request stream served at fixed budget levels and by the controller,
     first saturated (every request waiting from the start: throughput), then at a share of the level-0
@@ -499,6 +557,8 @@ def main():
                                               achieved) for f in args.sweep.split(",")]
     if args.layer_fifo:
         result["layer_fifo"] = layer_fifo_leg(w, dw, args.layer_fifo, args.swap_steps, args.t_other_us, base_step_ms)
+    if args.elastic:
+        result["elastic"] = elastic_leg(w, dw, args.elastic, args.swap_steps, args.t_other_us, base_step_ms)
     if args.adaptive_steps:
         units = args.adaptive_units or 8 * w.n_layers
         k_max = int(host_cap * units)
