@@ -148,3 +148,98 @@ def test_capacity_follows_the_layers_on_the_cpu_and_results_never_change(dtype):
         ep.close()
         inner.close()
         ref.close()
+
+
+def test_adaptive_expansion_grows_the_caches_on_hardware():
+    """Section 3.4.2 with Section 3.1's payoff: every layer starts on the GPU; a controller that only sees
+    whether computation waited asks for one more layer in CPU memory at a time, and one fewer when it did.  The
+    caches of the layers that stay grow with every level (and a leaving layer carries more), outputs stay
+    bit-identical, and the run settles where nothing waits with more blocks per layer than it began with."""
+    import time
+    n, host, C = 9, 6, 64
+    w = I.Workload("elastic2", n, 8, 8, 8, 128, I.DTYPE_F16, ctx_lo=1500, ctx_hi=2048, value_scale=0.5, seed=63)
+    ctx = I.draw_ctx_lens(w)
+    n_blocks = I.blocks_needed(ctx, 16)
+    nb, max_blocks = int(n_blocks.sum()), int(n_blocks.max())
+    k0 = (nb + C - 1) // C
+    k_cap = (n * k0) // (n - (host - 2))
+    mk = lambda: B.Pool(n, w.n_q_heads, w.n_kv_heads, w.head_dim, 16, w.dtype, k0 * C, 0, 0, max_batch=w.batch,
+                        max_blocks_per_seq=max_blocks, device=GH.DEV)
+    ref, inner = mk(), mk()
+    table = np.full((w.batch, max_blocks), -1, dtype=np.int32)
+    i = 0
+    for b in range(w.batch):
+        for j in range(int(n_blocks[b])):
+            table[b, j] = i
+            i += 1
+    assert ref.block_alloc(B.GPU, nb) == list(range(nb))
+    gen = torch.Generator(device=GH.DEV)
+    gen.manual_seed(5)
+    fill = (torch.randn(ref.gpu_image().numel() // 2, device=GH.DEV, generator=gen) * 0.5).to(torch.float16)
+    ref.gpu_image().view(-1).view(torch.float16).copy_(fill)
+    inner.gpu_image().copy_(ref.gpu_image())
+    q = (torch.randn(n, w.batch, w.n_q_heads, w.head_dim, device=GH.DEV, generator=gen) * 0.5).to(torch.float16)
+    ep = B.ElasticPool(inner, C, k_cap, host)
+    cs, si, so = torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()
+    d_table, d_ctx = torch.from_numpy(table).to(GH.DEV), torch.from_numpy(ctx).to(GH.DEV)
+    out_ref, out = torch.empty_like(q), torch.empty_like(q)
+    none = np.zeros(0, dtype=np.int32)
+    ctl = B.Controller(n, host - 2, k_up=3, k_down=2, probe_period=1000)
+
+    def token():
+        t0 = time.perf_counter()
+        ep.step(q, None, None, d_table, d_ctx, out, cs, si, so)
+        inner.sync()
+        dt = (time.perf_counter() - t0) * 1e3
+        assert torch.equal(out.view(torch.int16), out_ref.view(torch.int16))
+        return dt
+
+    try:
+        ref.step(q, None, None, d_table, d_ctx, none, none, out_ref, cs, si, so)
+        ref.sync()
+        t_swap_us = 40.0 + k0 * ep.chunk_bytes / 33e3            # copy engines with both directions busy
+        t_layer_us = t_swap_us / 1.7
+        inner.set_layer_compute_us(t_layer_us)
+        # once around before the clock counts: the first transfers through fresh pinned memory are slow
+        assert ep.set_layers_on_cpu(host - 2, nb, cs)
+        for _ in range(4):
+            token()
+        assert ep.set_layers_on_cpu(0, nb, cs)
+        for _ in range(12):
+            token()
+        ep.settle(cs)
+        assert all(s == B.LAYER_GPU for s, _, _ in ep.table()) and ep.capacity() == (k0 * C, k0 * C, 0)
+        levels, stalls, visible, dts, level, prev_stall = [], [], [], [], 0, ep.stats().stall_ms
+        for _ in range(70):
+            levels.append(level)
+            dt_ms = token()
+            st = ep.stats()
+            stall = st.stall_ms - prev_stall
+            prev_stall = st.stall_ms
+            stalls.append(stall)
+            dts.append(dt_ms)
+            vis, tgt, m = ep.capacity()
+            visible.append(vis)
+            assert m == level and vis <= tgt
+            tc = (dt_ms - stall) / n
+            # the level is credited with the size it leads to, as soon as it is asked for
+            new = ctl.observe([tc] * n, [0.0] * n, [stall / n] * n, 0.0, (1.0 / dt_ms) * tgt / (k0 * C))
+            if new != level:
+                assert ep.set_layers_on_cpu(new, nb, cs)         # the live blocks all lie below the smallest cache
+                level = new
+        assert inner.check_errors() == 0
+        print("levels", levels, "visible blocks", visible, "ms per token", [round(x, 2) for x in dts],
+              "waits", [round(x, 2) for x in stalls])
+        assert levels[:3] == [0, 0, 0] and max(levels) >= 2, levels
+        assert all(abs(b - a) <= 1 for a, b in zip(levels, levels[1:])), levels
+        assert len(set(levels[-12:])) == 1 and levels[-1] >= 1, levels
+        token_ms = n * t_layer_us / 1e3
+        assert sum(stalls[-10:]) <= 0.02 * 10 * token_ms, (levels, stalls[-10:])
+        m_end = levels[-1]
+        assert visible[-1] == min(k_cap, (n * k0) // (n - m_end)) * C > k0 * C     # a / (n - m), in whole chunks
+        assert visible[0] == k0 * C
+    finally:
+        ctl.close()
+        ep.close()
+        inner.close()
+        ref.close()
