@@ -450,8 +450,9 @@ int pie_chunk_book_destroy(pie_chunk_book* book);
  * PIE_ESTATE: the caches would have to shrink below that; what is visible has been lowered all the same
  * (hidden first), nothing else has changed; ask again when the blocks above have been given up. */
 int pie_chunk_book_set_layers_on_cpu(pie_chunk_book* book, int32_t m, int32_t chunks_in_use);
-/* The layer's swap-out has completed: its chunks are free (and may go to resident layers at once). */
-int pie_chunk_book_left_gpu(pie_chunk_book* book, int32_t layer);
+/* The layer's swap-out has completed: its chunks are free (and may go to resident layers at once).  n_carried:
+ * how many of its chunks it took along - those that hold live blocks; -1 = all. */
+int pie_chunk_book_left_gpu(pie_chunk_book* book, int32_t layer, int32_t n_carried);
 /* The layer's swap-in starts: it takes chunks; *out_n_data = how many of them its data fills.  PIE_ENOMEM if
  * fewer chunks are free than it carries or than are visible. */
 int pie_chunk_book_enters_gpu(pie_chunk_book* book, int32_t layer, int32_t* out_n_data);
@@ -479,6 +480,9 @@ int pie_elastic_destroy(pie_elastic_pool* ep);
  * block index + 1.  Completes the moves in flight first.  PIE_ESTATE as pie_chunk_book_set_layers_on_cpu.  The
  * layers then leave (or return) through the protocol during the following steps. */
 int pie_elastic_set_layers_on_cpu(pie_elastic_pool* ep, int32_t m, int32_t blocks_in_use_end, void* compute_stream);
+/* Tells the pool the highest live block index + 1 (-1: unknown, the default): a layer that leaves the GPU
+ * takes along only the chunks below it.  Blocks above must hold nothing that is still needed. */
+int pie_elastic_set_live_blocks(pie_elastic_pool* ep, int32_t blocks_in_use_end);
 /* Blocks per layer a scheduler may use now, what they will be when the reallocation is complete, and m. */
 int pie_elastic_capacity(pie_elastic_pool* ep, int32_t* out_visible_blocks, int32_t* out_target_blocks,
                          int32_t* out_layers_on_cpu);

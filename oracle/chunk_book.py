@@ -5,7 +5,8 @@ caches in CPU memory and gives the GPU memory they leave to the layers that
 stay: a cache of a bytes per n layers becomes a / (n - m) per layer.  New
 blocks are shown to the scheduler only once the reallocation is complete;
 when the cache shrinks, blocks are hidden from the scheduler first and freed
-afterwards.
+afterwards.  A layer that leaves takes along the chunks that hold live blocks
+(the caller says how many); the rest it simply gives up.
 
 The paper reallocates a layer's cache as one piece when the layer is swapped
 back in.  This build cuts the GPU memory into N chunks of equal size and lets a
@@ -73,11 +74,14 @@ class ChunkBook:
         return True
 
     # ---- what the driver reports ------------------------------------------------------------------
-    def left_gpu(self, j: int):
+    def left_gpu(self, j: int, n_carried=None):
+        """n_carried: how many of its chunks the layer took along (those with live blocks; all by default)."""
         if not self.resident[j]:
             raise BookError(ESTATE)
+        if n_carried is not None and not 0 <= n_carried <= len(self.chunks[j]):
+            raise BookError(EINVAL)
         self.resident[j] = False
-        self.image[j] = len(self.chunks[j])
+        self.image[j] = len(self.chunks[j]) if n_carried is None else n_carried
         for c in self.chunks[j]:
             self._release(c)
         self.chunks[j] = []

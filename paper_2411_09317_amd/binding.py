@@ -41,7 +41,7 @@ SYMBOLS = [
     "pie_chunk_book_create", "pie_chunk_book_destroy", "pie_chunk_book_set_layers_on_cpu", "pie_chunk_book_left_gpu",
     "pie_chunk_book_enters_gpu", "pie_chunk_book_layer", "pie_chunk_book_capacity",
     "pie_elastic_bytes_required", "pie_elastic_create", "pie_elastic_destroy", "pie_elastic_set_layers_on_cpu",
-    "pie_elastic_capacity", "pie_elastic_step", "pie_elastic_settle_sync", "pie_elastic_layer", "pie_elastic_table",
+    "pie_elastic_capacity", "pie_elastic_set_live_blocks", "pie_elastic_step", "pie_elastic_settle_sync", "pie_elastic_layer", "pie_elastic_table",
     "pie_elastic_stats",
 ]
 
@@ -495,8 +495,8 @@ class ChunkBook:
         _check(rc, "chunk_book_set_layers_on_cpu")
         return True
 
-    def left_gpu(self, layer: int):
-        _check(_lib.pie_chunk_book_left_gpu(self._h, C.c_int32(layer)), "chunk_book_left_gpu")
+    def left_gpu(self, layer: int, n_carried: int = -1):
+        _check(_lib.pie_chunk_book_left_gpu(self._h, C.c_int32(layer), C.c_int32(n_carried)), "chunk_book_left_gpu")
 
     def enters_gpu(self, layer: int) -> Tuple[List[int], int]:
         n_data = C.c_int32(0)
@@ -555,6 +555,9 @@ class ElasticPool:
             return False
         _check(rc, "elastic_set_layers_on_cpu")
         return True
+
+    def set_live_blocks(self, blocks_in_use_end: int):
+        _check(_lib.pie_elastic_set_live_blocks(self._h, C.c_int32(blocks_in_use_end)), "elastic_set_live_blocks")
 
     def capacity(self) -> Tuple[int, int, int]:
         """(visible blocks per layer, target blocks per layer, layers asked to be in CPU memory)."""

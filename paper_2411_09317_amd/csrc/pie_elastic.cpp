@@ -120,18 +120,21 @@ int pie_chunk_book_set_layers_on_cpu(pie_chunk_book* b, int32_t m, int32_t chunk
   return book_set(b, m, chunks_in_use, nullptr);
 }
 
-static int book_left(pie_chunk_book* b, int32_t layer, std::vector<int32_t>* grown) {
+static int book_left(pie_chunk_book* b, int32_t layer, int32_t n_carried, std::vector<int32_t>* grown) {
   if (!b || layer < 0 || layer >= b->n) return PIE_EINVAL;
   if (!b->resident[layer]) return PIE_ESTATE;
+  if (n_carried > (int32_t)b->chunks[layer].size()) return PIE_EINVAL;
   b->resident[layer] = 0;
-  b->image[layer] = (int32_t)b->chunks[layer].size();
+  b->image[layer] = n_carried < 0 ? (int32_t)b->chunks[layer].size() : n_carried;
   for (int32_t c : b->chunks[layer]) b->release(c);
   b->chunks[layer].clear();
   b->top_up(grown);
   return PIE_OK;
 }
 
-int pie_chunk_book_left_gpu(pie_chunk_book* b, int32_t layer) { return book_left(b, layer, nullptr); }
+int pie_chunk_book_left_gpu(pie_chunk_book* b, int32_t layer, int32_t n_carried) {
+  return book_left(b, layer, n_carried, nullptr);
+}
 
 int pie_chunk_book_enters_gpu(pie_chunk_book* b, int32_t layer, int32_t* out_n_data) {
   if (!b || layer < 0 || layer >= b->n) return PIE_EINVAL;
@@ -185,6 +188,8 @@ struct pie_elastic_pool {
   std::vector<uint8_t> ev_layer_rec;
   pie_layer_stats stats;
   int32_t prev_layer = -1;
+  int32_t live_chunks = -1;            // chunks of a cache that hold live blocks (-1: all)
+  int32_t out_carried = 0;             // chunks the swap-out in flight copies
 };
 
 namespace {
@@ -207,7 +212,7 @@ int on_out_complete(pie_elastic_pool* lp, hipStream_t cs) {
   const int32_t layer = lp->sched->moving_out;
   pie_layer_sched_complete(lp->sched, 1);
   std::vector<int32_t> grown;
-  int rc = book_left(lp->book, layer, &grown);
+  int rc = book_left(lp->book, layer, lp->out_carried, &grown);
   if (rc) return rc;
   for (int32_t j : grown)                          // resident layers that were given its chunks
     if ((rc = send_map(lp, j, cs))) return rc;
@@ -239,12 +244,15 @@ int start_moves(pie_elastic_pool* lp, const pie_layer_action& a, hipStream_t cs,
   if (a.out_layer >= 0) {
     if (lp->ev_layer_rec[a.out_layer]) PIE_HIP(hipEventSynchronize(lp->ev_layer[a.out_layer]));
     const std::vector<int32_t>& c = lp->book->chunks[a.out_layer];
-    for (size_t i = 0; i < c.size(); ++i)
+    // only the chunks that hold live blocks travel; the others are simply given up
+    const size_t n_carry = lp->live_chunks < 0 ? c.size() : std::min(c.size(), (size_t)lp->live_chunks);
+    for (size_t i = 0; i < n_carry; ++i)
       PIE_HIP(hipMemcpyAsync(slot_host(lp, a.out_host_slot) + i * lp->chunk_bytes, chunk_dev(lp, c[i]), lp->chunk_bytes,
                              hipMemcpyDeviceToHost, os));
     PIE_HIP(hipEventRecord(lp->ev_out, os));
+    lp->out_carried = (int32_t)n_carry;
     ++lp->stats.n_swap_out;
-    lp->stats.bytes_out += c.size() * lp->chunk_bytes;
+    lp->stats.bytes_out += n_carry * lp->chunk_bytes;
   }
   if (a.in_layer >= 0) {
     int32_t n_data = 0;
@@ -373,6 +381,12 @@ int pie_elastic_set_layers_on_cpu(pie_elastic_pool* lp, int32_t m, int32_t block
   for (int32_t j = 0; j < lp->n; ++j)
     if (changed[j] && (rc = send_map(lp, j, cs))) return rc;
   return pie_layer_sched_set_gpu_slots(lp->sched, lp->n - m);
+}
+
+int pie_elastic_set_live_blocks(pie_elastic_pool* lp, int32_t blocks_in_use_end) {
+  if (!lp || blocks_in_use_end < -1) return PIE_EINVAL;
+  lp->live_chunks = blocks_in_use_end < 0 ? -1 : (blocks_in_use_end + lp->C - 1) / lp->C;
+  return PIE_OK;
 }
 
 int pie_elastic_capacity(pie_elastic_pool* lp, int32_t* out_visible_blocks, int32_t* out_target_blocks,

@@ -52,7 +52,11 @@ def test_random_histories(seed):
             assert lib.set_layers_on_cpu(m, in_use) == mod.set_layers_on_cpu(m, in_use)
         elif r < 0.6 and n_res > 1:
             j = int(rng.choice([j for j in range(n) if mod.resident[j]]))
-            lib.left_gpu(j), mod.left_gpu(j)
+            if rng.random() < 0.5:
+                lib.left_gpu(j), mod.left_gpu(j)
+            else:                                                      # it takes along only the live chunks
+                carried = int(rng.integers(0, min(in_use, len(mod.chunks[j])) + 1))
+                lib.left_gpu(j, carried), mod.left_gpu(j, carried)
         else:
             cpu = [j for j in range(n) if not mod.resident[j]]
             if cpu:

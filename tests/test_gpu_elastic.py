@@ -104,6 +104,7 @@ def test_capacity_follows_the_layers_on_the_cpu_and_results_never_change(dtype):
         # ---- two layers to the CPU: each cache grows to 63 // 7 = 9 chunks once they have left ----
         assert ep.set_layers_on_cpu(2, nb, cs)
         assert ep.capacity() == (K0 * C, 9 * C, 2)
+        ep.set_live_blocks(nb)                                    # leaving layers take only the live chunks along
         seen = []
         for _ in range(6):
             step()
@@ -114,7 +115,9 @@ def test_capacity_follows_the_layers_on_the_cpu_and_results_never_change(dtype):
         assert seen[-1] == 9 * C and all(a <= b for a, b in zip(seen, seen[1:])), seen
         st = ep.stats()
         assert st.n_swap_out >= 2 and st.n_swap_in >= 0
+        assert st.bytes_out == st.n_swap_out * ((nb + C - 1) // C) * ep.chunk_bytes     # live chunks only
         # ---- a sequence joins in blocks beyond the old caches ----
+        ep.set_live_blocks(late[-1] + 1)
         for t in range(20):
             ctx[3] = t + 1                                        # grows from its first token, crosses into its 2nd block
             step()
@@ -125,6 +128,7 @@ def test_capacity_follows_the_layers_on_the_cpu_and_results_never_change(dtype):
         assert ep.capacity() == (K0 * C, 9 * C, 2)                # hidden at once, nothing else changed
         step()
         ctx[3] = 0                                                # the sequence ends; its blocks are given up
+        ep.set_live_blocks(nb)
         assert ep.set_layers_on_cpu(1, nb, cs)
         assert ep.capacity() == (K0 * C, K0 * C, 1)
         for _ in range(3):
@@ -200,6 +204,7 @@ def test_adaptive_expansion_grows_the_caches_on_hardware():
         t_swap_us = 40.0 + k0 * ep.chunk_bytes / 33e3            # copy engines with both directions busy
         t_layer_us = t_swap_us / 1.7
         inner.set_layer_compute_us(t_layer_us)
+        ep.set_live_blocks(nb)                                    # a layer always travels as its k0 live chunks
         # once around before the clock counts: the first transfers through fresh pinned memory are slow
         assert ep.set_layers_on_cpu(host - 2, nb, cs)
         for _ in range(4):

@@ -62,6 +62,20 @@ def test_a_shrink_hides_at_once_and_waits_for_the_blocks_above_to_be_given_up():
     assert b2.set_layers_on_cpu(2, 8) and b2.visible == 8
 
 
+def test_a_leaving_layer_carries_only_what_it_is_told_is_live():
+    b = ChunkBook(4, 16, 8)
+    b.set_layers_on_cpu(2, 4)
+    b.left_gpu(3, 3)                                 # three of its four chunks hold live blocks
+    b.left_gpu(2)
+    assert b.image == [4, 4, 4, 3] and b.visible == 8
+    b.left_gpu(0, 5)                                 # grown to eight, five of them live
+    got, n_data = b.enters_gpu(3)
+    assert len(got) == 8 and n_data == 3
+    with pytest.raises(BookError):
+        b.left_gpu(1, 9)
+    b.check()
+
+
 def test_the_cap_per_layer_bounds_the_target():
     b = ChunkBook(4, 16, 6)
     assert [b.target_for(m) for m in range(4)] == [4, 5, 6, 6]
