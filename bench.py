@@ -349,6 +349,7 @@ def elastic_leg(w, dw, m, n_steps, t_other_us, base_step_ms, chunk_blocks=256):
         return time.perf_counter() - t0
     run(1)
     resident_ms = run(n_steps) / n_steps * 1e3                       # everything on the GPU, through the block maps
+    ep.set_live_blocks(dw.total_blocks)                          # a leaving layer takes along only the chunks in use
     ep.set_layers_on_cpu(m, dw.total_blocks, streams[0])
     steps_to_visible = 0
     while ep.capacity()[0] < ep.capacity()[1] and steps_to_visible < 4 * n:
