@@ -232,8 +232,9 @@ class DeviceLoop:
         self.d_ctx = torch.empty(max_batch, dtype=torch.int32, device=device)
         self.streams = (torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream())
 
-    def iteration(self, sched: Scheduler):
-        """One decode iteration of everything running; returns (seconds, host blocks read per layer)."""
+    def iteration(self, sched: Scheduler, step=None):
+        """One decode iteration of everything running; returns (seconds, host blocks read per layer).  `step`:
+        another pool's step with the argument list of pie_layer_step (no prefetch lists), instead of pie_step."""
         import time
         torch, w = self.torch, self.w
         table, ctx = sched.tables()
@@ -244,12 +245,17 @@ class DeviceLoop:
         with torch.cuda.stream(self.streams[0]):
             self.d_table[:B].copy_(self.h_table[:B], non_blocking=True)
             self.d_ctx[:B].copy_(self.h_ctx[:B], non_blocking=True)
+        shape = lambda t, h: t[: w.n_layers * B * h * w.head_dim].view(w.n_layers, B, h, w.head_dim)
+        if step is not None:
+            step(shape(self.q, w.n_q_heads), shape(self.k_new, w.n_kv_heads), shape(self.v_new, w.n_kv_heads),
+                 self.d_table[:B], self.d_ctx[:B], shape(self.out, w.n_q_heads), *self.streams)
+            self.pool.sync()
+            return time.perf_counter() - t0, 0
         pf, dirty = self.pool.prefetch_list(table, ctx)
         self.last_runs = 0
         if len(pf):                                # pieces the layer's prefetch falls into (the list is in slot order)
             slots = np.asarray(self.pool.block_where(pf)[1])
             self.last_runs = 1 + int((np.diff(slots) != 1).sum())
-        shape = lambda t, h: t[: w.n_layers * B * h * w.head_dim].view(w.n_layers, B, h, w.head_dim)
         self.pool.step(shape(self.q, w.n_q_heads), shape(self.k_new, w.n_kv_heads), shape(self.v_new, w.n_kv_heads),
                        self.d_table[:B], self.d_ctx[:B], pf, dirty, shape(self.out, w.n_q_heads), *self.streams)
         self.pool.sync()
@@ -302,4 +308,119 @@ def serve(pool, w, requests: List[Request], budget: BlockBudget, max_batch: int,
     if levels:
         res["level_mean"] = float(np.mean(levels))
         res["level_max"] = int(max(levels))
+    return res
+
+
+# ---- the same on layer caches that grow and shrink (the paper's own unit) ------------------------------------
+
+class IndexStore:
+    """Blocks as indices into a layer's cache (the same index in every layer), lowest free index first, below
+    a limit that moves with the caches' size.  Has the block-store methods the scheduler uses; every block
+    counts as GPU-homed (in this unit whole layers move, not blocks)."""
+
+    def __init__(self, n_indices: int, limit: int):
+        self.used = np.zeros(n_indices, dtype=bool)
+        self.limit = limit
+
+    def n_free(self, where: int) -> int:
+        return int(self.limit - self.used[: self.limit].sum()) if where == GPU else 0
+
+    def block_alloc(self, where: int, n: int) -> List[int]:
+        if n == 0:
+            return []
+        idx = np.flatnonzero(~self.used[: self.limit])[:n]
+        if where != GPU or len(idx) < n:
+            raise MemoryError("no free block below the limit")
+        self.used[idx] = True
+        return idx.tolist()
+
+    def block_free(self, handles):
+        self.used[np.asarray(handles, dtype=np.int64)] = False
+
+    def block_where(self, handles):
+        return [GPU] * len(handles), list(handles)
+
+    def live_end(self) -> int:
+        nz = np.flatnonzero(self.used)
+        return int(nz[-1]) + 1 if len(nz) else 0
+
+
+class VisibleBudget:
+    """What the scheduler may promise = what the elastic pool shows."""
+
+    def __init__(self, elastic, base_blocks: int):
+        self.ep, self.base = elastic, base_blocks
+
+    @property
+    def capacity(self) -> int:
+        return self.ep.capacity()[0]
+
+    @property
+    def expansion(self) -> float:
+        return self.capacity / self.base
+
+
+def serve_elastic(elastic, w, requests: List[Request], max_batch: int, max_blocks: int, controller=None,
+                  layers_on_cpu: int = 0, progress=None) -> dict:
+    """Serves a request stream on an elastic pool (binding.ElasticPool).  The number of layers kept in CPU memory
+    is fixed (`layers_on_cpu`) or follows a controller (binding.Controller over levels = layers) that sees,
+    per token, whether computation waited for a layer.  A shrink that is refused hides the blocks at once; it
+    is asked for again every iteration until the blocks above the new size have been given up."""
+    pool = elastic.pool
+    base = pool.cfg.n_gpu_blocks
+    n = elastic.n_layers
+    loop = DeviceLoop(pool, w, max_batch, max_blocks)
+    store = IndexStore(elastic.k_cap * elastic.C, base)
+    budget = VisibleBudget(elastic, base)
+    sched = Scheduler(store, w.block_tokens, budget, max_batch, max_blocks)
+    for r in requests:
+        sched.submit(r)
+    cs = loop.streams[0]
+    want = layers_on_cpu
+    now, iters, batch_sum, busy, levels, sizes, recent, prev_stall, refused = 0.0, 0, 0, 0.0, [], [], [], 0.0, 0
+    while not sched.idle:
+        vis, tgt, m = elastic.capacity()
+        if want != m:
+            if elastic.set_layers_on_cpu(want, store.live_end(), cs):
+                vis, tgt, m = elastic.capacity()
+            else:
+                refused += 1
+        # blocks that exist in every layer right now: while a shrink is pending the caches are still large
+        store.limit = max(store.limit, vis) if want < m else vis
+        sched.admit(now)
+        if not sched.running:
+            now = max(now, sched.waiting[0].arrival)
+            continue
+        elastic.set_live_blocks(store.live_end())
+        dt, _ = loop.iteration(sched, step=elastic.step)
+        B = len(sched.running)
+        now += dt
+        busy += dt
+        iters += 1
+        batch_sum += B
+        levels.append(m)
+        sizes.append(vis)
+        if controller is not None:
+            st = elastic.stats()
+            stall, prev_stall = st.stall_ms - prev_stall, st.stall_ms
+            recent.append((B, dt))
+            del recent[:-8]
+            tc = (dt * 1e3 - stall) / n
+            rate = sum(b for b, _ in recent) / sum(t for _, t in recent)
+            want = controller.observe([tc] * n, [0.0] * n, [stall / n] * n, 0.0, rate * tgt / max(vis, 1))
+        sched.complete_iteration(now)
+        if progress and iters % 500 == 0:
+            progress(iters, now, len(sched.done))
+    flags = pool.check_errors()
+    if flags:
+        raise RuntimeError(f"device error flags {flags:#x} while serving")
+    res = summarize(sched.done, now)
+    st = elastic.stats()
+    res.update({"iterations": iters, "mean_batch": batch_sum / max(iters, 1), "ms_per_iteration": busy / max(iters, 1) * 1e3,
+                "layers_on_cpu_mean": float(np.mean(levels)) if levels else 0.0,
+                "layers_on_cpu_max": int(max(levels)) if levels else 0,
+                "blocks_per_layer_mean": float(np.mean(sizes)) if sizes else 0.0,
+                "blocks_per_layer_max": int(max(sizes)) if sizes else 0, "blocks_per_layer_base": base,
+                "shrinks_refused": refused, "swap_ins": int(st.n_swap_in), "swap_outs": int(st.n_swap_out),
+                "forced_ins": int(st.n_forced_in), "host_wait_ms": float(st.stall_ms)})
     return res

@@ -248,3 +248,99 @@ def test_adaptive_expansion_grows_the_caches_on_hardware():
         ep.close()
         inner.close()
         ref.close()
+
+
+def test_serving_on_growing_and_shrinking_caches_matches_an_all_resident_pool():
+    """Requests come and go while the number of layers kept in CPU memory is moved up and down: admission
+    follows the size the pool shows, new requests land in blocks that did not exist before, a shrink waits for
+    them to end.  Every iteration's outputs are, bit for bit, those of a plain pool holding all layers at the
+    largest size, fed the same tables and the same rows."""
+    from paper_2411_09317_amd import serving as S
+    n, C, k0, k_cap, host = 6, 4, 6, 12, 5
+    dtype = I.DTYPE_F16
+    w = I.Workload("eserve", n, 0, 8, 2, 128, dtype, ctx_lo=10, ctx_hi=90, value_scale=0.5, seed=71)
+    max_batch, max_blocks = 12, 8
+    mk = lambda blocks: B.Pool(n, w.n_q_heads, w.n_kv_heads, w.head_dim, 16, dtype, blocks, 0, 0, max_batch=max_batch,
+                               max_blocks_per_seq=max_blocks, device=GH.DEV)
+    ref, inner = mk(k_cap * C), mk(k0 * C)
+    assert ref.block_alloc(B.GPU, k_cap * C) == list(range(k_cap * C))
+    gen = torch.Generator(device=GH.DEV)
+    gen.manual_seed(9)
+    fill = (torch.randn(ref.gpu_image().numel() // 2, device=GH.DEV, generator=gen) * 0.5).to(torch.float16)
+    ref.gpu_image().view(-1).view(torch.float16).copy_(fill)           # whatever was there before
+    inner.gpu_image().copy_(ref.gpu_image()[:, : k0 * C])
+    ep = B.ElasticPool(inner, C, k_cap, host)
+    loop = S.DeviceLoop(inner, w, max_batch, max_blocks)
+    store = S.IndexStore(k_cap * C, k0 * C)
+    sched = S.Scheduler(store, 16, S.VisibleBudget(ep, k0 * C), max_batch, max_blocks)
+    # every token of a request is appended by a step (empty prompts): a block's content is then defined in both
+    # pools, whichever chunk it lives in (blocks that are not live are not carried when a layer moves)
+    a, p, o = I.draw_requests(w, 60, 1e6, 20, 110)
+    for i in range(60):
+        sched.submit(S.Request(i, float(a[i]), 0, int(o[i])))
+    none = np.zeros(0, dtype=np.int32)
+    plan = {5: 2, 50: 3, 90: 1, 130: 0}                               # iteration -> layers asked to be on the CPU
+    want, it, sizes, above, refused = 0, 0, [], 0, 0
+    cs = loop.streams[0]
+    try:
+        while not sched.idle:
+            want = plan.get(it, want)
+            vis, tgt, m = ep.capacity()
+            if want != m:
+                if ep.set_layers_on_cpu(want, store.live_end(), cs):
+                    vis, tgt, m = ep.capacity()
+                else:
+                    refused += 1
+            store.limit = max(store.limit, vis) if want < m else vis
+            sched.admit(1.0)
+            assert sched.running
+            table, ctx = sched.tables()
+            B_ = len(ctx)
+            above += int((table >= k0 * C).sum() > 0)
+            ep.set_live_blocks(store.live_end())
+            dt, _ = loop.iteration(sched, step=ep.step)
+            shape = lambda t, h: t[: n * B_ * h * w.head_dim].view(n, B_, h, w.head_dim)
+            out_ref = torch.empty_like(shape(loop.out, w.n_q_heads))
+            ref.step(shape(loop.q, w.n_q_heads), shape(loop.k_new, w.n_kv_heads), shape(loop.v_new, w.n_kv_heads),
+                     loop.d_table[:B_], loop.d_ctx[:B_], none, none, out_ref, *loop.streams)
+            ref.sync()
+            assert torch.equal(shape(loop.out, w.n_q_heads).view(torch.int16), out_ref.view(torch.int16)), it
+            sizes.append(vis)
+            sched.complete_iteration(1.0)
+            it += 1
+            assert it < 3000
+        assert inner.check_errors() == 0 and ref.check_errors() == 0
+        assert len(sched.done) == 60 and not store.used.any()
+        assert max(sizes) >= 9 * C > k0 * C and above > 10          # requests lived in blocks the small caches lack
+        assert it > 130 or want == plan[max(k for k in plan if k <= it)]
+    finally:
+        ep.close()
+        inner.close()
+        ref.close()
+
+
+def test_serve_elastic_runs_to_completion_with_the_controller():
+    from paper_2411_09317_amd import serving as S
+    n, C, k0, host = 8, 16, 8, 5
+    w = I.Workload("eserve2", n, 0, 8, 2, 128, I.DTYPE_BF16, ctx_lo=64, ctx_hi=400, value_scale=0.5, seed=72)
+    max_batch, max_blocks = 32, 32
+    k_cap = (n * k0) // (n - (host - 2))
+    inner = B.Pool(n, w.n_q_heads, w.n_kv_heads, w.head_dim, 16, w.dtype, k0 * C, 0, 0, max_batch=max_batch,
+                   max_blocks_per_seq=max_blocks, device=GH.DEV)
+    inner.gpu_image().zero_()
+    ep = B.ElasticPool(inner, C, k_cap, host)
+    inner.set_layer_compute_us(300.0)
+    a, p, o = I.draw_requests(w, 80, 1e6, 8, 48)
+    reqs = [S.Request(i, float(a[i]), int(p[i]), int(o[i])) for i in range(80)]
+    ctl = B.Controller(n, host - 2, k_up=3, k_down=2, probe_period=1000)
+    try:
+        res = S.serve_elastic(ep, w, reqs, max_batch, max_blocks, controller=ctl)
+        assert res["requests"] == 80 and res["tokens"] == int(o.sum()) and res["tokens_per_s"] > 0
+        assert res["blocks_per_layer_max"] >= k0 * C and res["layers_on_cpu_max"] >= 1
+        reqs = [S.Request(i, float(a[i]), int(p[i]), int(o[i])) for i in range(80)]
+        res2 = S.serve_elastic(ep, w, reqs, max_batch, max_blocks, layers_on_cpu=2)
+        assert res2["requests"] == 80 and res2["blocks_per_layer_max"] == min(k_cap, (n * k0) // (n - 2)) * C
+    finally:
+        ctl.close()
+        ep.close()
+        inner.close()

@@ -242,3 +242,43 @@ def test_counting_model_on_a_hand_worked_stream():
     # one unit of 2 host blocks more: all three at once, 6 blocks promised
     trace, adm, fin = serving_sim.simulate([0, 0, 0], [20, 40, 10], [12, 8, 6], 4, 2, lambda it: 1, 16)
     assert adm == [0, 0, 0] and fin == [11, 7, 5] and trace[0][1:] == ([0, 1, 2], 6, 6)
+
+
+def test_index_store_hands_out_the_lowest_free_index_below_its_limit():
+    st = S.IndexStore(16, 6)
+    assert st.n_free(GPU) == 6 and st.n_free(HOST) == 0 and st.live_end() == 0
+    assert st.block_alloc(GPU, 4) == [0, 1, 2, 3]
+    st.block_free([1, 2])
+    assert st.block_alloc(GPU, 3) == [1, 2, 4] and st.live_end() == 5 and st.n_free(GPU) == 1
+    with pytest.raises(MemoryError):
+        st.block_alloc(GPU, 2)
+    st.limit = 10                                                    # the caches have grown
+    assert st.block_alloc(GPU, 2) == [5, 6] and st.n_free(GPU) == 3
+    st.block_free([6, 5, 4])
+    assert st.live_end() == 4 and st.block_where([3, 0]) == ([GPU, GPU], [3, 0])
+
+
+def test_scheduler_over_an_index_store_follows_a_capacity_that_moves():
+    class Shown:                                                     # stands for the elastic pool's visible size
+        capacity = 24
+        expansion = 1.0
+    bud, st = Shown(), S.IndexStore(64, 24)
+    sc = S.Scheduler(st, T, bud, 64, 16)
+    for r in requests(n=120, rate=1e6):
+        sc.submit(r)
+    it, peak = 0, []
+    while not sc.idle:
+        if it == 20:
+            bud.capacity, st.limit = 40, 40                          # growth shows
+        if it == 60:
+            bud.capacity = 24                                        # a shrink hides at once; the blocks still exist
+        if it > 60 and st.limit == 40 and st.live_end() <= 24:
+            st.limit = 24                                            # given up: the cut can be made
+        sc.admit(1.0)
+        assert sc.running
+        assert sc.blocks_in_use == int(st.used.sum()) <= st.limit
+        peak.append(sc.blocks_in_use)
+        sc.complete_iteration(1.0)
+        it += 1
+    assert len(sc.done) == 120 and not st.used.any()
+    assert max(peak[:20]) <= 24 < max(peak[20:60]) <= 40 and st.limit == 24 and max(peak[-5:]) <= 24
