@@ -68,6 +68,11 @@ def parse():
                     help="experiment instead of the benchmark line: serve this many synthetic requests (Poisson arrivals, "
                          "iteration-level scheduling) on a GPU pool of --serve-gpu-blocks blocks per layer at the expansion "
                          "levels in --serve-levels and with the controller; prints its own JSON line")
+    ap.add_argument("--serve-elastic", action="store_true",
+                    help="with --serve: the paper's own unit - whole layers move and the caches of the layers that stay "
+                         "grow; --serve-levels are then numbers of layers kept in CPU memory, --serve-gpu-blocks a "
+                         "layer's cache while everything is on the GPU")
+    ap.add_argument("--serve-chunk-blocks", type=int, default=256)
     ap.add_argument("--serve-gpu-blocks", type=int, default=16384)
     ap.add_argument("--serve-levels", default="0,1,2,4,8", help="budget levels; one level = 1/64 of the GPU pool")
     ap.add_argument("--serve-load", type=float, default=0.8,
@@ -376,6 +381,64 @@ def elastic_leg(w, dw, m, n_steps, t_other_us, base_step_ms, chunk_blocks=256):
     return res
 
 
+def serving_elastic_mode(args):
+    """The same in the paper's own unit: whole layers move, the caches of the layers that stay grow, and the
+    scheduler admits against the size the pool shows.  Fixed numbers of layers in CPU memory, then the
+    controller; every request waiting from the start."""
+    import torch
+    from paper_2411_09317_amd import binding as B
+    from paper_2411_09317_amd import inputs as I
+    from paper_2411_09317_amd import serving as S
+    from paper_2411_09317_amd import workload as WL
+    w = I.scaled(I.CONFIGS[args.workload], batch=0, n_layers=args.layers or I.CONFIGS[args.workload].n_layers)
+    n, C = w.n_layers, args.serve_chunk_blocks
+    k0 = args.serve_gpu_blocks // C
+    ms = [int(x) for x in args.serve_levels.split(",")]
+    m_max = max(ms + [2])
+    k_cap = (n * k0) // (n - m_max)
+    out_lo, out_hi = 64, 256
+    max_blocks = (w.ctx_hi + out_hi + w.block_tokens - 1) // w.block_tokens
+    max_batch = 1024
+    inner = B.Pool(n, w.n_q_heads, w.n_kv_heads, w.head_dim, w.block_tokens, w.dtype, k0 * C, 0, 0, max_batch=max_batch,
+                   max_blocks_per_seq=max_blocks)
+    img = inner.gpu_image()
+    for l in range(n):
+        layer = img[l].view(-1).view(WL.TORCH_DT[w.dtype])
+        layer.copy_((torch.randn(layer.numel(), device=img.device, dtype=torch.float32) * w.value_scale).to(layer.dtype))
+    if args.t_other_us:
+        inner.set_layer_compute_us(args.t_other_us)
+
+    def stream():
+        a, p, o = I.draw_requests(w, args.serve, 1e9, out_lo, out_hi)
+        return [S.Request(i, float(a[i]), int(p[i]), int(o[i])) for i in range(args.serve)]
+
+    def run(m, adaptive=False):
+        ep = B.ElasticPool(inner, C, k_cap, m_max + 2)
+        ctl = B.Controller(n, m_max, k_up=8, k_down=2, probe_period=256) if adaptive else None
+        t0 = time.perf_counter()
+        r = S.serve_elastic(ep, w, stream(), max_batch, max_blocks, controller=ctl, layers_on_cpu=m,
+                            progress=lambda it, now, done: print(f"#   iteration {it}: {done} requests done, {now:.1f} s",
+                                                                 file=sys.stderr, flush=True))
+        r["wall_s"] = round(time.perf_counter() - t0, 2)
+        r["mode"] = "adaptive" if adaptive else f"{m} layers on the CPU"
+        if ctl:
+            ctl.close()
+        ep.close()
+        print(f"# serve elastic {r['mode']}: {r['tokens_per_s']:.0f} tok/s, batch {r['mean_batch']:.1f}, "
+              f"{r['ms_per_iteration']:.2f} ms/iter, blocks per layer {r['blocks_per_layer_mean']:.0f}, "
+              f"waits {r['host_wait_ms']:.0f} ms", file=sys.stderr, flush=True)
+        return r
+
+    res = {"experiment": "serving on layer caches that grow and shrink",
+           "workload": f"{w.name} shape, {n} layers, {k0} chunks of {C} blocks ({C * w.block_bytes / 1e6:.0f} MB) per layer "
+                       f"while everything is on the GPU ({n * k0 * C * w.block_bytes / 1e9:.1f} GB)",
+           "requests": args.serve, "prompt": f"{w.ctx_dist} [{w.ctx_lo},{w.ctx_hi}]", "output": f"uniform [{out_lo},{out_hi}]",
+           "t_other_us": args.t_other_us, "data": "synthetic"}
+    res["saturated"] = [run(m) for m in ms] + [run(0, adaptive=True)]
+    inner.close()
+    print(json.dumps(res))
+
+
 def serving_mode(args):
     """Expansion turned into batch size: a request stream served at fixed budget levels and by the controller,
     first saturated (every request waiting from the start: throughput), then at a share of the level-0
@@ -451,7 +514,7 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     if args.serve:
-        return serving_mode(args)
+        return serving_elastic_mode(args) if args.serve_elastic else serving_mode(args)
     w = I.CONFIGS[args.workload]
     if args.ctx_fixed:
         w = I.scaled(w, name=w.name + "-fixedctx", ctx_dist="fixed", ctx_lo=args.ctx_fixed, ctx_hi=args.ctx_fixed)
