@@ -169,7 +169,8 @@ inline char* h_block(const pie_pool* p, int32_t layer, int32_t slot) {
 }
 
 // kernel launchers (pie_kernels.hip)
-int launch_busy(double us, int wall_clock_khz, hipStream_t s, unsigned long long* clock_row = nullptr);
+int launch_busy(double us, int wall_clock_khz, hipStream_t s, unsigned long long* clock_row = nullptr,
+                hipEvent_t done = nullptr);
 int launch_stamp(unsigned long long* slot, hipStream_t s);
 int launch_clock_fold(unsigned long long* rows, int32_t n_layers, hipStream_t s);
 int launch_map_fill(int32_t* d_map, int32_t n, int32_t value, hipStream_t s);
@@ -194,7 +195,8 @@ int launch_attn_resolve(const pie_pool* p, const int32_t* d_table, const int32_t
 int launch_attn_decode(const pie_pool* p, int32_t layer, const void* d_q, int32_t max_blocks, const int32_t* d_ctx,
                        int32_t batch, void* d_out, hipStream_t s, hipEvent_t k_start = nullptr,
                        hipEvent_t k_end = nullptr, int32_t ticket_index = -1,
-                       unsigned long long* clock_row = nullptr, const LayerView* view = nullptr);
+                       unsigned long long* clock_row = nullptr, const LayerView* view = nullptr,
+                       hipEvent_t done = nullptr);
 int launch_stream_probe(const pie_pool* p, int32_t layer, int32_t max_blocks, int32_t batch, hipStream_t s);
 size_t attn_plan_ints(const pie_config& c);
 size_t attn_workspace_floats(const pie_config& c);

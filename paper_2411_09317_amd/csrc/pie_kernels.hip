@@ -17,6 +17,8 @@
 
 #include <cstdlib>
 
+#include <hip/hip_ext.h>
+
 #include "pie_internal.h"
 
 namespace pie {
@@ -105,13 +107,15 @@ int launch_stamp(unsigned long long* slot, hipStream_t s) {
   return PIE_OK;
 }
 
-int launch_busy(double us, int wall_clock_khz, hipStream_t s, unsigned long long* clock) {
+int launch_busy(double us, int wall_clock_khz, hipStream_t s, unsigned long long* clock, hipEvent_t done) {
   if (!(us > 0.0)) return PIE_OK;
   const unsigned long long ticks = (unsigned long long)(us * 1e-3 * (double)wall_clock_khz);
   // an iteration takes at least the sleep's 16 x 64 clocks, i.e. well over 0.1 us: 16 iterations per us plus
   // slack always reach the deadline first
   const uint32_t max_iter = (uint32_t)(us * 16.0) + 4096u;
-  hipLaunchKernelGGL(k_busy, dim3(1), dim3(64), 0, s, ticks, max_iter, clock);
+  // `done` completes with the kernel itself: no separate packet on the stream
+  if (done) hipExtLaunchKernelGGL(k_busy, dim3(1), dim3(64), 0, s, nullptr, done, 0, ticks, max_iter, clock);
+  else hipLaunchKernelGGL(k_busy, dim3(1), dim3(64), 0, s, ticks, max_iter, clock);
   PIE_HIP(hipGetLastError());
   return PIE_OK;
 }
@@ -1235,7 +1239,7 @@ int launch_attn_resolve(const pie_pool* p, const int32_t* d_table, const int32_t
 
 template <typename E, int HD, bool SPLIT>
 static int launch_mfma(const pie_pool* p, AttnArgs a, int32_t layer_row, int32_t batch, int32_t n_q_heads,
-                       hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
+                       hipStream_t s, hipEvent_t e0, hipEvent_t e1, hipEvent_t done) {
   const size_t lds = mfma_lds_floats<HD>(a.group) * sizeof(float);
   // as many workgroups as fit on the GPU at once; the ticket counter hands out the work
   static int wgs_per_cu[kMaxGroup + 1] = {};
@@ -1252,11 +1256,22 @@ static int launch_mfma(const pie_pool* p, AttnArgs a, int32_t layer_row, int32_t
   if (a.clock && grid <= kClockWgs)
     a.clock_wg = p->d_clock + ((size_t)p->cfg.n_layers + 1) * kClockRow + (size_t)layer_row * kClockWgs * 2;
   if (e0) PIE_HIP(hipEventRecord(e0, s));
-  hipLaunchKernelGGL((k_attn_decode_mfma<E, HD, SPLIT>), dim3(grid), dim3(kWaves * 64), lds, s, a);
+  // `done` (an event that completes with the layer's last kernel) rides on that kernel's own completion
+  // signal instead of a packet of its own behind it
+  const bool reduce = a.n_parts > 1;
+  if (done && !reduce)
+    hipExtLaunchKernelGGL((k_attn_decode_mfma<E, HD, SPLIT>), dim3(grid), dim3(kWaves * 64), (uint32_t)lds, s, nullptr,
+                          done, 0, a);
+  else
+    hipLaunchKernelGGL((k_attn_decode_mfma<E, HD, SPLIT>), dim3(grid), dim3(kWaves * 64), lds, s, a);
   PIE_HIP(hipGetLastError());
   if (e1) PIE_HIP(hipEventRecord(e1, s));
-  if (a.n_parts > 1) {
-    hipLaunchKernelGGL((k_attn_reduce<E, HD>), dim3(n_q_heads, batch), dim3(256), 0, s, a, n_q_heads);
+  if (reduce) {
+    if (done)
+      hipExtLaunchKernelGGL((k_attn_reduce<E, HD>), dim3(n_q_heads, batch), dim3(256), 0, s, nullptr, done, 0, a,
+                            n_q_heads);
+    else
+      hipLaunchKernelGGL((k_attn_reduce<E, HD>), dim3(n_q_heads, batch), dim3(256), 0, s, a, n_q_heads);
     PIE_HIP(hipGetLastError());
   }
   return PIE_OK;
@@ -1264,7 +1279,7 @@ static int launch_mfma(const pie_pool* p, AttnArgs a, int32_t layer_row, int32_t
 
 template <int HD>
 static int launch_f32(const AttnArgs& a, int32_t batch, int32_t n_q_heads, int32_t max_items, hipStream_t s,
-                      hipEvent_t e0, hipEvent_t e1) {
+                      hipEvent_t e0, hipEvent_t e1, hipEvent_t done) {
   if (e0) PIE_HIP(hipEventRecord(e0, s));
   // one workgroup per possible item and query head; those past the planned count return at once
   hipLaunchKernelGGL((k_attn_decode_f32<HD>), dim3(max_items, n_q_heads), dim3(kWaves * 64), 0, s, a);
@@ -1274,6 +1289,7 @@ static int launch_f32(const AttnArgs& a, int32_t batch, int32_t n_q_heads, int32
     hipLaunchKernelGGL((k_attn_reduce<F32, HD>), dim3(n_q_heads, batch), dim3(256), 0, s, a, n_q_heads);
     PIE_HIP(hipGetLastError());
   }
+  if (done) PIE_HIP(hipEventRecord(done, s));     // the fp32 path is not tuned: an ordinary record
   return PIE_OK;
 }
 
@@ -1281,7 +1297,7 @@ static int launch_f32(const AttnArgs& a, int32_t batch, int32_t n_q_heads, int32
 // same batch, table width and context lengths.
 int launch_attn_decode(const pie_pool* p, int32_t layer, const void* d_q, int32_t max_blocks, const int32_t* d_ctx,
                        int32_t batch, void* d_out, hipStream_t s, hipEvent_t k_start, hipEvent_t k_end,
-                       int32_t ticket_index, unsigned long long* clock_row, const LayerView* view) {
+                       int32_t ticket_index, unsigned long long* clock_row, const LayerView* view, hipEvent_t done) {
   const pie_config& c = p->cfg;
   if (((uintptr_t)d_q | (uintptr_t)d_out) % 16) return PIE_EINVAL;
   if (max_blocks <= 0) return PIE_EINVAL;
@@ -1319,15 +1335,15 @@ int launch_attn_decode(const pie_pool* p, int32_t layer, const void* d_q, int32_
   const int32_t row = clock_row ? (int32_t)((clock_row - p->d_clock) / kClockRow) : 0;
   switch (c.dtype) {
     case PIE_DTYPE_F32: {
-      return hd128 ? launch_f32<128>(a, batch, c.n_q_heads, a.max_items, s, k_start, k_end)
-                   : launch_f32<64>(a, batch, c.n_q_heads, a.max_items, s, k_start, k_end);
+      return hd128 ? launch_f32<128>(a, batch, c.n_q_heads, a.max_items, s, k_start, k_end, done)
+                   : launch_f32<64>(a, batch, c.n_q_heads, a.max_items, s, k_start, k_end, done);
     }
     case PIE_DTYPE_F16:
-      return hd128 ? launch_mfma<F16, 128, false>(p, a, row, batch, c.n_q_heads, s, k_start, k_end)
-                   : launch_mfma<F16, 64, false>(p, a, row, batch, c.n_q_heads, s, k_start, k_end);
+      return hd128 ? launch_mfma<F16, 128, false>(p, a, row, batch, c.n_q_heads, s, k_start, k_end, done)
+                   : launch_mfma<F16, 64, false>(p, a, row, batch, c.n_q_heads, s, k_start, k_end, done);
     case PIE_DTYPE_BF16:
-      return hd128 ? launch_mfma<BF16, 128, true>(p, a, row, batch, c.n_q_heads, s, k_start, k_end)
-                   : launch_mfma<BF16, 64, true>(p, a, row, batch, c.n_q_heads, s, k_start, k_end);
+      return hd128 ? launch_mfma<BF16, 128, true>(p, a, row, batch, c.n_q_heads, s, k_start, k_end, done)
+                   : launch_mfma<BF16, 64, true>(p, a, row, batch, c.n_q_heads, s, k_start, k_end, done);
     default: return PIE_EINVAL;
   }
 }

@@ -897,19 +897,19 @@ int pie_step(pie_pool* p, const void* d_q_all, const void* d_k_new, const void* 
     // for and sent once, at the start of the step)
     if (n_prefetch > 0 && (rc = wait_if(cs, p->ev_in[l & 1], p->ev_in_rec[l & 1]))) return rc;
     if (timed) PIE_HIP(hipEventRecord(p->lev[l].attn_start, cs));
+    // The next user of this layer's staging region (layer l + 2's prefetch, this layer's write-back) waits
+    // for the event that completes with the layer's last kernel.
+    const bool standin = p->layer_compute_us > 0.f;
+    hipEvent_t read_done = n_prefetch > 0 ? p->ev_read[l & 1] : nullptr;
     if ((rc = launch_attn_decode(p, l, (const char*)d_q_all + l * q_stride, max_blocks, d_ctx_lens, batch,
                                  (char*)d_out_all + l * q_stride, cs, timed ? p->lev[l].k_start : nullptr,
-                                 timed ? p->lev[l].k_end : nullptr, -1, clock_row(l))))
+                                 timed ? p->lev[l].k_end : nullptr, -1, clock_row(l), nullptr,
+                                 standin ? nullptr : read_done)))
       return rc;
-    if (p->layer_compute_us > 0.f &&
-        (rc = launch_busy(p->layer_compute_us, p->wall_clock_khz, cs, clock_row(l))))
+    if (standin && (rc = launch_busy(p->layer_compute_us, p->wall_clock_khz, cs, clock_row(l), read_done)))
       return rc;
     if (timed) PIE_HIP(hipEventRecord(p->lev[l].attn_end, cs));
-    if (n_prefetch > 0) {
-      // the next user of this staging region (layer l + 2's prefetch, this layer's write-back) waits for it
-      PIE_HIP(hipEventRecord(p->ev_read[l & 1], cs));
-      p->ev_read_rec[l & 1] = true;
-    }
+    if (n_prefetch > 0) p->ev_read_rec[l & 1] = true;
     if (l + 1 < L && n_prefetch > 0) {
       // The next layer's prefetch goes into the region layer l - 1 used, so it starts when that layer ends
       // and runs behind this one.  It is enqueued after this layer's kernels because a copy-engine
