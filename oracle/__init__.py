@@ -23,6 +23,9 @@ Pinned by (see tests/test_oracle_*.py):
       number of CPU layers its timing hides.
   layout.element_index              - bijection, vector contents, hand-worked
       positions.
+  chunk_book.ChunkBook              - the worked example's 9/7 per layer with two
+      of nine layers away, growth visible exactly when the second has left, a
+      refused and a granted shrink, conservation under random histories.
   serving_sim.simulate              - a hand-worked three-request stream
       (tests/test_serving_host.py); the scheduling rules themselves are this
       build's reading of an engine the paper inherits: parity unpinned beyond
