@@ -265,6 +265,12 @@ int pie_prefetch_list(pie_pool* pool, const int32_t* h_block_table, int32_t max_
  * host pool's memory directly between two steps must turn it off or call pie_swap_in for layer 0 afterwards. */
 int pie_set_cross_step_prefetch(pie_pool* pool, int32_t on);
 
+/* On the copy-engine path pie_step already paces the host with the GPU; it then also looks for a layer's
+ * swap-in from the host (polling its event while the layer before computes, until shortly before that ends)
+ * and queues the layer without a wait on the compute stream when it has seen the swap-in complete.  On by
+ * default; 0 makes pie_step always wait on the stream (no polling on the host). */
+int pie_set_host_presence_check(pie_pool* pool, int32_t on);
+
 /* How pie_step monitors itself (the per-layer times the adaptive expansion needs, Section 3.4.2).
  *   PIE_TIMING_OFF    nothing is measured (default).
  *   PIE_TIMING_EVENTS HIP events around every piece of work.  Exact for every stream, but an event between

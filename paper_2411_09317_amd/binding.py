@@ -30,7 +30,7 @@ SYMBOLS = [
     "pie_migrate", "pie_set_host_fraction", "pie_set_swap_path", "pie_set_attn_partition", "pie_set_swap_workgroups",
     "pie_set_layer_compute_us",
     "pie_kv_append", "pie_attn_decode", "pie_attn_stream_probe_sync",
-    "pie_step", "pie_prefetch_list", "pie_set_timing", "pie_set_cross_step_prefetch", "pie_pool_sync", "pie_get_stats", "pie_get_layer_times",
+    "pie_step", "pie_prefetch_list", "pie_set_timing", "pie_set_cross_step_prefetch", "pie_set_host_presence_check", "pie_pool_sync", "pie_get_stats", "pie_get_layer_times",
     "pie_check_errors_sync", "pie_controller_create", "pie_controller_destroy", "pie_controller_config",
     "pie_controller_observe", "pie_controller_level", "pie_controller_update", "pie_last_hip_error", "pie_strerror",
     "pie_version",
@@ -280,6 +280,9 @@ class Pool:
     # ---- control ---------------------------------------------------------------------------
     def set_cross_step_prefetch(self, on: bool):
         _check(_lib.pie_set_cross_step_prefetch(self._h, C.c_int32(1 if on else 0)), "set_cross_step_prefetch")
+
+    def set_host_presence_check(self, on: bool):
+        _check(_lib.pie_set_host_presence_check(self._h, C.c_int32(1 if on else 0)), "set_host_presence_check")
 
     def set_timing(self, mode):
         """False / TIMING_OFF, True / TIMING_EVENTS, or TIMING_CLOCK (kernels note their own times)."""

@@ -141,6 +141,8 @@ struct pie_pool {
   std::vector<pie::LayerEvents> lev;
   hipEvent_t ev_step_start = nullptr;
   int32_t step_timed = 0;         // the timing mode the last step ran with
+  bool in_on_host[2] = {false, false};   // the region's last swap-in was ordered on the host (copy-engine path)
+  bool presence_poll = true;             // look for a swap-in's completion from the host before waiting on the stream
   // the first layer's blocks staged ahead, behind the previous step's last layer
   bool cross_step_prefetch = true;
   bool pre_valid = false;         // region 0 holds layer 0's blocks of stage_list[0], nothing has changed since

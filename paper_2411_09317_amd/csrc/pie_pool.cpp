@@ -5,6 +5,7 @@
 // behind the current layer), Section 4.1 (block manager, base pointer + offset addressing).
 
 #include <algorithm>
+#include <chrono>
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
@@ -283,6 +284,7 @@ static int swap_in_impl(pie_pool* p, int32_t layer, int32_t n, const int32_t* ha
   // (also when the copy itself is skipped: a wait enqueued on this stream would make the copy-engine
   // transfers that follow on it block the host)
   const bool on_host = n > 0 && cp.path == PIE_SWAP_DMA;
+  p->in_on_host[r] = on_host;
   // the region may still be read by compute or written back
   int rc;
   if ((rc = order_after(s, p->ev_read[r], p->ev_read_rec[r], on_host))) return rc;
@@ -892,10 +894,31 @@ int pie_step(pie_pool* p, const void* d_q_all, const void* d_k_new, const void* 
       return rc;
     p->lev[0].in_used = (timed || clocked) && !pre_hit;
   }
+  // When the host itself orders the copies (copy-engine path) it passes, once per layer, the moment the
+  // previous layer's computation has ended; from two of those it knows how long a layer takes.
+  auto now_us = [] {
+    return std::chrono::duration<double, std::micro>(std::chrono::steady_clock::now().time_since_epoch()).count();
+  };
+  double t_free = -1.0, layer_us = -1.0;
   for (int32_t l = 0; l < L; ++l) {
-    // the presence check: the layer's staged blocks have arrived (migrations and map updates were waited
-    // for and sent once, at the start of the step)
-    if (n_prefetch > 0 && (rc = wait_if(cs, p->ev_in[l & 1], p->ev_in_rec[l & 1]))) return rc;
+    // The presence check: the layer's staged blocks have arrived (migrations and map updates were waited
+    // for and sent once, at the start of the step).  A wait on the compute stream costs about 8 us even when
+    // the event has long completed, so the host first looks for itself: the layer before is still computing,
+    // and until shortly before it ends (this layer's kernels must be queued by then) the host polls the
+    // swap-in's event.  A swap-in the host has seen complete needs no wait on the stream.
+    if (n_prefetch > 0 && p->ev_in_rec[l & 1]) {
+      bool arrived = false;
+      if (p->presence_poll && p->in_on_host[l & 1] && layer_us > 0.0) {
+        const double deadline = t_free + layer_us - (50.0 + 0.1 * layer_us);
+        for (;;) {
+          const hipError_t e = hipEventQuery(p->ev_in[l & 1]);
+          if (e == hipSuccess) { arrived = true; break; }
+          (void)hipGetLastError();
+          if (e != hipErrorNotReady || now_us() >= deadline) break;
+        }
+      }
+      if (!arrived && (rc = wait_if(cs, p->ev_in[l & 1], true))) return rc;
+    }
     if (timed) PIE_HIP(hipEventRecord(p->lev[l].attn_start, cs));
     // The next user of this layer's staging region (layer l + 2's prefetch, this layer's write-back) waits
     // for the event that completes with the layer's last kernel.
@@ -920,6 +943,11 @@ int pie_step(pie_pool* p, const void* d_q_all, const void* d_k_new, const void* 
                              mark(p->lev[l + 1].in_end, l + 1, kClockInEnd), job_for(l + 1))))
         return rc;
       p->lev[l + 1].in_used = timed || clocked;
+      if (p->in_on_host[(l + 1) & 1]) {            // the host has just waited for layer l - 1 to end
+        const double t = now_us();
+        if (t_free >= 0.0) layer_us = t - t_free;
+        t_free = t;
+      }
     }
     if (n_dirty > 0 && d_k_new) {
       if ((rc = swap_out_impl(p, l, n_dirty, h_dirty, os, mark(p->lev[l].out_start, l, kClockOutStart),
@@ -952,6 +980,12 @@ int pie_set_cross_step_prefetch(pie_pool* p, int32_t on) {
   if (!p) return PIE_EINVAL;
   p->cross_step_prefetch = on != 0;
   if (!on) p->pre_valid = false;
+  return PIE_OK;
+}
+
+int pie_set_host_presence_check(pie_pool* p, int32_t on) {
+  if (!p) return PIE_EINVAL;
+  p->presence_poll = on != 0;
   return PIE_OK;
 }
 
