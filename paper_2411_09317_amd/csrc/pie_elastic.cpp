@@ -293,7 +293,6 @@ int pie_elastic_create(pie_pool* pool, int32_t chunk_blocks, int32_t max_chunks_
   if (pool->d_layer_stride != (size_t)c.n_gpu_blocks * pool->block_bytes) return PIE_EINVAL;
   const int32_t k0 = c.n_gpu_blocks / chunk_blocks;
   if (max_chunks_per_layer < k0 || max_chunks_per_layer > pie::kMaxLayerChunks) return PIE_EINVAL;
-  if ((int64_t)max_chunks_per_layer * chunk_blocks > (int64_t)c.max_blocks_per_seq * c.max_batch) {}   // tables bound it anyway
   size_t need_d = 0, need_h = 0;
   pie_elastic_bytes_required(pool, chunk_blocks, max_chunks_per_layer, n_host_slots, &need_d, &need_h);
   if (!d_work || d_bytes < need_d || (uintptr_t)d_work % 16) return PIE_ENOMEM;
