@@ -183,7 +183,9 @@ def adaptive_leg(w, dw, streams, n_steps, units, k_max):
     fraction one level at a time.  The throughput signal is tokens/s x expansion: a larger effective cache
     admits a proportionally larger batch (the premise of the method); the batch itself is fixed here."""
     from paper_2411_09317_amd import binding as B
-    ctl = B.Controller(units, k_max)
+    # a level must bring at least half the capacity it adds to count as scaling (with levels finer than 1 % the
+    # default threshold of 1 % could never be met)
+    ctl = B.Controller(units, k_max, plateau_eps=min(0.01, 0.5 / units))
     dw.pool.set_host_fraction(0.0, dw.order, streams[1])
     dw.pool.sync()
     none = np.zeros(0, dtype=np.int32)
