@@ -73,6 +73,9 @@ def parse():
                          "grow; --serve-levels are then numbers of layers kept in CPU memory, --serve-gpu-blocks a "
                          "layer's cache while everything is on the GPU")
     ap.add_argument("--serve-chunk-blocks", type=int, default=256)
+    ap.add_argument("--serve-rates", default="", help="with --serve-elastic: also serve at these request rates, given as "
+                    "shares of the rate the first level sustains when saturated (e.g. 0.7,1.0,1.15), at the first and "
+                    "at the last of --serve-levels")
     ap.add_argument("--serve-gpu-blocks", type=int, default=16384)
     ap.add_argument("--serve-levels", default="0,1,2,4,8", help="budget levels; one level = 1/64 of the GPU pool")
     ap.add_argument("--serve-load", type=float, default=0.8,
@@ -410,23 +413,25 @@ def serving_elastic_mode(args):
     if args.t_other_us:
         inner.set_layer_compute_us(args.t_other_us)
 
-    def stream():
-        a, p, o = I.draw_requests(w, args.serve, 1e9, out_lo, out_hi)
+    def stream(rate):
+        a, p, o = I.draw_requests(w, args.serve, rate, out_lo, out_hi)
         return [S.Request(i, float(a[i]), int(p[i]), int(o[i])) for i in range(args.serve)]
 
-    def run(m, adaptive=False):
+    def run(m, adaptive=False, rate=1e9):
         ep = B.ElasticPool(inner, C, k_cap, m_max + 2)
         ctl = B.Controller(n, m_max, k_up=8, k_down=2, probe_period=256) if adaptive else None
         t0 = time.perf_counter()
-        r = S.serve_elastic(ep, w, stream(), max_batch, max_blocks, controller=ctl, layers_on_cpu=m,
+        r = S.serve_elastic(ep, w, stream(rate), max_batch, max_blocks, controller=ctl, layers_on_cpu=m,
                             progress=lambda it, now, done: print(f"#   iteration {it}: {done} requests done, {now:.1f} s",
                                                                  file=sys.stderr, flush=True))
         r["wall_s"] = round(time.perf_counter() - t0, 2)
         r["mode"] = "adaptive" if adaptive else f"{m} layers on the CPU"
+        r["requests_per_s_offered"] = rate if rate < 1e8 else None
         if ctl:
             ctl.close()
         ep.close()
-        print(f"# serve elastic {r['mode']}: {r['tokens_per_s']:.0f} tok/s, batch {r['mean_batch']:.1f}, "
+        print(f"# serve elastic {r['mode']} at {rate:.3g} req/s: {r['tokens_per_s']:.0f} tok/s, batch {r['mean_batch']:.1f}, "
+              f"latency {r['latency_s_mean']:.1f} s (queue {r['queue_s_mean']:.1f}), "
               f"{r['ms_per_iteration']:.2f} ms/iter, blocks per layer {r['blocks_per_layer_mean']:.0f}, "
               f"waits {r['host_wait_ms']:.0f} ms", file=sys.stderr, flush=True)
         return r
@@ -437,6 +442,13 @@ def serving_elastic_mode(args):
            "requests": args.serve, "prompt": f"{w.ctx_dist} [{w.ctx_lo},{w.ctx_hi}]", "output": f"uniform [{out_lo},{out_hi}]",
            "t_other_us": args.t_other_us, "data": "synthetic"}
     res["saturated"] = [run(m) for m in ms] + [run(0, adaptive=True)]
+    if args.serve_rates:
+        # offered load as a share of what the caches at their base size sustain: both sizes at every rate
+        base = res["saturated"][0]
+        full = base["requests"] / base["makespan_s"]
+        res["by_rate"] = [{"share_of_base_rate": x, "requests_per_s": x * full,
+                           "base": run(ms[0], rate=x * full), "expanded": run(ms[-1], rate=x * full)}
+                          for x in [float(v) for v in args.serve_rates.split(",")]]
     inner.close()
     print(json.dumps(res))
 
