@@ -381,7 +381,8 @@ def serve_elastic(elastic, w, requests: List[Request], max_batch: int, max_block
     while not sched.idle:
         vis, tgt, m = elastic.capacity()
         if want != m:
-            if elastic.set_layers_on_cpu(want, store.live_end(), cs):
+            # what must fit below a smaller size: the live blocks, and the blocks promised to running requests
+            if elastic.set_layers_on_cpu(want, max(store.live_end(), sched.reserved), cs):
                 vis, tgt, m = elastic.capacity()
             else:
                 refused += 1

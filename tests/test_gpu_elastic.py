@@ -287,11 +287,12 @@ def test_serving_on_growing_and_shrinking_caches_matches_an_all_resident_pool():
             want = plan.get(it, want)
             vis, tgt, m = ep.capacity()
             if want != m:
-                if ep.set_layers_on_cpu(want, store.live_end(), cs):
+                if ep.set_layers_on_cpu(want, max(store.live_end(), sched.reserved), cs):
                     vis, tgt, m = ep.capacity()
                 else:
                     refused += 1
             store.limit = max(store.limit, vis) if want < m else vis
+            assert sched.reserved <= store.limit
             sched.admit(1.0)
             assert sched.running
             table, ctx = sched.tables()
