@@ -489,6 +489,13 @@ int pie_elastic_set_layers_on_cpu(pie_elastic_pool* ep, int32_t m, int32_t block
 /* Tells the pool the highest live block index + 1 (-1: unknown, the default): a layer that leaves the GPU
  * takes along only the chunks below it.  Blocks above must hold nothing that is still needed. */
 int pie_elastic_set_live_blocks(pie_elastic_pool* ep, int32_t blocks_in_use_end);
+/* Between steps: copies block src[i] of a layer's cache to block dst[i], in every layer, wherever the layer is
+ * (on the GPU by a kernel on compute_stream, in CPU memory inside its image).  For a scheduler that wants
+ * live blocks out of the part of the caches a shrink will take away.  Each block moves once, targets are not
+ * themselves moved, and every resident layer must hold both ends (PIE_ESTATE otherwise).  Completes the
+ * moves in flight first.  The caller updates its block tables. */
+int pie_elastic_move_blocks(pie_elastic_pool* ep, int32_t n, const int32_t* src, const int32_t* dst,
+                            void* compute_stream);
 /* Blocks per layer a scheduler may use now, what they will be when the reallocation is complete, and m. */
 int pie_elastic_capacity(pie_elastic_pool* ep, int32_t* out_visible_blocks, int32_t* out_target_blocks,
                          int32_t* out_layers_on_cpu);

@@ -41,7 +41,7 @@ SYMBOLS = [
     "pie_chunk_book_create", "pie_chunk_book_destroy", "pie_chunk_book_set_layers_on_cpu", "pie_chunk_book_left_gpu",
     "pie_chunk_book_enters_gpu", "pie_chunk_book_layer", "pie_chunk_book_capacity",
     "pie_elastic_bytes_required", "pie_elastic_create", "pie_elastic_destroy", "pie_elastic_set_layers_on_cpu",
-    "pie_elastic_capacity", "pie_elastic_set_live_blocks", "pie_elastic_step", "pie_elastic_settle_sync", "pie_elastic_layer", "pie_elastic_table",
+    "pie_elastic_capacity", "pie_elastic_set_live_blocks", "pie_elastic_move_blocks", "pie_elastic_step", "pie_elastic_settle_sync", "pie_elastic_layer", "pie_elastic_table",
     "pie_elastic_stats",
 ]
 
@@ -558,6 +558,16 @@ class ElasticPool:
             return False
         _check(rc, "elastic_set_layers_on_cpu")
         return True
+
+    def blocks_for(self, m: int) -> int:
+        """Blocks per layer when m layers are kept in CPU memory and the reallocation is complete."""
+        n_chunks = self.n_layers * (self.pool.cfg.n_gpu_blocks // self.C)
+        return min(self.k_cap, n_chunks // (self.n_layers - m)) * self.C
+
+    def move_blocks(self, src: Sequence[int], dst: Sequence[int], compute_stream=None):
+        a, b = _i32(src), _i32(dst)
+        _check(_lib.pie_elastic_move_blocks(self._h, C.c_int32(len(a)), _ptr(a), _ptr(b), _stream_ptr(compute_stream)),
+               "elastic_move_blocks")
 
     def set_live_blocks(self, blocks_in_use_end: int):
         _check(_lib.pie_elastic_set_live_blocks(self._h, C.c_int32(blocks_in_use_end)), "elastic_set_live_blocks")

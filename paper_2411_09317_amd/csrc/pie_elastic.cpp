@@ -388,6 +388,57 @@ int pie_elastic_set_live_blocks(pie_elastic_pool* lp, int32_t blocks_in_use_end)
   return PIE_OK;
 }
 
+int pie_elastic_move_blocks(pie_elastic_pool* lp, int32_t n, const int32_t* src, const int32_t* dst,
+                            void* compute_stream) {
+  if (!lp || n < 0 || (n > 0 && (!src || !dst))) return PIE_EINVAL;
+  if (n == 0) return PIE_OK;
+  std::vector<uint8_t> is_src(lp->H, 0), is_dst(lp->H, 0);
+  for (int32_t i = 0; i < n; ++i) {
+    if (src[i] < 0 || src[i] >= lp->H || dst[i] < 0 || dst[i] >= lp->H) return PIE_EINVAL;
+    if (is_src[src[i]] || is_dst[dst[i]]) return PIE_EINVAL;        // each block moves once, to a place of its own
+    is_src[src[i]] = is_dst[dst[i]] = 1;
+  }
+  for (int32_t i = 0; i < n; ++i)
+    if (is_src[dst[i]]) return PIE_EINVAL;                           // no chains: a target is not itself moved
+  hipStream_t cs = (hipStream_t)compute_stream;
+  int rc = pie_elastic_settle_sync(lp, compute_stream);
+  if (rc) return rc;
+  pie_chunk_book* b = lp->book;
+  for (int32_t j = 0; j < lp->n; ++j)                                // every resident layer must have the targets
+    if (b->resident[j])
+      for (int32_t i = 0; i < n; ++i)
+        if (dst[i] / lp->C >= (int32_t)b->chunks[j].size() || src[i] / lp->C >= (int32_t)b->chunks[j].size())
+          return PIE_ESTATE;
+  const size_t bb = lp->pool->block_bytes;
+  for (int32_t j = 0; j < lp->n; ++j) {
+    if (b->resident[j]) {
+      const std::vector<int32_t>& c = b->chunks[j];
+      auto slot = [&](int32_t h) { return c[h / lp->C] * lp->C + h % lp->C; };
+      pie::SwapPairs pairs;
+      for (int32_t i = 0; i < n;) {
+        pairs.n = 0;
+        for (; i < n && pairs.n < pie::kSwapPairs; ++i) {
+          pairs.src[pairs.n] = slot(src[i]);
+          pairs.dst[pairs.n] = slot(dst[i]);
+          ++pairs.n;
+        }
+        if ((rc = pie::launch_swap_copy(lp->pool->d_kv, lp->pool->d_kv, bb, pairs, 32, cs))) return rc;
+      }
+      PIE_HIP(hipEventRecord(lp->ev_layer[j], cs));                  // a later swap-out of the layer waits for this
+      lp->ev_layer_rec[j] = 1;
+    } else {
+      // in CPU memory: inside its image; a source beyond what it carries holds nothing for this layer yet
+      char* img = slot_host(lp, lp->sched->table[j].host_slot);
+      for (int32_t i = 0; i < n; ++i) {
+        if (src[i] / lp->C >= b->image[j]) continue;
+        std::memcpy(img + (size_t)dst[i] * bb, img + (size_t)src[i] * bb, bb);
+        b->image[j] = std::max(b->image[j], dst[i] / lp->C + 1);
+      }
+    }
+  }
+  return PIE_OK;
+}
+
 int pie_elastic_capacity(pie_elastic_pool* lp, int32_t* out_visible_blocks, int32_t* out_target_blocks,
                          int32_t* out_layers_on_cpu) {
   if (!lp) return PIE_EINVAL;

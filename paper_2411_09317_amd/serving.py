@@ -152,6 +152,15 @@ class Scheduler:
         self.n_promoted += n
         return n
 
+    def relocate(self, src, dst):
+        """The blocks src[i] now live at dst[i] (someone has moved the bytes): tables follow."""
+        to = dict(zip(src, dst))
+        for r in self.running:
+            if any(h in to for h in r.handles):
+                r.handles = [to.get(h, h) for h in r.handles]
+                r.row[:len(r.handles)] = r.handles
+        self.store.relocate(src, dst)
+
     @property
     def blocks_in_use(self) -> int:
         return sum(len(r.handles) for r in self.running)
@@ -340,6 +349,17 @@ class IndexStore:
     def block_where(self, handles):
         return [GPU] * len(handles), list(handles)
 
+    def plan_compaction(self, below: int):
+        """Live indices at or above `below` paired with the lowest free indices under it; None if they do not
+        all fit."""
+        src = np.flatnonzero(self.used[below:]) + below
+        dst = np.flatnonzero(~self.used[:below])[: len(src)]
+        return (src.tolist(), dst.tolist()) if len(dst) == len(src) else None
+
+    def relocate(self, src, dst):
+        self.used[np.asarray(src, dtype=np.int64)] = False
+        self.used[np.asarray(dst, dtype=np.int64)] = True
+
     def live_end(self) -> int:
         nz = np.flatnonzero(self.used)
         return int(nz[-1]) + 1 if len(nz) else 0
@@ -377,11 +397,19 @@ def serve_elastic(elastic, w, requests: List[Request], max_batch: int, max_block
         sched.submit(r)
     cs = loop.streams[0]
     want = layers_on_cpu
-    now, iters, batch_sum, busy, levels, sizes, recent, prev_stall, refused = 0.0, 0, 0, 0.0, [], [], [], 0.0, 0
+    now, iters, batch_sum, busy, levels, sizes, recent, prev_stall, refused, moved = 0.0, 0, 0, 0.0, [], [], [], 0.0, 0, 0
     while not sched.idle:
         vis, tgt, m = elastic.capacity()
         if want != m:
-            # what must fit below a smaller size: the live blocks, and the blocks promised to running requests
+            # what must fit below a smaller size: the live blocks, and the blocks promised to running requests;
+            # live blocks scattered above it are moved down first if the promise already fits
+            below = elastic.blocks_for(want)
+            if want < m and sched.reserved <= below < store.live_end():
+                plan = store.plan_compaction(below)
+                if plan and plan[0]:
+                    elastic.move_blocks(plan[0], plan[1], cs)
+                    sched.relocate(*plan)
+                    moved += len(plan[0])
             if elastic.set_layers_on_cpu(want, max(store.live_end(), sched.reserved), cs):
                 vis, tgt, m = elastic.capacity()
             else:
@@ -422,6 +450,6 @@ def serve_elastic(elastic, w, requests: List[Request], max_batch: int, max_block
                 "layers_on_cpu_max": int(max(levels)) if levels else 0,
                 "blocks_per_layer_mean": float(np.mean(sizes)) if sizes else 0.0,
                 "blocks_per_layer_max": int(max(sizes)) if sizes else 0, "blocks_per_layer_base": base,
-                "shrinks_refused": refused, "swap_ins": int(st.n_swap_in), "swap_outs": int(st.n_swap_out),
+                "shrinks_refused": refused, "blocks_moved_down": moved, "swap_ins": int(st.n_swap_in), "swap_outs": int(st.n_swap_out),
                 "forced_ins": int(st.n_forced_in), "host_wait_ms": float(st.stall_ms)})
     return res

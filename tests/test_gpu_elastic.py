@@ -280,19 +280,41 @@ def test_serving_on_growing_and_shrinking_caches_matches_an_all_resident_pool():
         sched.submit(S.Request(i, float(a[i]), 0, int(o[i])))
     none = np.zeros(0, dtype=np.int32)
     plan = {5: 2, 50: 3, 90: 1, 130: 0}                               # iteration -> layers asked to be on the CPU
-    want, it, sizes, above, refused = 0, 0, [], 0, 0
+    want, it, sizes, above, refused, moved, on_cpu_at_move = 0, 0, [], 0, 0, 0, []
     cs = loop.streams[0]
     try:
         while not sched.idle:
             want = plan.get(it, want)
             vis, tgt, m = ep.capacity()
             if want != m:
+                below = ep.blocks_for(want)
+                if want < m and sched.reserved <= below < store.live_end():
+                    mv = store.plan_compaction(below)                # live blocks above the smaller size move down
+                    if mv and mv[0]:
+                        ep.move_blocks(mv[0], mv[1], cs)
+                        ref.sync()
+                        ref.gpu_image()[:, mv[1]] = ref.gpu_image()[:, mv[0]]
+                        sched.relocate(*mv)
+                        moved += len(mv[0])
                 if ep.set_layers_on_cpu(want, max(store.live_end(), sched.reserved), cs):
                     vis, tgt, m = ep.capacity()
                 else:
                     refused += 1
             store.limit = max(store.limit, vis) if want < m else vis
             assert sched.reserved <= store.limit
+            if it in (70, 75, 110):                                  # and a few times just so: the highest live
+                live = np.flatnonzero(store.used)                    # blocks go to the lowest free places, with
+                free = np.flatnonzero(~store.used[: store.limit])    # layers on the GPU and in CPU memory
+                k = min(4, len(live), len(free))
+                src, dst = live[-k:][live[-k:] > free[k - 1]].tolist(), free[:k].tolist()
+                dst = dst[: len(src)]
+                if src:
+                    ep.move_blocks(src, dst, cs)
+                    ref.sync()
+                    ref.gpu_image()[:, dst] = ref.gpu_image()[:, src]
+                    sched.relocate(src, dst)
+                    moved += len(src)
+                    on_cpu_at_move.append(sum(1 for st_, _, _ in ep.table() if st_ == B.LAYER_HOST))
             sched.admit(1.0)
             assert sched.running
             table, ctx = sched.tables()
@@ -313,6 +335,7 @@ def test_serving_on_growing_and_shrinking_caches_matches_an_all_resident_pool():
         assert inner.check_errors() == 0 and ref.check_errors() == 0
         assert len(sched.done) == 60 and not store.used.any()
         assert max(sizes) >= 9 * C > k0 * C and above > 10          # requests lived in blocks the small caches lack
+        assert moved > 0 and max(on_cpu_at_move) >= 1              # blocks were moved, in both kinds of memory
         assert it > 130 or want == plan[max(k for k in plan if k <= it)]
     finally:
         ep.close()

@@ -282,3 +282,27 @@ def test_scheduler_over_an_index_store_follows_a_capacity_that_moves():
         it += 1
     assert len(sc.done) == 120 and not st.used.any()
     assert max(peak[:20]) <= 24 < max(peak[20:60]) <= 40 and st.limit == 24 and max(peak[-5:]) <= 24
+
+
+def test_compaction_plan_and_relocation():
+    st = S.IndexStore(32, 32)
+    class Shown:
+        capacity = 32
+        expansion = 1.0
+    sc = S.Scheduler(st, T, Shown(), 8, 8)
+    for i, (p, o) in enumerate([(40, 20), (60, 30), (30, 10)]):
+        sc.submit(S.Request(i, 0.0, p, o))
+    sc.admit(0.0)
+    assert [r.handles for r in sc.running] == [[0, 1, 2], [3, 4, 5, 6], [7, 8]]
+    st.block_free([1, 2])
+    sc.running[0].handles = [0, 20, 21]                              # as if two of its blocks had been given high indices
+    st.used[[20, 21]] = True
+    sc.running[0].row[:3] = [0, 20, 21]
+    assert st.live_end() == 22 and st.plan_compaction(4) is None     # five live blocks below 4 cannot be
+    src, dst = st.plan_compaction(12)
+    assert (src, dst) == ([20, 21], [1, 2])
+    sc.relocate(src, dst)
+    assert sc.running[0].handles == [0, 1, 2] and sc.running[0].row[:4].tolist() == [0, 1, 2, -1]
+    assert st.live_end() == 9 and int(st.used.sum()) == 9 and sc.blocks_in_use == 9
+    table, ctx = sc.tables()
+    assert table[0, :3].tolist() == [0, 1, 2] and table[1, :4].tolist() == [3, 4, 5, 6]
