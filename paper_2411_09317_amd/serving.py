@@ -435,8 +435,10 @@ def serve_elastic(elastic, w, requests: List[Request], max_batch: int, max_block
             recent.append((B, dt))
             del recent[:-8]
             tc = (dt * 1e3 - stall) / n
+            # tokens/s per promised block x the blocks the level leads to: what the level will give once the
+            # scheduler has filled it, without waiting for the admissions to catch up
             rate = sum(b for b, _ in recent) / sum(t for _, t in recent)
-            want = controller.observe([tc] * n, [0.0] * n, [stall / n] * n, 0.0, rate * tgt / max(vis, 1))
+            want = controller.observe([tc] * n, [0.0] * n, [stall / n] * n, 0.0, rate * tgt / max(sched.reserved, 1))
         sched.complete_iteration(now)
         if progress and iters % 500 == 0:
             progress(iters, now, len(sched.done))
