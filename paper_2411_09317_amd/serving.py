@@ -299,7 +299,9 @@ def serve(pool, w, requests: List[Request], budget: BlockBudget, max_batch: int,
         if controller is not None:
             recent.append((B, dt))                 # tokens/s over the last few iterations: single ones are noisy
             del recent[:-8]
-            f = controller.update_from_pool(pool, sum(b for b, _ in recent) / sum(t for _, t in recent))
+            rate = sum(b for b, _ in recent) / sum(t for _, t in recent)
+            # per promised block x the blocks the level allows: what it gives once the scheduler has filled it
+            f = controller.update_from_pool(pool, rate * budget.capacity / max(sched.reserved, 1))
             budget.set_level(min(budget.k_max, int(round(f * controller.units))))
             levels.append(budget.level)
         sched.complete_iteration(now)
