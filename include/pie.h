@@ -93,7 +93,8 @@ typedef struct {
   float   softmax_scale;     /* 0 => 1/sqrt(head_dim) */
 } pie_config;
 
-/* Filled by pie_get_stats; times in milliseconds, from HIP events of the last pie_step. */
+/* Filled by pie_get_stats; times in milliseconds, from the last pie_step's monitoring (pie_set_timing: HIP
+ * events or the device clock). */
 typedef struct {
   int32_t n_layers;
   int32_t host_blocks_in_use;   /* handles currently homed on the host */
