@@ -382,3 +382,53 @@ def test_device_clock_with_the_fp32_kernel():
         assert st.step_ms >= lt["attn"].sum() * 0.99 and st.step_ms < 50.0
     assert lib.check_errors() == 0
     lib.close()
+
+
+def test_block_addresses_point_into_the_callers_buffers():
+    """pie_block_address names the bytes of (pool, layer, slot) inside the memory the caller handed over: writing a
+    block through that address and reading it through the pool's image gives the same bytes."""
+    case = I.make_case(I.scaled(W, n_layers=3))
+    n = int(case.n_blocks.sum())
+    lib, mod, table = GH.make_pools(case, n, 4, n, upto_ctx=case.ctx_lens - 1)
+    g, h = lib.gpu_image(), lib.host_image()
+    for layer, slot in ((0, 0), (2, n - 1), (1, n + 3), (1, n + 2 * 4 - 1)):      # resident and staging slots
+        assert lib.block_address(B.GPU, layer, slot) == g[layer, slot].data_ptr()
+    for layer, slot in ((0, 0), (2, n - 1)):
+        assert lib.block_address(B.HOST, layer, slot) == h[layer, slot].data_ptr()
+    for where, layer, slot in ((B.GPU, 3, 0), (B.GPU, 0, n + 8), (B.HOST, 0, n), (2, 0, 0),
+                               (B.GPU, -1, 0), (B.HOST, 0, -1)):
+        with pytest.raises(B.PieError) as e:
+            lib.block_address(where, layer, slot)
+        assert e.value.code == B.EINVAL
+    lib.close()
+
+
+def test_gather_workgroups_and_host_presence_check_change_no_result():
+    """Two knobs of the swap path that must not show in any byte: how many workgroups the gather kernel uses
+    (bounds checked), and whether the host looks for a layer's swap-in itself before queuing the layer."""
+    w = I.scaled(W, n_layers=4)
+    case = host_tails(I.make_case(w))
+    n = int(case.n_blocks.sum())
+    streams = (torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream())
+    outs, images = [], []
+    for path, wgs, check in ((B.SWAP_KERNEL, 64, True), (B.SWAP_KERNEL, 1, True), (B.SWAP_KERNEL, 7, True),
+                             (B.SWAP_KERNEL, 1024, True), (B.SWAP_DMA, 64, True), (B.SWAP_DMA, 64, False)):
+        lib, mod, table = GH.make_pools(case, n, n, n, upto_ctx=case.ctx_lens - 1)
+        lib.set_swap_path(path)
+        lib.set_swap_workgroups(wgs)
+        lib.set_host_presence_check(check)
+        for _ in range(2):                                                    # the second step finds layer 0 staged
+            got, pf, dirty = run_step(lib, case, table, streams)
+        assert lib.check_errors() == 0 and len(pf) > 0 and len(dirty) > 0
+        outs.append(got)
+        images.append(GH.images_of(lib)[1].copy())
+        for bad in (0, -3, 1025):
+            with pytest.raises(B.PieError) as e:
+                lib.set_swap_workgroups(bad)
+            assert e.value.code == B.EINVAL
+        lib.close()
+    ref = [A.dense_attention(*H.dense_f64(case, l), case.ctx_lens) for l in range(w.n_layers)]
+    for l in range(w.n_layers):
+        assert GH.rowwise_rel_err(outs[0][l], ref[l]) <= 2e-3
+    for got, img in zip(outs[1:], images[1:]):
+        assert np.array_equal(got, outs[0]) and np.array_equal(img, images[0])
