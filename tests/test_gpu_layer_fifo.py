@@ -14,7 +14,6 @@ import torch
 import gpu_helpers as GH
 from oracle import attention as A
 from oracle import layout as LY
-from oracle import numfmt
 from paper_2411_09317_amd import binding as B
 from paper_2411_09317_amd import inputs as I
 

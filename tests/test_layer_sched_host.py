@@ -1,6 +1,5 @@
 """The library's layer-granular swapping control (pure host logic) against the oracle's simulation of the
 paper's protocol, decision by decision, under the same timing model (no GPU)."""
-import numpy as np
 import pytest
 
 from oracle import layer_fifo as LF

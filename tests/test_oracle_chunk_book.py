@@ -5,7 +5,7 @@ import os
 import numpy as np
 import pytest
 
-from oracle.chunk_book import BookError, ChunkBook, ENOMEM, ESTATE
+from oracle.chunk_book import BookError, ChunkBook, ESTATE
 
 G = {}
 for line in open(os.path.join(os.path.dirname(__file__), "golden", "worked_example.txt")):

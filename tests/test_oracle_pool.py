@@ -206,7 +206,6 @@ def test_step_matches_dense_oracle_and_writes_back():
     """The pipeline's result is plain attention over the context including the
     appended token, whatever is host-resident; afterwards both homes hold it."""
     from oracle import attention as A
-    from oracle import numfmt
     case = make_case_with_host_tails()
     m = fresh()
     table = H.allocate(m, case, H.plan_allocation(case))
