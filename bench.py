@@ -588,7 +588,15 @@ def main():
                    "context_tokens": int(dw.ctx_lens.sum()), "kv_bytes_per_layer": bytes_layer,
                    "kv_blocks_per_layer": dw.total_blocks, "attn_partition_tokens": args.partition or 512,
                    "t_other_us": args.t_other_us, "layer_weight_bytes": w.layer_weight_bytes,
-                   "build_s": round(t_build, 1)},
+                   "build_s": round(t_build, 1),
+                   # where each part of the named metric ("decode tokens/s & HBM GB/s at X% host-resident KV;
+                   # per-layer latency inflation") is in this line
+                   "metric_parts": {"decode tokens/s": "value (0 % host-resident), swap.tokens_per_s, "
+                                                       "swap_below_knee.tokens_per_s",
+                                    "HBM GB/s": "roofline.achieved",
+                                    "X% host-resident": "swap.host_fraction, swap_below_knee.host_fraction",
+                                    "per-layer latency inflation": "swap.inflation_kernel / inflation_e2e, "
+                                                                   "swap_below_knee.inflation_kernel / inflation_e2e"}},
         "roofline": {"bound": "hbm", "kernel": "k_attn_decode_mfma", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic_from_profile(f"attn_decode_{w.name}_pmc.txt"),
