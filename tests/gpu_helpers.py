@@ -73,3 +73,32 @@ def rowwise_rel_err(got: np.ndarray, ref: np.ndarray) -> float:
     den = np.abs(ref).max(axis=-1)
     den = np.where(den == 0, 1.0, den)
     return float((num / den).max())
+
+
+def copy_engine_us(nbytes: int, pieces: int = 1, both_directions: bool = True, reps: int = 3) -> float:
+    """Microseconds a pinned-memory -> device transfer of nbytes, issued as `pieces` equal copies back to back,
+    takes on this machine (with the same transfers running the other way at the same time, if asked).  Tests that
+    need "a swap takes x layer times" size their stand-in compute from this instead of assuming a link rate."""
+    piece = nbytes // pieces
+    h_in = torch.empty(piece * pieces, dtype=torch.uint8, pin_memory=True)
+    h_out = torch.empty(piece * pieces, dtype=torch.uint8, pin_memory=True)
+    d_in = torch.empty(piece * pieces, dtype=torch.uint8, device=DEV)
+    d_out = torch.empty(piece * pieces, dtype=torch.uint8, device=DEV)
+    s_in, s_out = torch.cuda.Stream(), torch.cuda.Stream()
+    best = float("inf")
+    for rep in range(reps + 1):                          # the first pass through fresh pinned memory is slow
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        with torch.cuda.stream(s_in):
+            e0.record()
+            for i in range(pieces):
+                d_in[i * piece:(i + 1) * piece].copy_(h_in[i * piece:(i + 1) * piece], non_blocking=True)
+            e1.record()
+        if both_directions:
+            with torch.cuda.stream(s_out):
+                for i in range(pieces):
+                    h_out[i * piece:(i + 1) * piece].copy_(d_out[i * piece:(i + 1) * piece], non_blocking=True)
+        torch.cuda.synchronize()
+        if rep:
+            best = min(best, e0.elapsed_time(e1) * 1e3)
+    return best

@@ -45,7 +45,21 @@ def test_controller_grows_while_swaps_stay_hidden_and_gives_back_when_they_do_no
     ctl = B.Controller(UNITS, K_MAX, rho=RHO)
     try:
         dw.pool.set_timing(B.TIMING_CLOCK)
-        dw.pool.set_layer_compute_us(3000.0)
+        # The stand-in is sized from this box's own link: a step at level 1 gives the time one level's blocks
+        # take to come in, and a layer is made long enough to hide about five levels' worth (rho included).
+        dw.pool.set_host_fraction(1 / UNITS, dw.order, streams[1])
+        dw.pool.sync()
+        t_level = []
+        for _ in range(4):                                  # the first passes through fresh pinned memory are slow
+            pf, dirty = dw.pool.prefetch_list(dw.table, dw.ctx_lens)
+            dw.pool.step(dw.q, dw.k_new, dw.v_new, dw.d_table, dw.d_ctx, pf, dirty, dw.out, *streams)
+            dw.pool.sync()
+            t_level.append(float(dw.pool.layer_times()["swap_in"][1:].max()))
+        dw.pool.set_host_fraction(0.0, dw.order, streams[1])
+        dw.pool.sync()
+        layer_us = 5.5 * min(t_level) * 1e3 / RHO
+        assert 20.0 < layer_us < 1.0e5, t_level
+        dw.pool.set_layer_compute_us(layer_us)
         level, trace = drive(dw, ctl, streams, 70, 0)
         levels = [t[0] for t in trace]
         assert levels[0] == 0 and level >= 2, levels

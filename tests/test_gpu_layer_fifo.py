@@ -136,8 +136,8 @@ def test_worked_example_schedule_on_hardware():
     d_ctx = torch.from_numpy(case.ctx_lens).to(GH.DEV)
     out = torch.empty_like(q)
     try:
-        layer_mb = lp.layer_bytes / 1e6
-        t_swap_us = 40.0 + layer_mb / 33e3 * 1e6               # copy engines with both directions busy: 40 us + 33 GB/s
+        t_swap_us = GH.copy_engine_us(lp.layer_bytes)          # measured here, with both directions busy
+        print("measured swap time", round(t_swap_us, 1), "us")
         inner.set_layer_compute_us(t_swap_us / 1.7)
         tokens = 8
         for _ in range(tokens):
@@ -175,24 +175,24 @@ def test_adaptive_expansion_in_layers_on_hardware():
     try:
         ref.step(q, None, None, d_table, d_ctx, none, none, out_ref, cs, si, so)
         ref.sync()
-        t_swap_us = 40.0 + lp.layer_bytes / 33e3              # copy engines with both directions busy
+        t_swap_us = GH.copy_engine_us(lp.layer_bytes)          # measured here, with both directions busy
+        print("measured swap time", round(t_swap_us, 1), "us")
         t_layer_us = t_swap_us / 1.7
         inner.set_layer_compute_us(t_layer_us)
         levels, stalls, level, prev_stall = [], [], 0, 0.0
-        import time
         for token in range(60):
             levels.append(level)
-            t0 = time.perf_counter()
             lp.step(q, None, None, d_table, d_ctx, out, cs, si, so)
             inner.sync()
-            dt_ms = (time.perf_counter() - t0) * 1e3
             assert torch.equal(out.view(torch.int16), out_ref.view(torch.int16)), token
             st = lp.stats()
             stall = st.stall_ms - prev_stall
             prev_stall = st.stall_ms
             stalls.append(stall)
-            tc = (dt_ms - stall) / n
-            new = ctl.observe([tc] * n, [0.0] * n, [stall / n] * n, 0.0, (1.0 / dt_ms) * n / (n - level))
+            # the controller sees only whether computation waited: a token costs its layers' compute plus the
+            # waits (what else the host adds per token differs from box to box)
+            tc = t_layer_us / 1e3
+            new = ctl.observe([tc] * n, [0.0] * n, [stall / n] * n, 0.0, n / (n - level) / (n * tc + stall))
             if new != level:
                 lp.set_gpu_slots(n - new)
                 level = new
