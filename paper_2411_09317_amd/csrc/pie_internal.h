@@ -72,6 +72,16 @@ struct LayerView {
   int32_t n_handles, n_slots;
 };
 
+// Scratch of one attention call: the planning state (header, ticket counters, item records, slot lists) and
+// the split-context partials, laid out for lay_batch sequences of lay_max_blocks blocks.
+struct AttnWork {
+  int32_t* plan;
+  float* ws;
+  size_t ws_floats;
+  int32_t n_counters;       // ticket counters the planning kernel zeroes
+  int32_t lay_batch, lay_max_blocks;
+};
+
 struct SwapPairs {  // by-value kernel argument
   int32_t n;
   int32_t src[kSwapPairs];
@@ -189,16 +199,17 @@ int launch_kv_append(const pie_pool* p, int32_t layer, int32_t n_layers, const v
                      const int32_t* d_table, int32_t max_blocks, const int32_t* d_ctx, int32_t batch,
                      int32_t mode, hipStream_t s, const LayerView* view = nullptr);
 int launch_chunk_map_fill(int32_t* d_map, int32_t n_handles, int32_t chunk_blocks, const ChunkList& list, hipStream_t s);
+// work: the scratch to use; NULL = the pool's own (in the caller's device buffer)
 int launch_attn_plan(const pie_pool* p, const int32_t* d_ctx, int32_t batch, int32_t max_blocks, hipStream_t s,
-                     bool reset_clock = false);
+                     bool reset_clock = false, const AttnWork* work = nullptr);
 int launch_attn_resolve(const pie_pool* p, const int32_t* d_table, const int32_t* d_ctx, int32_t batch,
                         int32_t max_blocks, bool region0, bool valid0, bool region1, bool valid1, hipStream_t s,
-                        const LayerView* view = nullptr);
+                        const LayerView* view = nullptr, const AttnWork* work = nullptr);
 int launch_attn_decode(const pie_pool* p, int32_t layer, const void* d_q, int32_t max_blocks, const int32_t* d_ctx,
                        int32_t batch, void* d_out, hipStream_t s, hipEvent_t k_start = nullptr,
                        hipEvent_t k_end = nullptr, int32_t ticket_index = -1,
                        unsigned long long* clock_row = nullptr, const LayerView* view = nullptr,
-                       hipEvent_t done = nullptr);
+                       hipEvent_t done = nullptr, const AttnWork* work = nullptr);
 int launch_stream_probe(const pie_pool* p, int32_t layer, int32_t max_blocks, int32_t batch, hipStream_t s);
 size_t attn_plan_ints(const pie_config& c);
 size_t attn_workspace_floats(const pie_config& c);

@@ -1149,10 +1149,11 @@ bool attn_config_supported(const pie_config& c) {
   return c.max_batch <= kMaxPlanBatch && c.max_blocks_per_seq <= (1 << 19);
 }
 
-static size_t max_parts_of(const pie_config& c) {
-  const size_t mp = ((size_t)c.max_blocks_per_seq * c.block_tokens + kMinPartTokens - 1) / kMinPartTokens;
+static size_t max_parts_for(int32_t max_blocks) {
+  const size_t mp = ((size_t)max_blocks * kBlockTokens + kMinPartTokens - 1) / kMinPartTokens;
   return mp ? mp : 1;
 }
+static size_t max_parts_of(const pie_config& c) { return max_parts_for(c.max_blocks_per_seq); }
 
 size_t attn_workspace_floats(const pie_config& c) {
   return (size_t)c.max_batch * c.n_q_heads * max_parts_of(c) * (c.head_dim + 2);
@@ -1160,27 +1161,43 @@ size_t attn_workspace_floats(const pie_config& c) {
 
 // Blocks of slot lists one region needs: every item lists part_tokens / 16 slots, and a sequence's items
 // cover its blocks rounded up to a whole item.
-static size_t slot_list_ints(const pie_config& c) {
-  return (size_t)c.max_batch * ((size_t)c.max_blocks_per_seq + kWaves * 64);
+static size_t slot_list_ints(int32_t batch, int32_t max_blocks) {
+  return (size_t)batch * ((size_t)max_blocks + kWaves * 64);
 }
 
-// int32 words of planning state: header, per-layer ticket counters, item records (2 words each), and the
-// per-item slot lists of the two staging regions
-static size_t plan_counter_ints(const pie_config& c) {
-  return (size_t)c.n_layers + ((size_t)c.n_layers & 1);    // keeps the item records 8-byte aligned
+// int32 words of planning state: header, ticket counters (one per layer of a step), item records (2 words
+// each), and the per-item slot lists of the two staging regions
+static size_t plan_counter_ints(int32_t n_counters) {
+  return (size_t)n_counters + ((size_t)n_counters & 1);    // keeps the item records 8-byte aligned
 }
 
-size_t attn_plan_ints(const pie_config& c) {
-  return kPlanHdrInts + plan_counter_ints(c) + 2 * (size_t)c.max_batch * max_parts_of(c) + 2 * slot_list_ints(c);
+static size_t plan_ints_for(int32_t n_counters, int32_t batch, int32_t max_blocks) {
+  return kPlanHdrInts + plan_counter_ints(n_counters) + 2 * (size_t)batch * max_parts_for(max_blocks) +
+         2 * slot_list_ints(batch, max_blocks);
 }
 
-static int32_t* plan_hdr(const pie_pool* p) { return p->d_plan; }
-static uint32_t* plan_counters(const pie_pool* p) { return reinterpret_cast<uint32_t*>(p->d_plan + kPlanHdrInts); }
-static size_t plan_items_off(const pie_pool* p) { return kPlanHdrInts + plan_counter_ints(p->cfg); }
-static uint2* plan_items(const pie_pool* p) { return reinterpret_cast<uint2*>(p->d_plan + plan_items_off(p)); }
-static int32_t* plan_slots(const pie_pool* p, int region) {
-  return p->d_plan + plan_items_off(p) + 2 * (size_t)p->cfg.max_batch * max_parts_of(p->cfg) +
-         (size_t)region * slot_list_ints(p->cfg);
+size_t attn_plan_ints(const pie_config& c) { return plan_ints_for(c.n_layers, c.max_batch, c.max_blocks_per_seq); }
+
+// The pool's own scratch: the planning state and the partials carved from the caller's device buffer, laid out
+// for the pool's largest batch and table width.
+static AttnWork pool_work(const pie_pool* p) {
+  AttnWork w;
+  w.plan = p->d_plan;
+  w.ws = p->d_ws;
+  w.ws_floats = p->ws_floats;
+  w.n_counters = p->cfg.n_layers;
+  w.lay_batch = p->cfg.max_batch;
+  w.lay_max_blocks = p->cfg.max_blocks_per_seq;
+  return w;
+}
+
+static int32_t* plan_hdr(const AttnWork& w) { return w.plan; }
+static uint32_t* plan_counters(const AttnWork& w) { return reinterpret_cast<uint32_t*>(w.plan + kPlanHdrInts); }
+static size_t plan_items_off(const AttnWork& w) { return kPlanHdrInts + plan_counter_ints(w.n_counters); }
+static uint2* plan_items(const AttnWork& w) { return reinterpret_cast<uint2*>(w.plan + plan_items_off(w)); }
+static int32_t* plan_slots(const AttnWork& w, int region) {
+  return w.plan + plan_items_off(w) + 2 * (size_t)w.lay_batch * max_parts_for(w.lay_max_blocks) +
+         (size_t)region * slot_list_ints(w.lay_batch, w.lay_max_blocks);
 }
 
 // item size: a multiple of one pass of the workgroup's waves, at most 64 blocks per wave
@@ -1194,28 +1211,30 @@ static int32_t part_tokens_of(const pie_pool* p) {
 }
 
 int launch_attn_plan(const pie_pool* p, const int32_t* d_ctx, int32_t batch, int32_t max_blocks, hipStream_t s,
-                     bool reset_clock) {
-  if (batch > kMaxPlanBatch || batch > p->cfg.max_batch || max_blocks > p->cfg.max_blocks_per_seq) return PIE_EINVAL;
-  hipLaunchKernelGGL(k_attn_plan, dim3(1), dim3(256), 0, s, d_ctx, batch, part_tokens_of(p), max_blocks, plan_items(p),
-                     plan_hdr(p), plan_counters(p), p->cfg.n_layers, p->d_err, reset_clock ? p->d_clock : nullptr);
+                     bool reset_clock, const AttnWork* work) {
+  const AttnWork w = work ? *work : pool_work(p);
+  if (batch > kMaxPlanBatch || batch > w.lay_batch || max_blocks > w.lay_max_blocks) return PIE_EINVAL;
+  hipLaunchKernelGGL(k_attn_plan, dim3(1), dim3(256), 0, s, d_ctx, batch, part_tokens_of(p), max_blocks, plan_items(w),
+                     plan_hdr(w), plan_counters(w), w.n_counters, p->d_err, reset_clock ? p->d_clock : nullptr);
   PIE_HIP(hipGetLastError());
   return PIE_OK;
 }
 
 int launch_attn_resolve(const pie_pool* p, const int32_t* d_table, const int32_t* d_ctx, int32_t batch,
                         int32_t max_blocks, bool region0, bool valid0, bool region1, bool valid1, hipStream_t s,
-                        const LayerView* view) {
+                        const LayerView* view, const AttnWork* work) {
   (void)d_ctx;
-  if (batch > p->cfg.max_batch || max_blocks > p->cfg.max_blocks_per_seq || max_blocks <= 0) return PIE_EINVAL;
+  const AttnWork w = work ? *work : pool_work(p);
+  if (batch > w.lay_batch || max_blocks > w.lay_max_blocks || max_blocks <= 0) return PIE_EINVAL;
   const int32_t part = part_tokens_of(p);
   ResolveArgs a;
   a.table = d_table;
-  a.items = plan_items(p);
-  a.hdr = plan_hdr(p);
+  a.items = plan_items(w);
+  a.hdr = plan_hdr(w);
   a.map[0] = p->d_map[0];
   a.map[1] = p->d_map[1];
-  a.slots[0] = region0 ? plan_slots(p, 0) : nullptr;
-  a.slots[1] = region1 ? plan_slots(p, 1) : nullptr;
+  a.slots[0] = region0 ? plan_slots(w, 0) : nullptr;
+  a.slots[1] = region1 ? plan_slots(w, 1) : nullptr;
   a.err = p->d_err;
   a.max_blocks = max_blocks;
   a.n_handles = p->n_handles;
@@ -1297,8 +1316,10 @@ static int launch_f32(const AttnArgs& a, int32_t batch, int32_t n_q_heads, int32
 // same batch, table width and context lengths.
 int launch_attn_decode(const pie_pool* p, int32_t layer, const void* d_q, int32_t max_blocks, const int32_t* d_ctx,
                        int32_t batch, void* d_out, hipStream_t s, hipEvent_t k_start, hipEvent_t k_end,
-                       int32_t ticket_index, unsigned long long* clock_row, const LayerView* view, hipEvent_t done) {
+                       int32_t ticket_index, unsigned long long* clock_row, const LayerView* view, hipEvent_t done,
+                       const AttnWork* work) {
   const pie_config& c = p->cfg;
+  const AttnWork w = work ? *work : pool_work(p);
   if (((uintptr_t)d_q | (uintptr_t)d_out) % 16) return PIE_EINVAL;
   if (max_blocks <= 0) return PIE_EINVAL;
   if (c.n_gpu_blocks + 2 * c.n_stage_blocks <= 0) return PIE_EINVAL;
@@ -1306,20 +1327,21 @@ int launch_attn_decode(const pie_pool* p, int32_t layer, const void* d_q, int32_
   const int32_t part = part_tokens_of(p);
   const int32_t max_tokens = max_blocks * kBlockTokens;
   const int32_t n_parts = (max_tokens + part - 1) / part;
-  if ((size_t)batch * c.n_q_heads * n_parts * (c.head_dim + 2) > p->ws_floats) return PIE_ENOMEM;
+  if ((size_t)batch * c.n_q_heads * n_parts * (c.head_dim + 2) > w.ws_floats) return PIE_ENOMEM;
+  if (batch > w.lay_batch || max_blocks > w.lay_max_blocks) return PIE_EINVAL;
 
   AttnArgs a;
   a.kv_layer = view ? view->kv_base : p->d_kv + (size_t)layer * p->d_layer_stride;
-  a.slots = plan_slots(p, view ? 0 : (layer & 1));
-  a.items = plan_items(p);
-  a.hdr = plan_hdr(p);
+  a.slots = plan_slots(w, view ? 0 : (layer & 1));
+  a.items = plan_items(w);
+  a.hdr = plan_hdr(w);
   // one ticket counter per launch since the last planning kernel (by default the layer's)
   if (ticket_index < 0) ticket_index = layer;
-  if (ticket_index >= c.n_layers) return PIE_EINVAL;
-  a.counter = plan_counters(p) + ticket_index;
+  if (ticket_index >= w.n_counters) return PIE_EINVAL;
+  a.counter = plan_counters(w) + ticket_index;
   a.q = (const char*)d_q;
   a.out = (char*)d_out;
-  a.ws = p->d_ws;
+  a.ws = w.ws;
   a.ctx = d_ctx;
   a.block_bytes = p->block_bytes;
   a.scale_log2e = p->scale_log2e;
@@ -1353,12 +1375,13 @@ int launch_stream_probe(const pie_pool* p, int32_t layer, int32_t max_blocks, in
   const pie_config& c = p->cfg;
   if (max_blocks <= 0 || layer < 0 || layer >= c.n_layers) return PIE_EINVAL;
   const int32_t part = part_tokens_of(p);
+  const AttnWork w = pool_work(p);
   AttnArgs a = {};
   a.kv_layer = p->d_kv + (size_t)layer * p->d_layer_stride;
-  a.slots = plan_slots(p, layer & 1);
-  a.items = plan_items(p);
-  a.hdr = plan_hdr(p);
-  a.counter = plan_counters(p) + layer;
+  a.slots = plan_slots(w, layer & 1);
+  a.items = plan_items(w);
+  a.hdr = plan_hdr(w);
+  a.counter = plan_counters(w) + layer;
   a.block_bytes = p->block_bytes;
   a.n_kv_heads = c.n_kv_heads;
   a.part_tokens = part;
