@@ -225,6 +225,22 @@ int pie_attn_decode(pie_pool* pool, int32_t layer, const void* d_q,
                     const int32_t* d_ctx_lens, int32_t batch,
                     void* d_out, void* stream);
 
+/* pie_attn_decode for callers that cannot allocate or hand over scratch memory - code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc: same arguments, same kernels, same result bit for bit,
+ * but the call's scratch (planning state, ticket counter, split-context partials) lives in a static device array
+ * inside the library instead of the pool's workspace in the caller's buffer; the pool's max_batch and
+ * max_blocks_per_seq, which size that workspace, do not limit this call.  The array is 40 MiB, held by every
+ * GPU the library runs on until the process ends.  A call needs about
+ *   batch * n_q_heads * ceil(16 * max_blocks / partition) * (head_dim + 2) * 4 bytes  (partials)
+ *   + batch * (2 * max_blocks + 600) * 4 bytes                                         (planning state);
+ * PIE_ENOMEM if that exceeds the array (nothing is enqueued), PIE_EINVAL if batch > 4096.  Calls no hipMalloc,
+ * hipFree or other allocating routine; clears what it needs with its own kernels.  All calls on one GPU share
+ * the array: two calls that overlap in time on one GPU (different streams or pools) race - serialise them. */
+int pie_attn_decode_static(pie_pool* pool, int32_t layer, const void* d_q,
+                           const int32_t* d_block_table, int32_t max_blocks,
+                           const int32_t* d_ctx_lens, int32_t batch,
+                           void* d_out, void* stream);
+
 /* Calibration for the roofline of pie_attn_decode: reads exactly the K and V tiles that pie_attn_decode would
  * read for this layer, batch and table - same work items, same order, same loads - and discards them.
  * Waits for it and returns the kernel's duration in *out_ms (events around the launch on `stream`): the rate

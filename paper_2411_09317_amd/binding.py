@@ -29,7 +29,7 @@ SYMBOLS = [
     "pie_block_where", "pie_block_staged", "pie_pool_free_count", "pie_block_address", "pie_swap_in", "pie_swap_out",
     "pie_migrate", "pie_set_host_fraction", "pie_set_swap_path", "pie_set_attn_partition", "pie_set_swap_workgroups",
     "pie_set_layer_compute_us",
-    "pie_kv_append", "pie_attn_decode", "pie_attn_stream_probe_sync",
+    "pie_kv_append", "pie_attn_decode", "pie_attn_decode_static", "pie_attn_stream_probe_sync",
     "pie_step", "pie_prefetch_list", "pie_set_timing", "pie_set_cross_step_prefetch", "pie_set_host_presence_check", "pie_pool_sync", "pie_get_stats", "pie_get_layer_times",
     "pie_check_errors_sync", "pie_controller_create", "pie_controller_destroy", "pie_controller_config",
     "pie_controller_observe", "pie_controller_level", "pie_controller_update", "pie_last_hip_error", "pie_strerror",
@@ -248,6 +248,13 @@ class Pool:
         B, mb = block_table.shape
         _check(_lib.pie_attn_decode(self._h, C.c_int32(layer), _dptr(q), _dptr(block_table), C.c_int32(mb),
                                     _dptr(ctx_lens), C.c_int32(B), _dptr(out), _stream_ptr(stream)), "attn_decode")
+
+    def attn_decode_static(self, layer, q, block_table, ctx_lens, out, stream=None):
+        """attn_decode with its scratch in the library's static device array (allocates nothing)."""
+        B, mb = block_table.shape
+        _check(_lib.pie_attn_decode_static(self._h, C.c_int32(layer), _dptr(q), _dptr(block_table), C.c_int32(mb),
+                                           _dptr(ctx_lens), C.c_int32(B), _dptr(out), _stream_ptr(stream)),
+               "attn_decode_static")
 
     def attn_stream_probe(self, layer, block_table, ctx_lens, stream=None) -> float:
         """Duration in ms of a kernel that only reads the bytes attn_decode would read."""

@@ -211,6 +211,8 @@ int launch_attn_decode(const pie_pool* p, int32_t layer, const void* d_q, int32_
                        unsigned long long* clock_row = nullptr, const LayerView* view = nullptr,
                        hipEvent_t done = nullptr, const AttnWork* work = nullptr);
 int launch_stream_probe(const pie_pool* p, int32_t layer, int32_t max_blocks, int32_t batch, hipStream_t s);
+int attn_static_scratch(char** out);
+int attn_static_work(const pie_pool* p, int32_t batch, int32_t max_blocks, AttnWork* out);
 size_t attn_plan_ints(const pie_config& c);
 size_t attn_workspace_floats(const pie_config& c);
 bool attn_config_supported(const pie_config& c);

@@ -16,6 +16,7 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdlib>
+#include <mutex>
 
 #include <hip/hip_ext.h>
 
@@ -1395,6 +1396,57 @@ int launch_stream_probe(const pie_pool* p, int32_t layer, int32_t max_blocks, in
     default: return PIE_EINVAL;
   }
   PIE_HIP(hipGetLastError());
+  return PIE_OK;
+}
+
+// ---- attention without a workspace from the caller ---------------------------------------------------
+// For callers that cannot give or allocate scratch memory (code under graph capture, tight serving loops,
+// harnesses that forbid allocation): the planning state and the split-context partials of one attention call
+// live in a file-scope device array.  Every device the library runs on holds its own copy of the array for the
+// life of the process; its address on a device is looked up once, with that device current, and only that
+// address is ever handed to kernels (the array's name in host code is a host-side stand-in).
+
+constexpr size_t kStaticScratchBytes = (size_t)40 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxScratchDevices = 64;
+static char* g_scratch_ptr[kMaxScratchDevices] = {};
+static std::mutex g_scratch_mutex;
+
+// Device address of the current device's copy of the array.
+int attn_static_scratch(char** out) {
+  int dev = -1;
+  PIE_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxScratchDevices) return PIE_EINVAL;
+  std::lock_guard<std::mutex> guard(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    PIE_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return PIE_EHIP;
+    g_scratch_ptr[dev] = static_cast<char*>(ptr);
+  }
+  *out = g_scratch_ptr[dev];
+  return PIE_OK;
+}
+
+// The scratch of one call over `batch` sequences of up to `max_blocks` blocks, placed in the array: planning
+// state first, partials behind it.  PIE_ENOMEM if the call needs more than the array holds.
+int attn_static_work(const pie_pool* p, int32_t batch, int32_t max_blocks, AttnWork* out) {
+  if (batch < 0 || batch > kMaxPlanBatch || max_blocks < 0 || max_blocks > (1 << 19)) return PIE_EINVAL;
+  char* base = nullptr;
+  const int rc = attn_static_scratch(&base);
+  if (rc) return rc;
+  const int32_t part = part_tokens_of(p);
+  const size_t n_parts = ((size_t)max_blocks * kBlockTokens + part - 1) / part;
+  const size_t plan_bytes = (plan_ints_for(2, batch, max_blocks) * 4 + kAlign - 1) / kAlign * kAlign;
+  const size_t ws_floats = (size_t)batch * p->cfg.n_q_heads * n_parts * (p->cfg.head_dim + 2);
+  if (plan_bytes > kStaticScratchBytes || ws_floats * 4 > kStaticScratchBytes - plan_bytes) return PIE_ENOMEM;
+  out->plan = reinterpret_cast<int32_t*>(base);
+  out->ws = reinterpret_cast<float*>(base + plan_bytes);
+  out->ws_floats = ws_floats;
+  out->n_counters = 2;          // one is used; two keep the item records 8-byte aligned
+  out->lay_batch = batch;
+  out->lay_max_blocks = max_blocks;
   return PIE_OK;
 }
 

@@ -443,6 +443,10 @@ int pie_pool_init(const pie_config* cfg, void* d_base, size_t d_bytes, void* h_p
         (void)hipGetLastError();
     }
     auto fail = [&](int code) { pie_pool_destroy(p); return code; };
+    {
+      char* static_scratch = nullptr;               // the device's copy of the library's static scratch array
+      if ((rc = attn_static_scratch(&static_scratch))) return fail(rc);
+    }
     if (cfg->n_host_blocks > 0) {
       void* dev_ptr = nullptr;
       hipError_t e = hipHostGetDevicePointer(&dev_ptr, h_pinned_base, 0);
@@ -726,6 +730,24 @@ int pie_kv_append(pie_pool* p, int32_t layer, const void* d_k, const void* d_v, 
   return compute_epilogue(p, layer, s);
 }
 
+// work: the scratch the call's kernels use (NULL: the pool's own); ticket: which of its ticket counters.
+static int attn_decode_impl(pie_pool* p, int32_t layer, const void* d_q, const int32_t* d_block_table,
+                            int32_t max_blocks, const int32_t* d_ctx_lens, int32_t batch, void* d_out,
+                            hipStream_t s, const AttnWork* work, int32_t ticket) {
+  bool stage_valid = false;
+  int rc;
+  if ((rc = compute_prologue(p, layer, s, &stage_valid))) return rc;
+  const int r = layer & 1;
+  if ((rc = launch_attn_plan(p, d_ctx_lens, batch, max_blocks, s, false, work))) return rc;
+  if ((rc = launch_attn_resolve(p, d_block_table, d_ctx_lens, batch, max_blocks, r == 0, stage_valid, r == 1,
+                                stage_valid, s, nullptr, work)))
+    return rc;
+  if ((rc = launch_attn_decode(p, layer, d_q, max_blocks, d_ctx_lens, batch, d_out, s, nullptr, nullptr, ticket,
+                               nullptr, nullptr, nullptr, work)))
+    return rc;
+  return compute_epilogue(p, layer, s);
+}
+
 int pie_attn_decode(pie_pool* p, int32_t layer, const void* d_q, const int32_t* d_block_table, int32_t max_blocks,
                     const int32_t* d_ctx_lens, int32_t batch, void* d_out, void* stream) {
   if (!p) return PIE_EINVAL;
@@ -734,16 +756,22 @@ int pie_attn_decode(pie_pool* p, int32_t layer, const void* d_q, const int32_t* 
   if (batch > 0 && !d_out) return PIE_EINVAL;
   if (!p->device) return PIE_ESTATE;
   if (batch == 0) return PIE_OK;
-  hipStream_t s = (hipStream_t)stream;
-  bool stage_valid = false;
-  if ((rc = compute_prologue(p, layer, s, &stage_valid))) return rc;
-  const int r = layer & 1;
-  if ((rc = launch_attn_plan(p, d_ctx_lens, batch, max_blocks, s))) return rc;
-  if ((rc = launch_attn_resolve(p, d_block_table, d_ctx_lens, batch, max_blocks, r == 0, stage_valid, r == 1,
-                                stage_valid, s)))
-    return rc;
-  if ((rc = launch_attn_decode(p, layer, d_q, max_blocks, d_ctx_lens, batch, d_out, s))) return rc;
-  return compute_epilogue(p, layer, s);
+  return attn_decode_impl(p, layer, d_q, d_block_table, max_blocks, d_ctx_lens, batch, d_out, (hipStream_t)stream,
+                          nullptr, -1);
+}
+
+int pie_attn_decode_static(pie_pool* p, int32_t layer, const void* d_q, const int32_t* d_block_table,
+                           int32_t max_blocks, const int32_t* d_ctx_lens, int32_t batch, void* d_out, void* stream) {
+  if (!p) return PIE_EINVAL;
+  if (layer < 0 || layer >= p->cfg.n_layers || batch < 0 || max_blocks < 0) return PIE_EINVAL;
+  if (batch > 0 && (!d_q || !d_block_table || !d_ctx_lens || !d_out)) return PIE_EINVAL;
+  if (!p->device) return PIE_ESTATE;
+  if (batch == 0) return PIE_OK;
+  AttnWork work;
+  int rc = attn_static_work(p, batch, max_blocks, &work);   // PIE_ENOMEM: more than the static array holds
+  if (rc) return rc;
+  return attn_decode_impl(p, layer, d_q, d_block_table, max_blocks, d_ctx_lens, batch, d_out, (hipStream_t)stream,
+                          &work, 0);
 }
 
 static int elapsed(hipEvent_t a, hipEvent_t b, float* ms);
