@@ -516,6 +516,10 @@ int pie_elastic_move_blocks(pie_elastic_pool* ep, int32_t n, const int32_t* src,
 /* Blocks per layer a scheduler may use now, what they will be when the reallocation is complete, and m. */
 int pie_elastic_capacity(pie_elastic_pool* ep, int32_t* out_visible_blocks, int32_t* out_target_blocks,
                          int32_t* out_layers_on_cpu);
+/* Blocks per layer the caches will have with m layers kept in CPU memory, once that reallocation is complete:
+ * min(max_chunks_per_layer, N / (n - m)) chunks (Section 3.1's a / (n - m), in whole chunks).  For a scheduler
+ * that must know what fits below a size before it asks for it.  PIE_EINVAL unless 0 <= m < n_layers. */
+int pie_elastic_blocks_for(pie_elastic_pool* ep, int32_t m, int32_t* out_blocks);
 /* One decode step over the logical layers, in order; arguments as pie_layer_step. */
 int pie_elastic_step(pie_elastic_pool* ep, const void* d_q_all, const void* d_k_new, const void* d_v_new,
                      const int32_t* d_block_table, int32_t max_blocks, const int32_t* d_ctx_lens, int32_t batch,

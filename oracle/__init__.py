@@ -27,8 +27,10 @@ Pinned by (see tests/test_oracle_*.py):
       of nine layers away, growth visible exactly when the second has left, a
       refused and a granted shrink, conservation under random histories.
   serving_sim.simulate              - a hand-worked three-request stream
-      (tests/test_serving_host.py); the scheduling rules themselves are this
-      build's reading of an engine the paper inherits: parity unpinned beyond
-      that example.
+      (tests/test_serving_host.py); closed forms (equal requests run in waves,
+      a one-request budget serialises the stream, idle gaps are skipped) and
+      invariants recomputed from the trace under random streams
+      (tests/test_oracle_serving_sim.py).  The scheduling rules themselves are
+      this build's reading of an engine the paper inherits.
 Absolute throughput numbers: parity unpinned (the paper prints none for this path).
 """

@@ -41,7 +41,7 @@ SYMBOLS = [
     "pie_chunk_book_create", "pie_chunk_book_destroy", "pie_chunk_book_set_layers_on_cpu", "pie_chunk_book_left_gpu",
     "pie_chunk_book_enters_gpu", "pie_chunk_book_layer", "pie_chunk_book_capacity",
     "pie_elastic_bytes_required", "pie_elastic_create", "pie_elastic_destroy", "pie_elastic_set_layers_on_cpu",
-    "pie_elastic_capacity", "pie_elastic_set_live_blocks", "pie_elastic_move_blocks", "pie_elastic_step", "pie_elastic_settle_sync", "pie_elastic_layer", "pie_elastic_table",
+    "pie_elastic_capacity", "pie_elastic_blocks_for", "pie_elastic_set_live_blocks", "pie_elastic_move_blocks", "pie_elastic_step", "pie_elastic_settle_sync", "pie_elastic_layer", "pie_elastic_table",
     "pie_elastic_stats",
 ]
 
@@ -568,8 +568,9 @@ class ElasticPool:
 
     def blocks_for(self, m: int) -> int:
         """Blocks per layer when m layers are kept in CPU memory and the reallocation is complete."""
-        n_chunks = self.n_layers * (self.pool.cfg.n_gpu_blocks // self.C)
-        return min(self.k_cap, n_chunks // (self.n_layers - m)) * self.C
+        n = C.c_int32(0)
+        _check(_lib.pie_elastic_blocks_for(self._h, C.c_int32(m), C.byref(n)), "elastic_blocks_for")
+        return n.value
 
     def move_blocks(self, src: Sequence[int], dst: Sequence[int], compute_stream=None):
         a, b = _i32(src), _i32(dst)

@@ -450,6 +450,12 @@ int pie_elastic_capacity(pie_elastic_pool* lp, int32_t* out_visible_blocks, int3
   return PIE_OK;
 }
 
+int pie_elastic_blocks_for(pie_elastic_pool* lp, int32_t m, int32_t* out_blocks) {
+  if (!lp || !out_blocks || m < 0 || m >= lp->n) return PIE_EINVAL;
+  *out_blocks = lp->book->target_for(m) * lp->C;
+  return PIE_OK;
+}
+
 int pie_elastic_layer(pie_elastic_pool* lp, int32_t layer, int32_t* out_where, int32_t* out_n_chunks,
                       int32_t* out_chunks, void** out_host_ptr) {
   if (!lp || layer < 0 || layer >= lp->n || !out_where || !out_n_chunks) return PIE_EINVAL;

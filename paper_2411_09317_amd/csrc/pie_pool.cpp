@@ -655,6 +655,8 @@ int pie_migrate(pie_pool* p, int32_t n, const int32_t* handles, int32_t to_where
     const bool on_host = cp.path == PIE_SWAP_DMA;
     note_stream(p, s);
     if ((rc = order_after(s, p->ev_compute, p->ev_compute_rec, on_host))) return rc;
+    // an earlier migration, possibly on another stream, may still be reading a slot this one is given
+    if ((rc = order_after(s, p->ev_migrate, p->ev_migrate_rec, on_host))) return rc;
     for (int r = 0; r < 2; ++r) {
       if ((rc = order_after(s, p->ev_in[r], p->ev_in_rec[r], on_host))) return rc;
       if ((rc = order_after(s, p->ev_out[r], p->ev_out_rec[r], on_host))) return rc;

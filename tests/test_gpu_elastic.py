@@ -65,6 +65,25 @@ def test_capacity_follows_the_layers_on_the_cpu_and_results_never_change(dtype):
     ctx = np.concatenate([case.ctx_lens, [0]]).astype(np.int32)
     none = np.zeros(0, dtype=np.int32)
     token = [0]
+    # What every sequence holds, token by token, kept densely on the host: the oracle's input at every token,
+    # not only the first (the fourth sequence starts empty; the others may grow to the end of their last block).
+    from oracle import numfmt
+    from test_gpu_attention import check
+    cap = [int(case.n_blocks[b]) * 16 for b in range(3)] + [2 * 16]
+    dense = []
+    for d_src in (case.k_dense, case.v_dense):
+        rows = [np.zeros((n, cap[b], w.n_kv_heads, w.head_dim), dtype=sd) for b in range(4)]
+        for b in range(3):
+            rows[b][:, : int(case.ctx_lens[b]) - 1] = d_src[b][:, : int(case.ctx_lens[b]) - 1]
+        dense.append(rows)
+
+    def oracle_check(out, layers):
+        live = [b for b in range(batch) if ctx[b] > 0]
+        for l in layers:
+            K = [numfmt.to_f64(dense[0][b][l, : ctx[b]], dtype) for b in live]
+            V = [numfmt.to_f64(dense[1][b][l, : ctx[b]], dtype) for b in live]
+            ref = A.dense_attention(numfmt.to_f64(q_np[l][live], dtype), K, V, ctx[live])
+            check(GH.from_dev(out[l][live], dtype), ref, dtype)
 
     def step():
         t = token[0]
@@ -78,6 +97,10 @@ def test_capacity_follows_the_layers_on_the_cpu_and_results_never_change(dtype):
             v_new = I.to_storage(I.draw_values(w, (n, batch, w.n_kv_heads, w.head_dim), 200 + t), dtype)
         dk, dv = GH.to_dev(k_new, dtype), GH.to_dev(v_new, dtype)
         d_ctx = torch.from_numpy(ctx).to(GH.DEV)
+        for b in range(batch):
+            if ctx[b] > 0:                                        # the step appends this token's rows
+                dense[0][b][:, ctx[b] - 1] = k_new[:, b]
+                dense[1][b][:, ctx[b] - 1] = v_new[:, b]
         out_ref, out = torch.empty_like(q), torch.full_like(q, float("nan"))
         ref.step(q, dk, dv, d_table, d_ctx, none, none, out_ref, cs, si, so)
         ref.sync()
@@ -85,10 +108,11 @@ def test_capacity_follows_the_layers_on_the_cpu_and_results_never_change(dtype):
         inner.sync()
         assert inner.check_errors() == 0 and ref.check_errors() == 0
         assert torch.equal(out.view(torch.int16), out_ref.view(torch.int16)), t
-        if t == 0:                                                # and the reference is the oracle's answer
-            from test_gpu_attention import check
-            for l in (0, 4, 8):
-                check(GH.from_dev(out[l, :3], dtype), A.dense_attention(*H.dense_f64(case, l), case.ctx_lens), dtype)
+        # and it is the oracle's answer: three layers at the first token, two rotating ones at every later
+        # token (after the appends, the join in new blocks, the moves out and in, the shrink)
+        oracle_check(out, (0, 4, 8) if t == 0 else (t % n, (t + 4) % n))
+        if t == 0:
+            check(GH.from_dev(out[4, :3], dtype), A.dense_attention(*H.dense_f64(case, 4), case.ctx_lens), dtype)
         token[0] += 1
         return out
 
@@ -203,7 +227,9 @@ def test_adaptive_expansion_grows_the_caches_on_hardware():
         ref.sync()
         t_swap_us = GH.copy_engine_us(k0 * ep.chunk_bytes, pieces=k0)   # measured here: one copy per chunk, both directions busy
         print("measured swap time", round(t_swap_us, 1), "us")
-        t_layer_us = t_swap_us / 1.7
+        # a layer's move takes 1.4 layer times by that measurement: the protocol hides up to two, and the chunked
+        # moves it really makes (host-ordered, both directions interleaved) come out somewhat slower than measured
+        t_layer_us = t_swap_us / 1.4
         inner.set_layer_compute_us(t_layer_us)
         ep.set_live_blocks(nb)                                    # a layer always travels as its k0 live chunks
         # once around before the clock counts: the first transfers through fresh pinned memory are slow
@@ -284,6 +310,8 @@ def test_serving_on_growing_and_shrinking_caches_matches_an_all_resident_pool():
     none = np.zeros(0, dtype=np.int32)
     plan = {5: 2, 50: 3, 90: 1, 130: 0}                               # iteration -> layers asked to be on the CPU
     want, it, sizes, above, refused, moved, on_cpu_at_move = 0, 0, [], 0, 0, 0, []
+    rows_of, n_oracle = {}, 0
+    from test_gpu_attention import check
     cs = loop.streams[0]
     try:
         while not sched.idle:
@@ -326,6 +354,19 @@ def test_serving_on_growing_and_shrinking_caches_matches_an_all_resident_pool():
             ep.set_live_blocks(store.live_end())
             dt, _ = loop.iteration(sched, step=ep.step)
             shape = lambda t, h: t[: n * B_ * h * w.head_dim].view(n, B_, h, w.head_dim)
+            # the oracle's view: every request's rows, kept densely on the host as the steps append them
+            k_rows, v_rows = shape(loop.k_new, w.n_kv_heads).cpu().numpy(), shape(loop.v_new, w.n_kv_heads).cpu().numpy()
+            for i, r in enumerate(sched.running):
+                kd, vd = rows_of.setdefault(r.rid, (np.zeros((n, max_blocks * 16, w.n_kv_heads, w.head_dim), np.float16),
+                                                    np.zeros((n, max_blocks * 16, w.n_kv_heads, w.head_dim), np.float16)))
+                kd[:, r.ctx - 1], vd[:, r.ctx - 1] = k_rows[:, i], v_rows[:, i]
+            if it % 7 == 0 or it in plan or it - 1 in plan or it in (70, 75, 110, 71, 76, 111):
+                l = it % n
+                K = [rows_of[r.rid][0][l, : r.ctx].astype(np.float64) for r in sched.running]
+                V = [rows_of[r.rid][1][l, : r.ctx].astype(np.float64) for r in sched.running]
+                want_out = A.dense_attention(shape(loop.q, w.n_q_heads)[l].cpu().numpy().astype(np.float64), K, V, ctx)
+                check(GH.from_dev(shape(loop.out, w.n_q_heads)[l], dtype), want_out, dtype)
+                n_oracle += 1
             out_ref = torch.empty_like(shape(loop.out, w.n_q_heads))
             ref.step(shape(loop.q, w.n_q_heads), shape(loop.k_new, w.n_kv_heads), shape(loop.v_new, w.n_kv_heads),
                      loop.d_table[:B_], loop.d_ctx[:B_], none, none, out_ref, *loop.streams)
@@ -336,7 +377,7 @@ def test_serving_on_growing_and_shrinking_caches_matches_an_all_resident_pool():
             it += 1
             assert it < 3000
         assert inner.check_errors() == 0 and ref.check_errors() == 0
-        assert len(sched.done) == 60 and not store.used.any()
+        assert len(sched.done) == 60 and not store.used.any() and n_oracle > 20
         assert max(sizes) >= 9 * C > k0 * C and above > 10          # requests lived in blocks the small caches lack
         assert moved > 0 and max(on_cpu_at_move) >= 1              # blocks were moved, in both kinds of memory
         assert it > 130 or want == plan[max(k for k in plan if k <= it)]

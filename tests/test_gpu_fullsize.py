@@ -82,6 +82,60 @@ def sample_pairs(dw, n, seed):
     return pairs
 
 
+def fresh_rows(dw, seed):
+    """New K / V rows for this step's token (the same distribution as the workload's), in place."""
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(seed)
+    for t in (dw.k_new, dw.v_new):
+        t.copy_((torch.randn(t.shape, device="cuda:0", dtype=torch.float32, generator=gen) * dw.w.value_scale).to(t.dtype))
+    torch.cuda.synchronize()
+
+
+def rows_np(t):
+    return t.view(torch.int16).cpu().numpy().view(np.uint16 if t.dtype == torch.bfloat16 else np.float16)
+
+
+def step_and_check_tail_blocks(dw, pf, dirty, seed, layers, n_each=5):
+    """One step with fresh rows.  Afterwards the home image of sampled tail blocks - host-homed ones in the pinned
+    pool (they were staged, appended to and written back), GPU-homed ones in the device pool - must be what the
+    oracle's layout says: the image before the step with row (ctx - 1) % T of every kv head's K and V replaced
+    by the new rows, every other byte unchanged.  Sampled host blocks that are not tails (staged, read, dropped)
+    must not have changed at all."""
+    w = dw.w
+    T = w.block_tokens
+    fresh_rows(dw, seed)
+    k_new, v_new = rows_np(dw.k_new), rows_np(dw.v_new)
+    sd = I.storage_numpy_dtype(w.dtype)
+    tail_of = {int(dw.table[b, (int(dw.ctx_lens[b]) - 1) // T]): b for b in range(w.batch)}
+    dirty_set = set(int(h) for h in dirty)
+    assert dirty_set <= set(tail_of)
+    rng = np.random.Generator(np.random.PCG64([w.seed, 902, seed]))
+    pick = lambda xs, n: [xs[i] for i in rng.permutation(len(xs))[:n]]
+    host_tails = pick(sorted(dirty_set), n_each)
+    gpu_tails = pick(sorted(set(tail_of) - dirty_set), n_each)
+    clean = pick(sorted(set(int(h) for h in pf) - dirty_set), n_each)
+    assert host_tails and gpu_tails and clean
+    handles = host_tails + gpu_tails + clean
+    where, slots = dw.pool.block_where(handles)
+    assert where == [B.HOST] * len(host_tails) + [B.GPU] * len(gpu_tails) + [B.HOST] * len(clean)
+    image = lambda wh: dw.pool.host_image() if wh == B.HOST else dw.pool.gpu_image()
+    before = {(l, h): image(wh)[l, sl].cpu().numpy().copy() for h, wh, sl in zip(handles, where, slots) for l in layers}
+    run_steps(dw, pf, dirty, n=1)
+    for h, wh, sl in zip(handles, where, slots):
+        for l in layers:
+            after = image(wh)[l, sl].cpu().numpy()
+            if h not in tail_of:
+                assert np.array_equal(after, before[(l, h)]), (l, h)
+                continue
+            b, t = tail_of[h], (int(dw.ctx_lens[tail_of[h]]) - 1) % T
+            logical = LY.from_physical(before[(l, h)].view(sd), w.n_kv_heads, T, w.head_dim).copy()   # [2][Hkv][T][d]
+            logical[0, :, t, :] = k_new[l, b]
+            logical[1, :, t, :] = v_new[l, b]
+            expect = LY.to_physical(logical).view(np.uint8)
+            assert np.array_equal(after, expect), (l, h, wh)
+            assert not np.array_equal(after, before[(l, h)])          # the row really is new
+
+
 def test_llama2_7b_shape_all_resident_then_thirty_percent_on_the_host():
     """The benchmark's workload: all resident, then the 30 % leg; sampled outputs against the oracle, and the
     swap leg's outputs bit-identical to the resident ones."""
@@ -104,6 +158,11 @@ def test_llama2_7b_shape_all_resident_then_thirty_percent_on_the_host():
         check_samples(dw, samples[:3])          # the oracle now reads 30 % of the blocks from the host pool
         st = dw.pool.stats()
         assert abs(st.host_fraction - 0.30) < 0.01
+        # the write-back at this size, through the copy engine and through the gather / scatter kernel
+        for path, seed in ((B.SWAP_DMA, 11), (B.SWAP_KERNEL, 12), (B.SWAP_AUTO, 13)):
+            dw.pool.set_swap_path(path)
+            step_and_check_tail_blocks(dw, pf, dirty, seed, layers=(0, 17, 31))
+            check_samples(dw, samples[3:5])     # and the attention saw the new rows (the oracle reads the pools' bytes)
     finally:
         dw.pool.close()
 
