@@ -46,6 +46,11 @@ def parse():
     ap.add_argument("--swap-path", type=int, default=0)
     ap.add_argument("--swap-wgs", type=int, default=0, help="workgroups of the gather / scatter kernel (0 = library default)")
     ap.add_argument("--no-swap", action="store_true")
+    ap.add_argument("--no-extra", action="store_true",
+                    help="leave out the compact legs of the 8B-shaped and 70B-shaped workloads (cfg4, cfg5) that the "
+                         "default line carries beside the headline")
+    ap.add_argument("--scatter-link-fraction", type=float, default=0.02,
+                    help="host fraction of the transfer-bound point of the gather-kernel leg")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--cpu-seqs", type=int, default=64)
     ap.add_argument("--cpu-layers", type=int, default=6)
@@ -181,6 +186,133 @@ def fixed_fraction_leg(w, dw, streams, f, n_steps, base_kernel_ms, base_step_ms,
     return {k: m[k] for k in keep}
 
 
+def scattered_kernel_leg(w, dw, streams, f_small, f_link, base_kernel_ms, base_step_ms, achieved):
+    """The gather kernel on a host pool full of holes: twice the blocks go to the host and every other one comes
+    back, so a layer's prefetch is as many pieces as blocks and the copy engine would pay its per-call cost for
+    each.  Two points: f_small (below what the link hides: what the path costs a step) and f_link (transfer-bound:
+    the link rate the kernel reaches, and the decode kernel's slowdown with the gather beside it all the time)."""
+    from paper_2411_09317_amd import binding as B
+    out = {"swap_path": "gather kernel (PIE_SWAP_KERNEL), library defaults"}
+    for name, f in (("below_knee", f_small), ("link_bound", f_link)):
+        k = int(round(2 * f * len(dw.order)))
+        dw.pool.migrate(dw.order[:k], B.HOST, streams[1])
+        dw.pool.migrate(dw.order[1:k:2], B.GPU, streams[1])
+        dw.pool.sync()
+        pf, dirty = dw.pool.prefetch_list(dw.table, dw.ctx_lens)
+        slots = np.asarray(dw.pool.block_where(pf)[1])
+        dw.pool.set_swap_path(B.SWAP_KERNEL)
+        timed_steps(dw, streams, 1, pf, dirty)
+        n = 10 if name == "below_knee" else 3
+        s_total = timed_steps(dw, streams, n, pf, dirty)
+        sp = layer_profile(dw, streams, pf, dirty, reps=3)
+        assert dw.pool.check_errors() == 0
+        m = leg_metrics(w, dw, sp, s_total / n, base_kernel_ms, base_step_ms, achieved)
+        keep = ("host_fraction", "tokens_per_s", "ms_per_step", "bytes_in_per_layer", "swap_in_ms_per_layer",
+                "host_link_GBps", "attn_kernel_ms_per_layer", "inflation_kernel", "inflation_e2e", "stall_ms_per_step")
+        out[name] = {k_: m[k_] for k_ in keep}
+        out[name]["pieces_per_layer"] = 1 + int((np.diff(slots) != 1).sum())
+        dw.pool.set_swap_path(B.SWAP_AUTO)
+        dw.pool.migrate(dw.order[:k], B.GPU, streams[1])
+        dw.pool.sync()
+    return out
+
+
+def roofline_of(w, dw, streams, steps, warmup):
+    """All-resident steps of a workload: throughput and the decode kernel's roofline numbers."""
+    none = np.zeros(0, dtype=np.int32)
+    timed_steps(dw, streams, 1, none, none)
+    probe_ms = float(np.mean([dw.pool.attn_stream_probe(l % w.n_layers, dw.d_table, dw.d_ctx, streams[0])
+                              for l in range(2 * min(w.n_layers, 8))][2:]))
+    timed_steps(dw, streams, warmup, none, none)
+    s = timed_steps(dw, streams, steps, none, none) / steps
+    prof = layer_profile(dw, streams, none, none)
+    assert dw.pool.check_errors() == 0
+    k_ms = float(np.mean(prof["kernel"]))
+    achieved = dw.kv_bytes_per_layer / (k_ms * 1e-3) / 1e9
+    traffic, source = traffic_from_profile(f"attn_decode_{w.name}_pmc.txt")
+    res = {"tokens_per_s": w.batch / s, "ms_per_step": s * 1e3, "layers": w.n_layers,
+           "roofline": {"bound": "hbm", "kernel": "k_attn_decode_mfma", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                        "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": source,
+                        "kernel_ms": k_ms, "algorithmic_bytes_per_launch": dw.kv_bytes_per_layer,
+                        "stream_probe_ms": probe_ms, "frac_of_stream_probe": probe_ms / k_ms}}
+    return res, prof["kernel"].copy(), s * 1e3, achieved
+
+
+def compact_cfg4(steps, warmup):
+    """The 8B-shaped GQA workload in the default line: roofline at the full shape, fixed host fractions around
+    the knee and at 30 %, and the controller's operating point next to the best fixed point (the criterion the
+    paper's ablation applies to its adaptive expansion: close to the exhaustive optimum)."""
+    import torch
+    from paper_2411_09317_amd import inputs as I
+    from paper_2411_09317_amd import workload as WL
+    w = I.CONFIGS["cfg4"]
+    dw = WL.build(w, host_capacity_fraction=0.32)
+    streams = (torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream())
+    res, base_k, base_ms, achieved = roofline_of(w, dw, streams, steps, warmup)
+    res["workload"] = (f"cfg4: {w.n_layers} layers, batch {w.batch}, {w.n_q_heads} q heads / {w.n_kv_heads} kv heads, "
+                       f"head_dim {w.head_dim}, bf16, ctx lognormal(median {w.ctx_median}, sigma {w.ctx_sigma}) clipped to "
+                       f"[{w.ctx_lo},{w.ctx_hi}], {int(dw.ctx_lens.sum())} context tokens")
+    pts = [{"host_fraction": 0.0, "tokens_per_s": res["tokens_per_s"], "ms_per_step": res["ms_per_step"],
+            "inflation_kernel": 0.0, "inflation_e2e": 0.0, "stall_ms_per_step": 0.0, "expansion_simple": 1.0}]
+    for f in (0.0025, 0.005, 0.0075, 0.01, 0.30):
+        pts.append(fixed_fraction_leg(w, dw, streams, f, 3, base_k, base_ms, achieved))
+    res["fixed_fraction"] = pts
+    units = 8 * w.n_layers
+    ad = adaptive_leg(w, dw, streams, 160, units, int(0.04 * units))
+    # the controller's own signal, tokens/s x expansion, at every fixed point and where the controller ended
+    signal = lambda p: p["tokens_per_s"] * p["expansion_simple"]
+    best = max(pts[:-1], key=signal)
+    at = min(pts[:-1], key=lambda p: abs(p["host_fraction"] - ad["final_host_fraction"]))
+    res["adaptive"] = {k: ad[k] for k in ("units", "steps", "final_level", "final_host_fraction", "level_min_second_half",
+                                          "level_max_second_half", "monitoring_overhead")}
+    res["adaptive"].update({"best_fixed_host_fraction": best["host_fraction"],
+                            "signal_at_final_over_best_fixed": signal(at) / signal(best),
+                            "signal": "tokens/s x 1/(1-f), evaluated on the fixed-fraction points nearest to each f"})
+    dw.pool.close()
+    del dw
+    torch.cuda.empty_cache()
+    return res
+
+
+def compact_cfg5(steps, warmup, layers=16, overflow=0.215):
+    """The 70B-shaped long-context workload: 343.6 GB of KV do not fit 288 GB of HBM, so at least 21.5 % must live
+    on the host.  One GPU shows the real per-layer shape (batch 32 x 32768 tokens, 64 / 8 heads, 4.29 GB per
+    layer) on `layers` of the 80 layers: the roofline of the kernel, and the pipeline with the overflow share of
+    every sequence's blocks in pinned memory."""
+    import torch
+    from paper_2411_09317_amd import binding as B
+    from paper_2411_09317_amd import inputs as I
+    from paper_2411_09317_amd import workload as WL
+    w0 = I.CONFIGS["cfg5"]
+    dw = WL.build(w0, host_capacity_fraction=overflow + 0.01, n_layers=layers)
+    w = dw.w
+    streams = (torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream())
+    res, base_k, base_ms, achieved = roofline_of(w, dw, streams, steps, warmup)
+    res["workload"] = (f"cfg5 per-layer shape on {layers} of {w0.n_layers} layers: batch {w.batch} x {w.ctx_hi} tokens, "
+                       f"{w.n_q_heads} q heads / {w.n_kv_heads} kv heads, head_dim {w.head_dim}, bf16")
+    res["aliasing"] = (f"{layers} physical layers stand for {w0.n_layers}: per-layer numbers are real, a whole step would "
+                       f"take {w0.n_layers}/{layers} times ms_per_step; the full cache ({w0.n_layers} x "
+                       f"{dw.kv_bytes_per_layer / 1e9:.2f} GB = {w0.n_layers * dw.kv_bytes_per_layer / 1e9:.1f} GB) does not fit one GPU")
+    res["tokens_per_s_whole_model_extrapolated"] = res["tokens_per_s"] * layers / w0.n_layers
+    hs = WL.per_sequence_host_order(dw, overflow)
+    dw.pool.migrate(hs, B.HOST, streams[1])
+    dw.pool.sync()
+    pf, dirty = dw.pool.prefetch_list(dw.table, dw.ctx_lens)
+    timed_steps(dw, streams, 1, pf, dirty)
+    s = timed_steps(dw, streams, 2, pf, dirty) / 2
+    sp = layer_profile(dw, streams, pf, dirty, reps=2)
+    assert dw.pool.check_errors() == 0
+    m = leg_metrics(w, dw, sp, s, base_k, base_ms, achieved)
+    keep = ("host_fraction", "tokens_per_s", "ms_per_step", "bytes_in_per_layer", "swap_in_ms_per_layer", "host_link_GBps",
+            "host_link_frac", "attn_kernel_ms_per_layer", "inflation_kernel", "inflation_e2e", "stall_ms_per_step")
+    res["overflow_on_host"] = {k: m[k] for k in keep}
+    res["overflow_on_host"]["tokens_per_s_whole_model_extrapolated"] = m["tokens_per_s"] * layers / w0.n_layers
+    dw.pool.close()
+    del dw
+    torch.cuda.empty_cache()
+    return res
+
+
 def adaptive_leg(w, dw, streams, n_steps, units, k_max):
     """The controller in the loop: it starts at f = 0, sees every step's per-layer times, and moves the host
     fraction one level at a time.  The throughput signal is tokens/s x expansion: a larger effective cache
@@ -275,14 +407,18 @@ def layer_fifo_leg(w, dw, m, n_steps, t_other_us, base_step_ms):
 
 
 def traffic_from_profile(name):
-    """HBM bytes per launch measured with rocprofv3 counters, if a summary has been committed."""
+    """HBM bytes per launch measured with rocprofv3 counters, as a committed summary states them: (bytes, where
+    that number comes from).  It is a figure from an earlier, separate profiler run of the same command (counters
+    cannot be collected inside this run), so the line names the file and its date beside it."""
     path = os.path.join(ROOT, "profiles", name)
     if not os.path.exists(path):
-        return None
+        return None, None
     for line in open(path):
         if line.startswith("traffic_bytes_per_launch"):
-            return float(line.split("=")[1].split()[0])
-    return None
+            stamp = time.strftime("%Y-%m-%d", time.gmtime(os.path.getmtime(path)))
+            return float(line.split("=")[1].split()[0]), (f"profiles/{name} (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, separate "
+                                                          f"earlier runs, file dated {stamp}; not measured in this run)")
+    return None, None
 
 
 def cpu_baseline(dw, n_seqs, n_layers):
@@ -599,7 +735,8 @@ def main():
                                                                    "swap_below_knee.inflation_kernel / inflation_e2e"}},
         "roofline": {"bound": "hbm", "kernel": "k_attn_decode_mfma", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": traffic_from_profile(f"attn_decode_{w.name}_pmc.txt"),
+                     "traffic": traffic_from_profile(f"attn_decode_{w.name}_pmc.txt")[0],
+                     "traffic_source": traffic_from_profile(f"attn_decode_{w.name}_pmc.txt")[1],
                      "kernel_ms": k_ms, "algorithmic_bytes_per_launch": bytes_layer,
                      "stream_probe_ms": probe_ms, "stream_probe_GBps": bytes_layer / (probe_ms * 1e-3) / 1e9,
                      "frac_of_stream_probe": probe_ms / k_ms},
@@ -636,6 +773,9 @@ def main():
                                                        base_step_ms, achieved)
         dw.pool.set_host_fraction(0.0, dw.order, streams[1])
         dw.pool.sync()
+        # and through the gather kernel, on a host pool full of holes
+        result["swap_kernel"] = scattered_kernel_leg(w, dw, streams, args.below_knee_fraction, args.scatter_link_fraction,
+                                                     base_kernel_ms, base_step_ms, achieved)
 
     # ---- optional: fixed-fraction sweep and the adaptive controller ---------------------------------------
     if args.sweep:
@@ -650,6 +790,13 @@ def main():
         k_max = int(host_cap * units)
         result["adaptive"] = adaptive_leg(w, dw, streams, args.adaptive_steps, units, k_max)
     dw.pool.close()
+    headline = args.workload == "cfg2" and not args.layers and not args.ctx_fixed
+    del dw
+    torch.cuda.empty_cache()
+    # ---- the other two named workloads, compact (each builds and frees its own pools) ------------------------
+    if headline and not args.no_extra:
+        result["cfg4"] = compact_cfg4(10, 2)
+        result["cfg5"] = compact_cfg5(5, 1)
     print(json.dumps(result))
 
 

@@ -71,7 +71,7 @@ extern "C" {
 #define PIE_WHERE_HOST 1
 
 /* swap paths (pie_set_swap_path) */
-#define PIE_SWAP_AUTO   0  /* copy engine for few long runs, kernel otherwise */
+#define PIE_SWAP_AUTO   0  /* per transfer: the copy engine unless the list is so scattered that the kernel is faster */
 #define PIE_SWAP_DMA    1  /* one hipMemcpyAsync per contiguous run of slots */
 #define PIE_SWAP_KERNEL 2  /* gather / scatter kernel reading or writing pinned host memory directly */
 
@@ -191,8 +191,12 @@ int pie_set_swap_path(pie_pool* pool, int32_t path);
  * [256, 4096]); longer contexts are split and reduced.  Default 512. */
 int pie_set_attn_partition(pie_pool* pool, int32_t tokens);
 
-/* Workgroups the gather / scatter kernel may occupy (1..1024, default 64): it is bound by the host link,
- * so few are enough and the rest of the GPU stays free for attention. */
+/* Workgroups of the gather / scatter kernel (1..1024, default 16).  The kernel is bound by the host link, not
+ * by compute.  A transfer of up to 12 MiB - one that can hide behind a layer - is moved by that many workgroups
+ * of 256 threads (about 28 GB/s beside a running decode kernel, which slows by 2-3 %); a larger one by that many
+ * one-wavefront workgroups with sixteen 16-byte accesses in flight per lane (about 41 GB/s, the decode kernels it
+ * runs beside slow by 2-3 %).  More workgroups move more and disturb more; the link's own limit is near 56 GB/s,
+ * which the copy engine reaches. */
 int pie_set_swap_workgroups(pie_pool* pool, int32_t n);
 
 /* Stand-in for the rest of a transformer layer.  The paper's per-layer compute time (Section 3.1, the

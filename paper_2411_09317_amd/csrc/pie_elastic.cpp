@@ -422,7 +422,7 @@ int pie_elastic_move_blocks(pie_elastic_pool* lp, int32_t n, const int32_t* src,
           pairs.dst[pairs.n] = slot(dst[i]);
           ++pairs.n;
         }
-        if ((rc = pie::launch_swap_copy(lp->pool->d_kv, lp->pool->d_kv, bb, pairs, 32, cs))) return rc;
+        if ((rc = pie::launch_swap_copy(lp->pool->d_kv, lp->pool->d_kv, bb, pairs, 32, cs, 25604))) return rc;
       }
       PIE_HIP(hipEventRecord(lp->ev_layer[j], cs));                  // a later swap-out of the layer waits for this
       lp->ev_layer_rec[j] = 1;

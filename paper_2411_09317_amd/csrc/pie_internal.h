@@ -141,7 +141,8 @@ struct pie_pool {
   // options
   int32_t swap_path = PIE_SWAP_AUTO;
   int32_t attn_partition = 512;   // tokens per work item (one workgroup)
-  int32_t swap_wgs = 64;          // workgroups of the gather / scatter kernel
+  int32_t swap_wgs = 16;          // workgroups of the gather / scatter kernel
+  int32_t swap_shape = 0;         // its threads per workgroup * 100 + loads in flight per lane; 0: by transfer size
   float layer_compute_us = 0.f;   // stand-in for the rest of a layer's compute in pie_step (0 = none)
   int32_t wall_clock_khz = 100000;
   int32_t timing = 0;             // PIE_TIMING_*
@@ -189,7 +190,7 @@ int launch_map_fill(int32_t* d_map, int32_t n, int32_t value, hipStream_t s);
 int launch_map_patch(int32_t* d_map, const MapPatch& patch, hipStream_t s);
 int launch_zero_u32(uint32_t* d, int32_t n, hipStream_t s);
 int launch_swap_copy(char* dst_layer_base, const char* src_layer_base, size_t block_bytes, const SwapPairs& pairs,
-                     int n_wgs, hipStream_t s);
+                     int n_wgs, hipStream_t s, int shape = 0, size_t transfer_bytes = 0);
 // which tail blocks an append launch writes (a tail block is GPU-homed, staged for the layer, or neither)
 constexpr int32_t kAppendPresent = 0;     // GPU-homed or staged; neither raises NOT_PRESENT
 constexpr int32_t kAppendGpuStrict = 1;   // GPU-homed; anything else raises NOT_PRESENT (the layer's region is not valid)

@@ -160,51 +160,82 @@ int launch_map_patch(int32_t* d_map, const MapPatch& patch, hipStream_t s) {
 //
 // Copies pairs.n blocks of block_bytes each: dst_base + dst[i]*block_bytes <- src_base + src[i]*block_bytes.
 // Either side may be pinned host memory mapped into the device's address space, so the kernel is bound by
-// the host link: what matters is the number of 16-byte requests in flight, not the number of CUs.  A fixed,
-// small grid strides over 4 KiB pieces; each lane keeps four loads in flight.
+// the host link: what matters is the number of 16-byte requests in flight, not the number of CUs (one compute
+// unit sustains about 3.5 GB/s per wavefront with sixteen loads in flight, at most about 14 GB/s).  A fixed,
+// small grid strides over pieces of THREADS x UNROLL 16-byte vectors; each lane keeps UNROLL loads in flight.
 // ---------------------------------------------------------------------------------------------------
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int kSwapThreads = 256;
-constexpr int kSwapUnroll = 4;
-constexpr size_t kSwapPiece = (size_t)kSwapThreads * 16 * kSwapUnroll;  // 16 KiB per workgroup iteration
-
-__global__ __launch_bounds__(kSwapThreads) void k_swap_copy(char* __restrict__ dst_base,
-                                                            const char* __restrict__ src_base, size_t block_bytes,
-                                                            const SwapPairs pairs) {
-  const size_t pieces_per_block = (block_bytes + kSwapPiece - 1) / kSwapPiece;
+template <int THREADS, int UNROLL>
+__global__ __launch_bounds__(THREADS) void k_swap_copy(char* __restrict__ dst_base, const char* __restrict__ src_base,
+                                                       size_t block_bytes, const SwapPairs pairs) {
+  constexpr size_t kPiece = (size_t)THREADS * 16 * UNROLL;        // bytes per workgroup iteration
+  // few instructions, long waits: let them issue ahead of the decode kernel's waves on the same compute unit
+  __builtin_amdgcn_s_setprio(3);
+  const size_t pieces_per_block = (block_bytes + kPiece - 1) / kPiece;
   const size_t n_pieces = pieces_per_block * (size_t)pairs.n;
   for (size_t piece = blockIdx.x; piece < n_pieces; piece += gridDim.x) {
     const int32_t i = (int32_t)(piece / pieces_per_block);
-    const size_t off = (piece % pieces_per_block) * kSwapPiece;
+    const size_t off = (piece % pieces_per_block) * kPiece;
     const u32x4* s = reinterpret_cast<const u32x4*>(src_base + (size_t)pairs.src[i] * block_bytes + off);
     u32x4* d = reinterpret_cast<u32x4*>(dst_base + (size_t)pairs.dst[i] * block_bytes + off);
-    const size_t n16 = (block_bytes - off < kSwapPiece ? block_bytes - off : kSwapPiece) / 16;
-    u32x4 v[kSwapUnroll];
+    const size_t n16 = (block_bytes - off < kPiece ? block_bytes - off : kPiece) / 16;
+    u32x4 v[UNROLL];
 #pragma unroll
-    for (int u = 0; u < kSwapUnroll; ++u) {
-      const size_t j = (size_t)u * kSwapThreads + threadIdx.x;
+    for (int u = 0; u < UNROLL; ++u) {
+      const size_t j = (size_t)u * THREADS + threadIdx.x;
       if (j < n16) v[u] = __builtin_nontemporal_load(s + j);
     }
 #pragma unroll
-    for (int u = 0; u < kSwapUnroll; ++u) {
-      const size_t j = (size_t)u * kSwapThreads + threadIdx.x;
+    for (int u = 0; u < UNROLL; ++u) {
+      const size_t j = (size_t)u * THREADS + threadIdx.x;
       if (j < n16) __builtin_nontemporal_store(v[u], d + j);
     }
   }
 }
 
-int launch_swap_copy(char* dst_layer_base, const char* src_layer_base, size_t block_bytes, const SwapPairs& pairs,
-                     int n_wgs, hipStream_t s) {
-  if (pairs.n <= 0) return PIE_OK;
-  if (block_bytes % 16) return PIE_EINVAL;
-  const size_t pieces = ((block_bytes + kSwapPiece - 1) / kSwapPiece) * (size_t)pairs.n;
+template <int THREADS, int UNROLL>
+static int launch_swap_copy_as(char* dst_layer_base, const char* src_layer_base, size_t block_bytes,
+                               const SwapPairs& pairs, int n_wgs, hipStream_t s) {
+  constexpr size_t kPiece = (size_t)THREADS * 16 * UNROLL;
+  const size_t pieces = ((block_bytes + kPiece - 1) / kPiece) * (size_t)pairs.n;
   const int grid = (int)(pieces < (size_t)n_wgs ? pieces : (size_t)n_wgs);
-  hipLaunchKernelGGL(k_swap_copy, dim3(grid), dim3(kSwapThreads), 0, s, dst_layer_base, src_layer_base, block_bytes,
-                     pairs);
+  hipLaunchKernelGGL((k_swap_copy<THREADS, UNROLL>), dim3(grid), dim3(THREADS), 0, s, dst_layer_base, src_layer_base,
+                     block_bytes, pairs);
   PIE_HIP(hipGetLastError());
   return PIE_OK;
+}
+
+// shape: threads per workgroup x 16-byte loads in flight per lane, as threads * 100 + loads; 0 = chosen here
+// from the size of the transfer.  What was measured beside the decode kernel of the 7B-shaped workload
+// (265 us per layer, every compute unit streaming from HBM):
+//  - While the decode kernel runs, a gather wave's requests queue behind the decode waves' in the compute
+//    unit's memory pipeline and the link rate is set by the number of gather waves, whatever each has in
+//    flight: 64 waves move about 28 GB/s, 128 about 45 GB/s; the decode kernel slows by 2-3 %.
+//  - A gather that outlasts the layer runs alone part of the time and then reaches 40-55 GB/s with few waves,
+//    but at full speed it costs the decode kernel next to it more: workgroups of 256 threads, 8 / 16 / 64 of
+//    them: +4-5 % / +15 % / +110 %; one-wave workgroups with sixteen loads in flight, which fit beside the
+//    decode kernel's resident workgroups instead of displacing one, 12 / 16 of them: +1-2 % / +2-3 % at
+//    39 / 41 GB/s.
+// So a transfer small enough to hide behind a layer is moved by n_wgs workgroups of 256 threads (it must finish
+// before the layer does), and a larger one, for which the layer will wait in any case, by n_wgs one-wave
+// workgroups (it must not slow the layers it runs beside).
+constexpr size_t kGatherSmallBytes = (size_t)12 << 20;
+
+int launch_swap_copy(char* dst_layer_base, const char* src_layer_base, size_t block_bytes, const SwapPairs& pairs,
+                     int n_wgs, hipStream_t s, int shape, size_t transfer_bytes) {
+  if (pairs.n <= 0) return PIE_OK;
+  if (block_bytes % 16 || n_wgs < 1) return PIE_EINVAL;
+  if (shape == 0) shape = (transfer_bytes ? transfer_bytes : block_bytes * pairs.n) <= kGatherSmallBytes ? 25604 : 6416;
+  switch (shape) {
+    case 6404: return launch_swap_copy_as<64, 4>(dst_layer_base, src_layer_base, block_bytes, pairs, n_wgs, s);
+    case 6416: return launch_swap_copy_as<64, 16>(dst_layer_base, src_layer_base, block_bytes, pairs, n_wgs, s);
+    case 25602: return launch_swap_copy_as<256, 2>(dst_layer_base, src_layer_base, block_bytes, pairs, n_wgs, s);
+    case 25604: return launch_swap_copy_as<256, 4>(dst_layer_base, src_layer_base, block_bytes, pairs, n_wgs, s);
+    case 102416: return launch_swap_copy_as<1024, 16>(dst_layer_base, src_layer_base, block_bytes, pairs, n_wgs, s);
+    default: return PIE_EINVAL;
+  }
 }
 
 // ---------------------------------------------------------------------------------------------------

@@ -154,10 +154,14 @@ static CopyPlan plan_copy(const pie_pool* p, const std::vector<int32_t>& src, co
       cp.runs.push_back({src[i], dst[i], 1});
   }
   cp.path = p->swap_path;
-  if (cp.path == PIE_SWAP_AUTO) {
-    // the copy engine pays a fixed cost per call; use it when runs are long on average
-    const size_t avg_bytes = n ? n * p->block_bytes / cp.runs.size() : 0;
-    cp.path = (cp.runs.size() <= 64 && avg_bytes >= ((size_t)1 << 20)) ? PIE_SWAP_DMA : PIE_SWAP_KERNEL;
+  if (cp.path == PIE_SWAP_AUTO && n) {
+    // Measured on this machine: a copy-engine transfer costs about 16 us per call and then moves 56 GB/s with
+    // no compute unit involved; the gather kernel moves about 2.6 GB/s per workgroup, 41 GB/s at most, after
+    // about 12 us.  The copy engine is taken unless the kernel is clearly faster for this list.
+    const double bytes = (double)n * (double)p->block_bytes;
+    const double dma_us = 16.0 * (double)cp.runs.size() + bytes / 56.0e3;
+    const double kernel_us = 12.0 + bytes / (std::min(41.0, 2.6 * p->swap_wgs) * 1.0e3);
+    cp.path = dma_us <= 1.1 * kernel_us ? PIE_SWAP_DMA : PIE_SWAP_KERNEL;
   }
   return cp;
 }
@@ -191,7 +195,8 @@ static int copy_blocks(pie_pool* p, int kind, int32_t layer, const std::vector<i
       ++pairs.n;
       ++i;
     }
-    int rc = launch_swap_copy(dst_base, src_base, p->block_bytes, pairs, p->swap_wgs, s);
+    int rc = launch_swap_copy(dst_base, src_base, p->block_bytes, pairs, p->swap_wgs, s, p->swap_shape,
+                              n * p->block_bytes);
     if (rc) return rc;
   }
   return PIE_OK;
@@ -418,6 +423,7 @@ int pie_pool_init(const pie_config* cfg, void* d_base, size_t d_bytes, void* h_p
   p->h_kv = (char*)h_pinned_base;
   // tuning hooks for experiments; the defaults are what the benchmarks use
   if (const char* e = std::getenv("PIE_ATTN_PART")) { const int v = std::atoi(e); if (v > 0) p->attn_partition = v; }
+  if (const char* e = std::getenv("PIE_SWAP_SHAPE")) { const int v = std::atoi(e); if (v > 0) p->swap_shape = v; }
   if (device) {
     char* base = (char*)d_base;
     p->d_kv = base;
