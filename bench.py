@@ -186,6 +186,29 @@ def fixed_fraction_leg(w, dw, streams, f, n_steps, base_kernel_ms, base_step_ms,
     return {k: m[k] for k in keep}
 
 
+def host_time_in_step(dw, streams, pf, dirty, n=10):
+    """How long the caller's thread spends inside pie_step, when it enqueues the step itself (on the copy-engine
+    path it then paces the GPU) and when the pool's own thread does (pie_set_async_submit); and the step time
+    with the latter."""
+    import torch
+    res = {}
+    for name, on in (("caller_enqueues_ms", False), ("async_submit_ms", True)):
+        dw.pool.set_async_submit(on)
+        timed_steps(dw, streams, 2, pf, dirty)
+        ts = []
+        for _ in range(n):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            dw.pool.step(dw.q, dw.k_new, dw.v_new, dw.d_table, dw.d_ctx, pf, dirty, dw.out, *streams)
+            ts.append((time.perf_counter() - t0) * 1e3)
+            dw.pool.sync()
+        res[name] = float(np.median(ts))
+        if on:
+            res["ms_per_step_async_submit"] = timed_steps(dw, streams, n, pf, dirty) / n * 1e3
+    dw.pool.set_async_submit(False)
+    return res
+
+
 def scattered_kernel_leg(w, dw, streams, f_small, f_link, base_kernel_ms, base_step_ms, achieved):
     """The gather kernel on a host pool full of holes: twice the blocks go to the host and every other one comes
     back, so a layer's prefetch is as many pieces as blocks and the copy engine would pay its per-call cost for
@@ -728,11 +751,16 @@ def main():
                    # where each part of the named metric ("decode tokens/s & HBM GB/s at X% host-resident KV;
                    # per-layer latency inflation") is in this line
                    "metric_parts": {"decode tokens/s": "value (0 % host-resident), swap.tokens_per_s, "
-                                                       "swap_below_knee.tokens_per_s",
-                                    "HBM GB/s": "roofline.achieved",
-                                    "X% host-resident": "swap.host_fraction, swap_below_knee.host_fraction",
-                                    "per-layer latency inflation": "swap.inflation_kernel / inflation_e2e, "
-                                                                   "swap_below_knee.inflation_kernel / inflation_e2e"}},
+                                                       "swap_below_knee.tokens_per_s, swap_kernel.*.tokens_per_s, "
+                                                       "cfg4.fixed_fraction[].tokens_per_s, cfg5.*.tokens_per_s",
+                                    "HBM GB/s": "roofline.achieved, cfg4.roofline.achieved, cfg5.roofline.achieved",
+                                    "X% host-resident": "swap.host_fraction, swap_below_knee.host_fraction, "
+                                                        "cfg4.fixed_fraction[].host_fraction, "
+                                                        "cfg5.overflow_on_host.host_fraction",
+                                    "per-layer latency inflation": "inflation_kernel (the attention kernel's own "
+                                                                   "slowdown) and inflation_e2e (step time, waits "
+                                                                   "included) in swap, swap_below_knee, swap_kernel.*, "
+                                                                   "cfg4.fixed_fraction[], cfg5.overflow_on_host"}},
         "roofline": {"bound": "hbm", "kernel": "k_attn_decode_mfma", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic_from_profile(f"attn_decode_{w.name}_pmc.txt")[0],
@@ -771,6 +799,8 @@ def main():
         # the same path below the link's knee: what the swaps cost when every transfer hides behind a layer
         result["swap_below_knee"] = fixed_fraction_leg(w, dw, streams, args.below_knee_fraction, 10, base_kernel_ms,
                                                        base_step_ms, achieved)
+        result["swap_below_knee"]["host_time_in_pie_step"] = host_time_in_step(
+            dw, streams, *dw.pool.prefetch_list(dw.table, dw.ctx_lens))
         dw.pool.set_host_fraction(0.0, dw.order, streams[1])
         dw.pool.sync()
         # and through the gather kernel, on a host pool full of holes

@@ -24,7 +24,9 @@
  *   - No function waits for the GPU unless its name ends in _sync, with one exception: a swap or migration
  *     that goes through the copy engine (PIE_SWAP_DMA, or PIE_SWAP_AUTO choosing it) waits on the host for
  *     the work the copy must follow (the staging region's last reader and write-back), and then enqueues
- *     the copy.  pie_step therefore paces the host one layer behind the GPU on that path.
+ *     the copy; this runtime gives the best overlap that way.  pie_step therefore paces the host one layer
+ *     behind the GPU on that path - unless the pool submits asynchronously (pie_set_async_submit): pie_step then
+ *     returns at once and a thread of the pool's own does the enqueuing and the waiting.
  *   - Ownership: the caller allocates the device buffer, the pinned host buffer
  *     and the streams, and frees them after pie_pool_destroy.  The library
  *     allocates no device memory at any time.
@@ -278,6 +280,24 @@ int pie_step(pie_pool* pool, const void* d_q_all, const void* d_k_new, const voi
 int pie_prefetch_list(pie_pool* pool, const int32_t* h_block_table, int32_t max_blocks,
                       const int32_t* h_ctx_lens, int32_t batch,
                       int32_t* out_prefetch, int32_t* out_n_prefetch, int32_t* out_dirty, int32_t* out_n_dirty);
+
+/* Asynchronous submission.  With on != 0, pie_step checks its arguments, copies the two handle lists, hands the
+ * step to a thread that belongs to the pool and returns (a few microseconds); the thread enqueues the step
+ * exactly as pie_step would have, in the order the steps were given.  For callers whose host thread has other
+ * work between steps (scheduling the next iteration), above all on the copy-engine path, where enqueuing a step
+ * takes as long as the step.  What changes for the caller:
+ *   - the step's work appears on the three streams as the thread gets to it, so work the caller itself puts on
+ *     those streams right after pie_step is not ordered after the step; pie_step_join_sync (below) returns when
+ *     everything handed over has been enqueued, and from then on stream order holds as usual;
+ *   - every other call on the pool (pie_pool_sync included) first waits for the thread to run dry, so calls that
+ *     change residency between steps cannot overtake a step;
+ *   - an error the thread meets while enqueuing (PIE_EHIP) is returned by the next call that waits for it.
+ * Device and host arguments of a step must stay valid until it has run, as always.  Off by default. */
+int pie_set_async_submit(pie_pool* pool, int32_t on);
+
+/* Waits until every step handed to the pool's thread has been enqueued (not: has run), and returns the first
+ * error met on the way.  Returns at once when asynchronous submission was never switched on. */
+int pie_step_join_sync(pie_pool* pool);
 
 /* pie_step ends by bringing layer 0's host blocks in again, behind its last layer, for the step that follows
  * (the paper's swapping runs around the layer loop, token after token: Section 3.3's worked example); the

@@ -30,7 +30,7 @@ SYMBOLS = [
     "pie_migrate", "pie_set_host_fraction", "pie_set_swap_path", "pie_set_attn_partition", "pie_set_swap_workgroups",
     "pie_set_layer_compute_us",
     "pie_kv_append", "pie_attn_decode", "pie_attn_decode_static", "pie_attn_stream_probe_sync",
-    "pie_step", "pie_prefetch_list", "pie_set_timing", "pie_set_cross_step_prefetch", "pie_set_host_presence_check", "pie_pool_sync", "pie_get_stats", "pie_get_layer_times",
+    "pie_step", "pie_set_async_submit", "pie_step_join_sync", "pie_prefetch_list", "pie_set_timing", "pie_set_cross_step_prefetch", "pie_set_host_presence_check", "pie_pool_sync", "pie_get_stats", "pie_get_layer_times",
     "pie_check_errors_sync", "pie_controller_create", "pie_controller_destroy", "pie_controller_config",
     "pie_controller_observe", "pie_controller_level", "pie_controller_update", "pie_last_hip_error", "pie_strerror",
     "pie_version",
@@ -285,6 +285,13 @@ class Pool:
                              _stream_ptr(swap_out_stream)), "step")
 
     # ---- control ---------------------------------------------------------------------------
+    def set_async_submit(self, on: bool):
+        """Steps are enqueued by a thread of the pool's own; step() returns at once."""
+        _check(_lib.pie_set_async_submit(self._h, C.c_int32(1 if on else 0)), "set_async_submit")
+
+    def step_join(self):
+        _check(_lib.pie_step_join_sync(self._h), "step_join_sync")
+
     def set_cross_step_prefetch(self, on: bool):
         _check(_lib.pie_set_cross_step_prefetch(self._h, C.c_int32(1 if on else 0)), "set_cross_step_prefetch")
 

@@ -3,8 +3,12 @@
 
 #include <hip/hip_runtime.h>
 
+#include <condition_variable>
 #include <cstdint>
+#include <deque>
+#include <mutex>
 #include <set>
+#include <thread>
 #include <vector>
 
 #include "pie.h"
@@ -82,6 +86,20 @@ struct AttnWork {
   int32_t lay_batch, lay_max_blocks;
 };
 
+// One pie_step call, as handed to the pool's submit thread.
+struct StepJob {
+  const void* d_q_all;
+  const void* d_k_new;
+  const void* d_v_new;
+  const int32_t* d_block_table;
+  int32_t max_blocks;
+  const int32_t* d_ctx_lens;
+  int32_t batch;
+  std::vector<int32_t> prefetch, dirty;
+  void* d_out_all;
+  hipStream_t cs, is, os;
+};
+
 struct SwapPairs {  // by-value kernel argument
   int32_t n;
   int32_t src[kSwapPairs];
@@ -153,6 +171,7 @@ struct pie_pool {
   hipEvent_t ev_step_start = nullptr;
   int32_t step_timed = 0;         // the timing mode the last step ran with
   bool in_on_host[2] = {false, false};   // the region's last swap-in was ordered on the host (copy-engine path)
+  bool dma_stream_order = false;         // copy-engine transfers ordered by stream waits instead of on the host
   bool presence_poll = true;             // look for a swap-in's completion from the host before waiting on the stream
   // the first layer's blocks staged ahead, behind the previous step's last layer
   bool cross_step_prefetch = true;
@@ -163,11 +182,24 @@ struct pie_pool {
   int32_t pre_idx = 0, step_pre_idx = 0;
   hipEvent_t ev_pre_end[2] = {nullptr, nullptr};
   uint64_t bytes_in = 0, bytes_out = 0;
+
+  // Asynchronous submission: pie_step hands the step to a thread of the pool's own, which enqueues it (and does
+  // the waiting the copy-engine path needs).  Everything but the job queue is touched by one thread at a time:
+  // the caller's thread drains the queue before any other call on the pool.
+  int device_id = 0;
+  bool async_submit = false;
+  std::thread submitter;
+  std::mutex submit_mutex;
+  std::condition_variable submit_wake, submit_idle;
+  std::deque<pie::StepJob> submit_jobs;
+  bool submit_busy = false, submit_stop = false;
+  int submit_rc = 0, submit_hip = 0;          // first error of a step enqueued by the thread, until reported
 };
 
 namespace pie {
 
 // host-side pieces used across files
+int submit_drain(pie_pool* p);          // waits for the submit thread to run dry; returns (and clears) its first error
 int note_stream(pie_pool* p, hipStream_t s);
 int flush_map(pie_pool* p, hipStream_t s);
 void map_set(pie_pool* p, int region, int32_t handle, int32_t slot);

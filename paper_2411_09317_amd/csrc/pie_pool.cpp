@@ -74,6 +74,49 @@ int note_stream(pie_pool* p, hipStream_t s) {
   return PIE_OK;
 }
 
+// ---- the submit thread ------------------------------------------------------------------------------------
+static int step_body(pie_pool* p, const StepJob& j);
+
+static void submit_loop(pie_pool* p) {
+  (void)hipSetDevice(p->device_id);
+  std::unique_lock<std::mutex> lock(p->submit_mutex);
+  for (;;) {
+    p->submit_wake.wait(lock, [p] { return p->submit_stop || !p->submit_jobs.empty(); });
+    if (p->submit_jobs.empty()) return;                       // asked to stop, nothing left
+    StepJob job = std::move(p->submit_jobs.front());
+    p->submit_jobs.pop_front();
+    p->submit_busy = true;
+    lock.unlock();
+    g_last_hip_error = 0;
+    const int rc = step_body(p, job);
+    lock.lock();
+    if (rc && !p->submit_rc) {
+      p->submit_rc = rc;
+      p->submit_hip = g_last_hip_error;
+    }
+    p->submit_busy = false;
+    if (p->submit_jobs.empty()) p->submit_idle.notify_all();
+  }
+}
+
+int submit_drain(pie_pool* p) {
+  if (!p->submitter.joinable()) return PIE_OK;
+  std::unique_lock<std::mutex> lock(p->submit_mutex);
+  p->submit_idle.wait(lock, [p] { return p->submit_jobs.empty() && !p->submit_busy; });
+  const int rc = p->submit_rc;
+  if (rc) g_last_hip_error = p->submit_hip;
+  p->submit_rc = p->submit_hip = 0;
+  return rc;
+}
+
+// Every call but pie_step first lets the submit thread finish what it was given: one thread at a time touches
+// the pool's state.
+#define PIE_DRAIN(p)                       \
+  do {                                     \
+    const int drc_ = submit_drain(p);      \
+    if (drc_) return drc_;                 \
+  } while (0)
+
 void map_set(pie_pool* p, int region, int32_t handle, int32_t slot) {
   if (p->map_mirror[region][handle] == slot) return;
   p->map_mirror[region][handle] = slot;
@@ -288,7 +331,7 @@ static int swap_in_impl(pie_pool* p, int32_t layer, int32_t n, const int32_t* ha
   const CopyPlan cp = plan_copy(p, src, dst);
   // (also when the copy itself is skipped: a wait enqueued on this stream would make the copy-engine
   // transfers that follow on it block the host)
-  const bool on_host = n > 0 && cp.path == PIE_SWAP_DMA;
+  const bool on_host = n > 0 && cp.path == PIE_SWAP_DMA && !p->dma_stream_order;
   p->in_on_host[r] = on_host;
   // the region may still be read by compute or written back
   int rc;
@@ -329,7 +372,7 @@ static int swap_out_impl(pie_pool* p, int32_t layer, int32_t n, const int32_t* h
     dst[i] = p->home[handles[i]].slot;
   }
   const CopyPlan cp = plan_copy(p, src, dst);
-  const bool on_host = n > 0 && cp.path == PIE_SWAP_DMA;
+  const bool on_host = n > 0 && cp.path == PIE_SWAP_DMA && !p->dma_stream_order;
   if ((rc = order_after(s, p->ev_in[r], p->ev_in_rec[r], on_host))) return rc;
   if ((rc = order_after(s, p->ev_read[r], p->ev_read_rec[r], on_host))) return rc;
   if ((rc = note(t0, s))) return rc;
@@ -423,6 +466,7 @@ int pie_pool_init(const pie_config* cfg, void* d_base, size_t d_bytes, void* h_p
   p->h_kv = (char*)h_pinned_base;
   // tuning hooks for experiments; the defaults are what the benchmarks use
   if (const char* e = std::getenv("PIE_ATTN_PART")) { const int v = std::atoi(e); if (v > 0) p->attn_partition = v; }
+  if (const char* e = std::getenv("PIE_DMA_STREAM_ORDER")) p->dma_stream_order = std::atoi(e) != 0;
   if (const char* e = std::getenv("PIE_SWAP_SHAPE")) { const int v = std::atoi(e); if (v > 0) p->swap_shape = v; }
   if (device) {
     char* base = (char*)d_base;
@@ -437,6 +481,7 @@ int pie_pool_init(const pie_config* cfg, void* d_base, size_t d_bytes, void* h_p
     int rc = PIE_OK;
     {
       int dev = 0, n_cu = 0;
+      if (hipGetDevice(&dev) == hipSuccess) p->device_id = dev;
       if (hipGetDevice(&dev) == hipSuccess &&
           hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n_cu > 0)
         p->n_cu = n_cu;
@@ -495,6 +540,7 @@ int pie_pool_init(const pie_config* cfg, void* d_base, size_t d_bytes, void* h_p
 
 int pie_pool_sync(pie_pool* p) {
   if (!p) return PIE_EINVAL;
+  PIE_DRAIN(p);
   if (!p->device) return PIE_OK;
   for (hipStream_t s : p->streams_seen) PIE_HIP(hipStreamSynchronize(s));
   return PIE_OK;
@@ -502,6 +548,15 @@ int pie_pool_sync(pie_pool* p) {
 
 int pie_pool_destroy(pie_pool* p) {
   if (!p) return PIE_EINVAL;
+  if (p->submitter.joinable()) {
+    (void)submit_drain(p);
+    {
+      std::lock_guard<std::mutex> g(p->submit_mutex);
+      p->submit_stop = true;
+    }
+    p->submit_wake.notify_all();
+    p->submitter.join();
+  }
   if (p->device) {
     for (hipStream_t s : p->streams_seen) (void)hipStreamSynchronize(s);
     hipEvent_t evs[] = {p->ev_in[0], p->ev_in[1], p->ev_read[0], p->ev_read[1], p->ev_out[0], p->ev_out[1],
@@ -522,6 +577,7 @@ int pie_pool_destroy(pie_pool* p) {
 int pie_block_alloc(pie_pool* p, int32_t where, int32_t n, int32_t* out_handles) {
   if (!p || (where != PIE_WHERE_GPU && where != PIE_WHERE_HOST) || n < 0 || (n > 0 && !out_handles))
     return PIE_EINVAL;
+  PIE_DRAIN(p);
   if ((size_t)n > p->free_slots[where].size() || (size_t)n > p->free_handles.size()) return PIE_ENOMEM;
   for (int32_t i = 0; i < n; ++i) {
     const int32_t h = *p->free_handles.begin();
@@ -540,6 +596,7 @@ int pie_block_alloc(pie_pool* p, int32_t where, int32_t n, int32_t* out_handles)
 
 int pie_block_free(pie_pool* p, int32_t n, const int32_t* handles) {
   if (!p) return PIE_EINVAL;
+  PIE_DRAIN(p);
   std::vector<uint8_t> seen;
   int rc = check_handles(p, n, handles, -1, seen);
   if (rc) return rc;
@@ -572,6 +629,7 @@ int pie_block_staged(pie_pool* p, int32_t region, int32_t n, const int32_t* hand
                      int32_t* out_state) {
   if (!p || (region != 0 && region != 1) || n < 0 || (n > 0 && (!handles || !out_stage_slot || !out_state)))
     return PIE_EINVAL;
+  PIE_DRAIN(p);
   for (int32_t i = 0; i < n; ++i)
     if (handles[i] < 0 || handles[i] >= p->n_handles) return PIE_EINVAL;
   bool done = true;
@@ -617,16 +675,19 @@ int pie_block_address(pie_pool* p, int32_t where, int32_t layer, int32_t slot, v
 
 int pie_swap_in(pie_pool* p, int32_t layer, int32_t n, const int32_t* handles, void* stream) {
   if (!p) return PIE_EINVAL;
+  PIE_DRAIN(p);
   return swap_in_impl(p, layer, n, handles, (hipStream_t)stream, false, Mark(), Mark());
 }
 
 int pie_swap_out(pie_pool* p, int32_t layer, int32_t n, const int32_t* handles, void* stream) {
   if (!p) return PIE_EINVAL;
+  PIE_DRAIN(p);
   return swap_out_impl(p, layer, n, handles, (hipStream_t)stream, Mark(), Mark());
 }
 
 int pie_migrate(pie_pool* p, int32_t n, const int32_t* handles, int32_t to_where, void* stream) {
   if (!p || (to_where != PIE_WHERE_GPU && to_where != PIE_WHERE_HOST)) return PIE_EINVAL;
+  PIE_DRAIN(p);
   std::vector<uint8_t> seen;
   int rc = check_handles(p, n, handles, -1, seen);
   if (rc) return rc;
@@ -658,7 +719,7 @@ int pie_migrate(pie_pool* p, int32_t n, const int32_t* handles, int32_t to_where
   p->n_in_use[to_where] += (int32_t)movers.size();
   if (p->device) {
     const CopyPlan cp = plan_copy(p, src, dst);
-    const bool on_host = cp.path == PIE_SWAP_DMA;
+    const bool on_host = cp.path == PIE_SWAP_DMA && !p->dma_stream_order;
     note_stream(p, s);
     if ((rc = order_after(s, p->ev_compute, p->ev_compute_rec, on_host))) return rc;
     // an earlier migration, possibly on another stream, may still be reading a slot this one is given
@@ -678,6 +739,7 @@ int pie_migrate(pie_pool* p, int32_t n, const int32_t* handles, int32_t to_where
 int pie_set_host_fraction(pie_pool* p, float f, int32_t n, const int32_t* order, void* stream,
                           int32_t* out_n_host) {
   if (!p || !(f >= 0.f && f <= 1.f)) return PIE_EINVAL;
+  PIE_DRAIN(p);
   std::vector<uint8_t> seen;
   int rc = check_handles(p, n, order, -1, seen);
   if (rc) return rc;
@@ -699,24 +761,28 @@ int pie_set_host_fraction(pie_pool* p, float f, int32_t n, const int32_t* order,
 
 int pie_set_swap_path(pie_pool* p, int32_t path) {
   if (!p || path < PIE_SWAP_AUTO || path > PIE_SWAP_KERNEL) return PIE_EINVAL;
+  PIE_DRAIN(p);
   p->swap_path = path;
   return PIE_OK;
 }
 
 int pie_set_attn_partition(pie_pool* p, int32_t tokens) {
   if (!p || tokens <= 0) return PIE_EINVAL;
+  PIE_DRAIN(p);
   p->attn_partition = tokens;
   return PIE_OK;
 }
 
 int pie_set_layer_compute_us(pie_pool* p, float us) {
   if (!p || !(us >= 0.f) || us > 1.0e6f) return PIE_EINVAL;
+  PIE_DRAIN(p);
   p->layer_compute_us = us;
   return PIE_OK;
 }
 
 int pie_set_swap_workgroups(pie_pool* p, int32_t n) {
   if (!p || n < 1 || n > 1024) return PIE_EINVAL;
+  PIE_DRAIN(p);
   p->swap_wgs = n;
   return PIE_OK;
 }
@@ -724,6 +790,7 @@ int pie_set_swap_workgroups(pie_pool* p, int32_t n) {
 int pie_kv_append(pie_pool* p, int32_t layer, const void* d_k, const void* d_v, const int32_t* d_block_table,
                   int32_t max_blocks, const int32_t* d_ctx_lens, int32_t batch, void* stream) {
   if (!p) return PIE_EINVAL;
+  PIE_DRAIN(p);
   int rc = check_batch_args(p, layer, d_k, d_block_table, max_blocks, d_ctx_lens, batch);
   if (rc) return rc;
   if (batch > 0 && !d_v) return PIE_EINVAL;
@@ -759,6 +826,7 @@ static int attn_decode_impl(pie_pool* p, int32_t layer, const void* d_q, const i
 int pie_attn_decode(pie_pool* p, int32_t layer, const void* d_q, const int32_t* d_block_table, int32_t max_blocks,
                     const int32_t* d_ctx_lens, int32_t batch, void* d_out, void* stream) {
   if (!p) return PIE_EINVAL;
+  PIE_DRAIN(p);
   int rc = check_batch_args(p, layer, d_q, d_block_table, max_blocks, d_ctx_lens, batch);
   if (rc) return rc;
   if (batch > 0 && !d_out) return PIE_EINVAL;
@@ -771,6 +839,7 @@ int pie_attn_decode(pie_pool* p, int32_t layer, const void* d_q, const int32_t* 
 int pie_attn_decode_static(pie_pool* p, int32_t layer, const void* d_q, const int32_t* d_block_table,
                            int32_t max_blocks, const int32_t* d_ctx_lens, int32_t batch, void* d_out, void* stream) {
   if (!p) return PIE_EINVAL;
+  PIE_DRAIN(p);
   if (layer < 0 || layer >= p->cfg.n_layers || batch < 0 || max_blocks < 0) return PIE_EINVAL;
   if (batch > 0 && (!d_q || !d_block_table || !d_ctx_lens || !d_out)) return PIE_EINVAL;
   if (!p->device) return PIE_ESTATE;
@@ -787,6 +856,7 @@ static int elapsed(hipEvent_t a, hipEvent_t b, float* ms);
 int pie_attn_stream_probe_sync(pie_pool* p, int32_t layer, const int32_t* d_block_table, int32_t max_blocks,
                           const int32_t* d_ctx_lens, int32_t batch, void* stream, float* out_ms) {
   if (!p || !out_ms) return PIE_EINVAL;
+  PIE_DRAIN(p);
   *out_ms = 0.f;
   int rc = check_batch_args(p, layer, d_block_table, d_block_table, max_blocks, d_ctx_lens, batch);
   if (rc) return rc;
@@ -844,28 +914,24 @@ int pie_prefetch_list(pie_pool* p, const int32_t* h_block_table, int32_t max_blo
   return PIE_OK;
 }
 
-int pie_step(pie_pool* p, const void* d_q_all, const void* d_k_new, const void* d_v_new,
-             const int32_t* d_block_table, int32_t max_blocks, const int32_t* d_ctx_lens, int32_t batch,
-             int32_t n_prefetch, const int32_t* h_prefetch, int32_t n_dirty, const int32_t* h_dirty,
-             void* d_out_all, void* compute_stream, void* swap_in_stream, void* swap_out_stream) {
-  if (!p) return PIE_EINVAL;
-  int rc = check_batch_args(p, 0, d_q_all, d_block_table, max_blocks, d_ctx_lens, batch);
-  if (rc) return rc;
-  if (batch > 0 && !d_out_all) return PIE_EINVAL;
-  if ((d_k_new == nullptr) != (d_v_new == nullptr)) return PIE_EINVAL;
-  if (n_prefetch < 0 || n_dirty < 0) return PIE_EINVAL;
-  if (n_prefetch > p->cfg.n_stage_blocks) return PIE_ENOMEM;
-  std::vector<uint8_t> seen;
-  if ((rc = check_handles(p, n_prefetch, h_prefetch, PIE_WHERE_HOST, seen))) return rc;
-  {
-    std::vector<uint8_t> seen_d;
-    if ((rc = check_handles(p, n_dirty, h_dirty, PIE_WHERE_HOST, seen_d))) return rc;
-    for (int32_t i = 0; i < n_dirty; ++i)
-      if (!seen[h_dirty[i]]) return PIE_ESTATE;  // a dirty block must be among the prefetched ones
-  }
-  if (!p->device) return PIE_ESTATE;
-  if (batch == 0) return PIE_OK;
-  hipStream_t cs = (hipStream_t)compute_stream, is = (hipStream_t)swap_in_stream, os = (hipStream_t)swap_out_stream;
+}  // extern "C"
+
+namespace pie {
+
+// The step itself: everything pie_step enqueues, for arguments that have been checked.
+static int step_body(pie_pool* p, const StepJob& j) {
+  const void* d_q_all = j.d_q_all;
+  const void* d_k_new = j.d_k_new;
+  const void* d_v_new = j.d_v_new;
+  const int32_t* d_block_table = j.d_block_table;
+  const int32_t* d_ctx_lens = j.d_ctx_lens;
+  const int32_t max_blocks = j.max_blocks, batch = j.batch;
+  const int32_t n_prefetch = (int32_t)j.prefetch.size(), n_dirty = (int32_t)j.dirty.size();
+  const int32_t* h_prefetch = j.prefetch.data();
+  const int32_t* h_dirty = j.dirty.data();
+  void* d_out_all = j.d_out_all;
+  int rc;
+  hipStream_t cs = j.cs, is = j.is, os = j.os;
   const int32_t L = p->cfg.n_layers;
   const size_t q_stride = (size_t)batch * p->cfg.n_q_heads * p->cfg.head_dim * p->elem_bytes;
   const size_t kv_stride = (size_t)batch * p->cfg.n_kv_heads * p->cfg.head_dim * p->elem_bytes;
@@ -1012,8 +1078,66 @@ int pie_step(pie_pool* p, const void* d_q_all, const void* d_k_new, const void* 
   return PIE_OK;
 }
 
+}  // namespace pie
+
+extern "C" {
+
+int pie_step(pie_pool* p, const void* d_q_all, const void* d_k_new, const void* d_v_new,
+             const int32_t* d_block_table, int32_t max_blocks, const int32_t* d_ctx_lens, int32_t batch,
+             int32_t n_prefetch, const int32_t* h_prefetch, int32_t n_dirty, const int32_t* h_dirty,
+             void* d_out_all, void* compute_stream, void* swap_in_stream, void* swap_out_stream) {
+  if (!p) return PIE_EINVAL;
+  int rc = check_batch_args(p, 0, d_q_all, d_block_table, max_blocks, d_ctx_lens, batch);
+  if (rc) return rc;
+  if (batch > 0 && !d_out_all) return PIE_EINVAL;
+  if ((d_k_new == nullptr) != (d_v_new == nullptr)) return PIE_EINVAL;
+  if (n_prefetch < 0 || n_dirty < 0) return PIE_EINVAL;
+  if (n_prefetch > p->cfg.n_stage_blocks) return PIE_ENOMEM;
+  std::vector<uint8_t> seen;
+  if ((rc = check_handles(p, n_prefetch, h_prefetch, PIE_WHERE_HOST, seen))) return rc;
+  {
+    std::vector<uint8_t> seen_d;
+    if ((rc = check_handles(p, n_dirty, h_dirty, PIE_WHERE_HOST, seen_d))) return rc;
+    for (int32_t i = 0; i < n_dirty; ++i)
+      if (!seen[h_dirty[i]]) return PIE_ESTATE;  // a dirty block must be among the prefetched ones
+  }
+  if (!p->device) return PIE_ESTATE;
+  if (batch == 0) return PIE_OK;
+  StepJob job{d_q_all, d_k_new, d_v_new, d_block_table, max_blocks, d_ctx_lens, batch,
+              std::vector<int32_t>(h_prefetch, h_prefetch + n_prefetch), std::vector<int32_t>(h_dirty, h_dirty + n_dirty),
+              d_out_all, (hipStream_t)compute_stream, (hipStream_t)swap_in_stream, (hipStream_t)swap_out_stream};
+  if (!p->async_submit) return step_body(p, job);
+  {                                              // hand it to the submit thread and return
+    std::lock_guard<std::mutex> g(p->submit_mutex);
+    p->submit_jobs.push_back(std::move(job));
+  }
+  p->submit_wake.notify_one();
+  return PIE_OK;
+}
+
+int pie_set_async_submit(pie_pool* p, int32_t on) {
+  if (!p) return PIE_EINVAL;
+  PIE_DRAIN(p);
+  if (!p->device) return PIE_ESTATE;
+  if (on && !p->submitter.joinable()) {
+    try {
+      p->submitter = std::thread(submit_loop, p);
+    } catch (...) {
+      return PIE_ENOMEM;
+    }
+  }
+  p->async_submit = on != 0;
+  return PIE_OK;
+}
+
+int pie_step_join_sync(pie_pool* p) {
+  if (!p) return PIE_EINVAL;
+  return submit_drain(p);
+}
+
 int pie_set_cross_step_prefetch(pie_pool* p, int32_t on) {
   if (!p) return PIE_EINVAL;
+  PIE_DRAIN(p);
   p->cross_step_prefetch = on != 0;
   if (!on) p->pre_valid = false;
   return PIE_OK;
@@ -1021,12 +1145,14 @@ int pie_set_cross_step_prefetch(pie_pool* p, int32_t on) {
 
 int pie_set_host_presence_check(pie_pool* p, int32_t on) {
   if (!p) return PIE_EINVAL;
+  PIE_DRAIN(p);
   p->presence_poll = on != 0;
   return PIE_OK;
 }
 
 int pie_set_timing(pie_pool* p, int32_t mode) {
   if (!p || mode < PIE_TIMING_OFF || mode > PIE_TIMING_CLOCK) return PIE_EINVAL;
+  PIE_DRAIN(p);
   p->timing = mode;
   return PIE_OK;
 }
@@ -1090,6 +1216,7 @@ static int layer_times_from_clock(pie_pool* p, float* t_attn, float* t_kernel, f
 
 int pie_get_layer_times(pie_pool* p, float* t_attn, float* t_kernel, float* t_in, float* t_out, float* t_stall) {
   if (!p) return PIE_EINVAL;
+  PIE_DRAIN(p);
   if (!p->device || !p->step_timed) return PIE_ESTATE;
   if (p->step_timed == PIE_TIMING_CLOCK) return layer_times_from_clock(p, t_attn, t_kernel, t_in, t_out, t_stall, nullptr);
   const int32_t L = p->cfg.n_layers;
@@ -1132,6 +1259,7 @@ int pie_get_layer_times(pie_pool* p, float* t_attn, float* t_kernel, float* t_in
 
 int pie_get_stats(pie_pool* p, pie_stats* out) {
   if (!p || !out) return PIE_EINVAL;
+  PIE_DRAIN(p);
   std::memset(out, 0, sizeof(*out));
   out->n_layers = p->cfg.n_layers;
   out->host_blocks_in_use = p->n_in_use[1];
@@ -1166,6 +1294,7 @@ int pie_get_stats(pie_pool* p, pie_stats* out) {
 
 int pie_check_errors_sync(pie_pool* p, uint32_t* out_flags) {
   if (!p || !out_flags) return PIE_EINVAL;
+  PIE_DRAIN(p);
   *out_flags = 0;
   if (!p->device) return PIE_OK;
   int rc = pie_pool_sync(p);

@@ -48,6 +48,7 @@ static void part_step() {
     OK(pie_set_swap_path(p, (step / 3) % 3));
     OK(pie_set_cross_step_prefetch(p, (step / 9) % 2));
     OK(pie_set_host_presence_check(p, (step / 18) % 2));
+    OK(pie_set_async_submit(p, (step / 6) % 2));                      // every other six steps by the pool's own thread
     if (step % 10 == 5) { int32_t nh; OK(pie_set_host_fraction(p, 0.1f * (step / 10), (int32_t)all.size(), all.data(), is, &nh)); }
     if (step % 10 == 8) OK(pie_migrate(p, 3, all.data() + step % 5, (step / 10) % 2, is));
     HIP_OK(hipMemcpy(d_table, table.data(), table.size() * 4, hipMemcpyHostToDevice));
@@ -55,6 +56,13 @@ static void part_step() {
     int32_t npf, nd;
     OK(pie_prefetch_list(p, table.data(), MB, ctx.data(), B, pf.data(), &npf, dirty.data(), &nd));
     OK(pie_step(p, q, k, v, d_table, MB, d_ctx, B, npf, pf.data(), nd, dirty.data(), out, cs, is, os));
+    if (step % 4 == 1) {                                              // two in a row; the lists may go away at once
+      std::vector<int32_t> pf2(pf.begin(), pf.begin() + npf), dirty2(dirty.begin(), dirty.begin() + nd);
+      OK(pie_step(p, q, k, v, d_table, MB, d_ctx, B, npf, pf2.data(), nd, dirty2.data(), out, cs, is, os));
+      pf2.assign(pf2.size(), -7);
+      dirty2.assign(dirty2.size(), -7);
+      OK(pie_step_join_sync(p));
+    }
     OK(pie_pool_sync(p));
     if (step % 3) {
       pie_stats st; OK(pie_get_stats(p, &st));
@@ -73,6 +81,8 @@ static void part_step() {
   }
   uint32_t flags; OK(pie_check_errors_sync(p, &flags));
   if (flags) { printf("step part: device flags %u\n", flags); exit(4); }
+  OK(pie_set_async_submit(p, 1));                                     // destroyed with the thread alive and a step handed over
+  OK(pie_step(p, q, k, v, d_table, MB, d_ctx, B, npf, pf.data(), nd, dirty.data(), out, cs, is, os));
   OK(pie_block_free(p, (int32_t)all.size(), all.data()));
   OK(pie_controller_destroy(ctl));
   OK(pie_pool_destroy(p));

@@ -432,3 +432,55 @@ def test_gather_workgroups_and_host_presence_check_change_no_result():
         assert GH.rowwise_rel_err(outs[0][l], ref[l]) <= 2e-3
     for got, img in zip(outs[1:], images[1:]):
         assert np.array_equal(got, outs[0]) and np.array_equal(img, images[0])
+
+
+@pytest.mark.parametrize("path", PATHS)
+def test_asynchronous_submission_changes_no_result_and_frees_the_caller(path):
+    """pie_set_async_submit: steps handed to the pool's own thread give the bytes and outputs of steps enqueued by
+    the caller, in the order given; pie_step returns without waiting; argument errors are still returned by
+    pie_step itself; calls that change residency cannot overtake a step."""
+    import time
+    w = I.scaled(W, n_layers=6, batch=6)
+    case = host_tails(I.make_case(w))
+    n = int(case.n_blocks.sum())
+    streams = (torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream())
+    k_new, v_new = new_token_rows(case)
+    q = GH.to_dev(case.q, w.dtype)
+    dk, dv = GH.to_dev(k_new, w.dtype), GH.to_dev(v_new, w.dtype)
+    d_ctx = torch.from_numpy(case.ctx_lens).to(GH.DEV)
+    results = {}
+    for mode in ("caller", "thread"):
+        lib, mod, table = GH.make_pools(case, n, n, n, upto_ctx=case.ctx_lens - 1)
+        lib.set_swap_path(path)
+        lib.set_async_submit(mode == "thread")
+        d_table = torch.from_numpy(table).to(GH.DEV)
+        pf, dirty = lib.prefetch_list(table, case.ctx_lens)
+        outs = [torch.full_like(q, float("nan")) for _ in range(4)]
+        torch.cuda.synchronize()
+        host = []
+        for i in range(4):                                            # four steps in a row, nothing in between
+            t0 = time.perf_counter()
+            lib.step(q, dk, dv, d_table, d_ctx, pf, dirty, outs[i], *streams)
+            host.append(time.perf_counter() - t0)
+        if mode == "thread":
+            with pytest.raises(B.PieError) as e:                      # checked in the caller's thread, as ever
+                lib.step(q, dk, dv, d_table, d_ctx, pf[::-1].tolist() + [pf[0]], dirty, outs[0], *streams)
+            assert e.value.code == B.ESTATE
+            lib.step_join()                                           # everything is on the streams now
+        # a residency change right behind the steps: it must wait for them, and the last step's write-back
+        lib.migrate(pf[: len(pf) // 2], B.GPU, streams[1])
+        lib.sync()
+        torch.cuda.synchronize()
+        assert lib.check_errors() == 0
+        results[mode] = ([GH.from_dev(o, w.dtype) for o in outs], GH.images_of(lib), host)
+        lib.set_async_submit(False)
+        lib.close()
+    ref = [A.dense_attention(*H.dense_f64(case, l), case.ctx_lens) for l in range(w.n_layers)]
+    for l in range(w.n_layers):
+        assert GH.rowwise_rel_err(results["caller"][0][0][l], ref[l]) <= 2e-3
+    for a, b in zip(results["caller"][0], results["thread"][0]):
+        assert np.array_equal(a, b)
+    assert np.array_equal(results["caller"][1][0], results["thread"][1][0])          # device pool, staging included
+    assert np.array_equal(results["caller"][1][1], results["thread"][1][1])          # host pool
+    # handing a step over costs less than enqueuing it (a handful of list copies against dozens of launches)
+    assert np.median(results["thread"][2]) < np.median(results["caller"][2])
