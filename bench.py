@@ -85,6 +85,9 @@ def parse():
     ap.add_argument("--serve-levels", default="0,1,2,4,8", help="budget levels; one level = 1/64 of the GPU pool")
     ap.add_argument("--serve-load", type=float, default=0.8,
                     help="arrival rate of the latency legs as a share of the level-0 saturated request rate")
+    ap.add_argument("--link-sweep", action="store_true",
+                    help="experiment instead of the benchmark line: host-link rate against transfer size, copy engine and "
+                         "gather kernel, and the flavours of page-locked memory; prints its own JSON line")
     ap.add_argument("--calib-copy-mib", type=int, default=0,
                     help="also run a plain elementwise copy of this many MiB (a known-size reference for HBM counters)")
     return ap.parse_args()
@@ -545,6 +548,96 @@ def elastic_leg(w, dw, m, n_steps, t_other_us, base_step_ms, chunk_blocks=256):
     return res
 
 
+def link_sweep_mode(args):
+    """The host link against transfer size (the paper's Section 2.4 measurement on its machine: bandwidth against
+    access size, large accesses needed for the link's rate): single copy-engine transfers host to device and
+    device to host, 64 KiB to 1 GiB, and the gather / scatter kernel moving the same bytes as 64 KiB blocks,
+    alone on the GPU; then the 256 MiB point again for the flavours of page-locked memory hipHostMalloc offers,
+    given to the library as its host pool.  Prints its own JSON line."""
+    import ctypes
+    import torch
+    from paper_2411_09317_amd import binding as B
+    hip = ctypes.CDLL("libamdhip64.so.7")                          # the copy torch has loaded
+    hip.hipHostMalloc.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_size_t, ctypes.c_uint]
+    hip.hipHostFree.argtypes = [ctypes.c_void_p]
+    hip.hipMemcpyAsync.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p]
+    GiB = 1 << 30
+    blk = 64 << 10                                                 # 8 kv heads x 16 tokens x 128 dims x 2 bytes x (K, V)
+    sizes = [64 << 10, 256 << 10, 1 << 20, 4 << 20, 16 << 20, 64 << 20, 256 << 20, GiB]
+    stream = torch.cuda.Stream()
+    d_buf = torch.empty(GiB, dtype=torch.uint8, device="cuda:0")
+
+    def timed(fn, reps):
+        ts = []
+        for _ in range(reps + 1):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            fn()
+            e1.record(stream)
+            e1.synchronize()
+            ts.append(e0.elapsed_time(e1) * 1e-3)
+        return float(np.median(ts[1:]))                            # the first pass through fresh memory is slow
+
+    def copies(h_ptr, size, reps):
+        s = ctypes.c_void_p(stream.cuda_stream)
+        h2d = timed(lambda: hip.hipMemcpyAsync(ctypes.c_void_p(d_buf.data_ptr()), ctypes.c_void_p(h_ptr), size, 1, s), reps)
+        d2h = timed(lambda: hip.hipMemcpyAsync(ctypes.c_void_p(h_ptr), ctypes.c_void_p(d_buf.data_ptr()), size, 2, s), reps)
+        return size / h2d / 1e9, size / d2h / 1e9
+
+    def gather(h_ptr, n_blocks_total, points, reps):
+        """pie_swap_in / pie_swap_out of the first n blocks of a pool whose host pool is the given memory."""
+        pool = B.Pool(1, 32, 8, 128, 16, 2, 8, n_blocks_total, n_blocks_total, host_ptr=h_ptr, host_bytes=n_blocks_total * blk)
+        hs = np.asarray(pool.block_alloc(B.HOST, n_blocks_total), dtype=np.int32)
+        pool.set_swap_path(B.SWAP_KERNEL)
+        out = []
+        for size in points:
+            n = size // blk
+            t_in = timed(lambda: pool.swap_in(0, hs[:n], stream), reps)
+            t_out = timed(lambda: pool.swap_out(0, hs[:n], stream), reps)
+            out.append((size / t_in / 1e9, size / t_out / 1e9))
+        pool.sync()
+        pool.close()
+        return out
+
+    reps_of = lambda size: 20 if size <= (4 << 20) else (6 if size <= (64 << 20) else 3)
+    pinned = torch.empty(GiB, dtype=torch.uint8, pin_memory=True)
+    pinned.zero_()
+    rows = []
+    g = gather(pinned.data_ptr(), GiB // blk, sizes, 3)
+    for size, (gi, go) in zip(sizes, g):
+        h2d, d2h = copies(pinned.data_ptr(), size, reps_of(size))
+        rows.append({"bytes": size, "copy_engine_h2d_GBps": h2d, "copy_engine_d2h_GBps": d2h,
+                     "gather_kernel_h2d_GBps": gi, "scatter_kernel_d2h_GBps": go})
+        print(f"# {size >> 10:8d} KiB: copy engine {h2d:5.1f} / {d2h:5.1f} GB/s   kernel {gi:5.1f} / {go:5.1f} GB/s",
+              file=sys.stderr, flush=True)
+    big = rows[-1]["copy_engine_h2d_GBps"]
+    knee = next((r["bytes"] for r in rows if r["copy_engine_h2d_GBps"] >= 0.95 * big), None)
+    del pinned
+    flavours = []
+    size = 256 << 20
+    for name, flags in (("hipHostMallocDefault", 0x0), ("hipHostMallocCoherent", 0x40000000),
+                        ("hipHostMallocNonCoherent", 0x80000000), ("hipHostMallocWriteCombined", 0x4),
+                        ("hipHostMallocNumaUser", 0x20000000)):
+        ptr = ctypes.c_void_p(0)
+        rc = hip.hipHostMalloc(ctypes.byref(ptr), size, flags)
+        if rc != 0 or not ptr.value:
+            flavours.append({"flavour": name, "error": f"hipHostMalloc returned {rc}"})
+            continue
+        ctypes.memset(ptr, 0, size)
+        h2d, d2h = copies(ptr.value, size, 3)
+        (gi, go), = gather(ptr.value, size // blk, [size], 3)
+        flavours.append({"flavour": name, "bytes": size, "copy_engine_h2d_GBps": h2d, "copy_engine_d2h_GBps": d2h,
+                         "gather_kernel_h2d_GBps": gi, "scatter_kernel_d2h_GBps": go})
+        print(f"# {name}: copy engine {h2d:5.1f} / {d2h:5.1f} GB/s   kernel {gi:5.1f} / {go:5.1f} GB/s", file=sys.stderr, flush=True)
+        torch.cuda.synchronize()
+        hip.hipHostFree(ptr)
+    print(json.dumps({"experiment": "host link against transfer size", "link_peak_GBps_theoretical": LINK_PEAK_GBS,
+                      "memory": "torch pin_memory (hipHostMalloc default flags), 1 GiB", "sweep": rows,
+                      "bytes_for_95_percent_of_large_transfer_rate_h2d": knee,
+                      "gather_kernel": "library defaults, alone on the GPU, 64 KiB blocks in ascending slots",
+                      "pinned_memory_flavours_at_256MiB": flavours}))
+
+
 def serving_elastic_mode(args):
     """The same in the paper's own unit: whole layers move, the caches of the layers that stay grow, and the
     scheduler admits against the size the pool shows.  Fixed numbers of layers in CPU memory, then the
@@ -686,6 +779,8 @@ def main():
     from paper_2411_09317_amd import workload as WL
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
+    if args.link_sweep:
+        return link_sweep_mode(args)
     if args.serve:
         return serving_elastic_mode(args) if args.serve_elastic else serving_mode(args)
     w = I.CONFIGS[args.workload]

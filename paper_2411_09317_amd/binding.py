@@ -122,7 +122,10 @@ class Pool:
     """A KV pool over torch-owned memory.  device=None makes a bookkeeping-only pool (no GPU needed)."""
 
     def __init__(self, n_layers, n_q_heads, n_kv_heads, head_dim, block_tokens, dtype, n_gpu_blocks, n_stage_blocks,
-                 n_host_blocks, max_batch=1, max_blocks_per_seq=1, softmax_scale=0.0, device: Optional[str] = "cuda:0"):
+                 n_host_blocks, max_batch=1, max_blocks_per_seq=1, softmax_scale=0.0, device: Optional[str] = "cuda:0",
+                 host_ptr: int = 0, host_bytes: int = 0):
+        """host_ptr / host_bytes: page-locked host memory of the caller's own (e.g. hipHostMalloc with particular
+        flags) for the host pool instead of a torch pinned tensor; the caller keeps it alive and frees it."""
         self.cfg = PieConfig(n_layers, n_q_heads, n_kv_heads, head_dim, block_tokens, dtype, n_gpu_blocks,
                              n_stage_blocks, n_host_blocks, max_batch, max_blocks_per_seq, softmax_scale)
         self._h = C.c_void_p(0)
@@ -140,11 +143,12 @@ class Pool:
             off = (-self.d_buf.data_ptr()) % 256
             self._d_base = self.d_buf.data_ptr() + off
             self._d_off = off
-            if self.h_bytes:
+            if self.h_bytes and not host_ptr:
                 self.h_buf = torch.empty(self.h_bytes, dtype=torch.uint8, pin_memory=True)
-            h_ptr = self.h_buf.data_ptr() if self.h_buf is not None else 0
+            h_ptr = host_ptr or (self.h_buf.data_ptr() if self.h_buf is not None else 0)
             _check(_lib.pie_pool_init(C.byref(self.cfg), C.c_void_p(self._d_base), C.c_size_t(self.d_bytes),
-                                      C.c_void_p(h_ptr), C.c_size_t(self.h_bytes), C.byref(self._h)), "pool_init")
+                                      C.c_void_p(h_ptr), C.c_size_t(host_bytes if host_ptr else self.h_bytes),
+                                      C.byref(self._h)), "pool_init")
         else:
             _check(_lib.pie_pool_init(C.byref(self.cfg), C.c_void_p(0), C.c_size_t(0), C.c_void_p(0), C.c_size_t(0),
                                       C.byref(self._h)), "pool_init")
