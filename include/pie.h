@@ -86,7 +86,8 @@ typedef struct {
   int32_t n_kv_heads;        /* divides n_q_heads; 16-bit dtypes: n_q_heads / n_kv_heads <= 16 */
   int32_t head_dim;          /* 64 or 128 */
   int32_t block_tokens;      /* 16 */
-  int32_t dtype;             /* PIE_DTYPE_* */
+  int32_t dtype;             /* PIE_DTYPE_*; fp32 caches are served by a plain kernel that reads a kv head's K and V
+                                once per query head (G x the traffic with grouped queries): for validation, not speed */
   int32_t n_gpu_blocks;      /* resident slots per layer */
   int32_t n_stage_blocks;    /* slots per staging region (there are two) */
   int32_t n_host_blocks;     /* host slots per layer */
