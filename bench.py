@@ -45,6 +45,8 @@ def parse():
                     help="host-resident fraction of the second, short swap leg (below link rate / attention rate)")
     ap.add_argument("--swap-path", type=int, default=0)
     ap.add_argument("--swap-wgs", type=int, default=0, help="workgroups of the gather / scatter kernel (0 = library default)")
+    ap.add_argument("--attn-vector-alu", action="store_true",
+                    help="MHA workloads: the attention's products on the vector ALU instead of the matrix cores (A/B)")
     ap.add_argument("--no-swap", action="store_true")
     ap.add_argument("--no-extra", action="store_true",
                     help="leave out the compact legs of the 8B-shaped and 70B-shaped workloads (cfg4, cfg5) that the "
@@ -799,6 +801,8 @@ def main():
     if args.partition:
         dw.pool.set_attn_partition(args.partition)
     dw.pool.set_swap_path(args.swap_path)
+    if args.attn_vector_alu:
+        dw.pool.set_attn_vector_alu(True)
     if args.swap_wgs:
         dw.pool.set_swap_workgroups(args.swap_wgs)
     streams = (torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream())

@@ -194,6 +194,13 @@ int pie_set_swap_path(pie_pool* pool, int32_t path);
  * [256, 4096]); longer contexts are split and reduced.  Default 512. */
 int pie_set_attn_partition(pie_pool* pool, int32_t tokens);
 
+/* 16-bit caches with one query head per kv head (MHA): on != 0 computes the attention's two products on the
+ * vector ALU (two-element dot products, fp32 accumulation) instead of the matrix cores, where with a single query
+ * head they are matrix-vector products.  Same loads, same order, same softmax; results agree to rounding.  Off by
+ * default: on the 7B-shaped workload the kernel takes the same time either way (it is bound by HBM) and a step
+ * 0.7 % longer on the vector ALU.  PIE_ESTATE for grouped-query or fp32 pools. */
+int pie_set_attn_vector_alu(pie_pool* pool, int32_t on);
+
 /* Workgroups of the gather / scatter kernel (1..1024, default 16).  The kernel is bound by the host link, not
  * by compute.  A transfer of up to 12 MiB - one that can hide behind a layer - is moved by that many workgroups
  * of 256 threads (about 28 GB/s beside a running decode kernel, which slows by 2-3 %); a larger one by that many

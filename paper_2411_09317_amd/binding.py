@@ -28,7 +28,7 @@ SYMBOLS = [
     "pie_pool_bytes_required", "pie_pool_init", "pie_pool_destroy", "pie_block_alloc", "pie_block_free",
     "pie_block_where", "pie_block_staged", "pie_pool_free_count", "pie_block_address", "pie_swap_in", "pie_swap_out",
     "pie_migrate", "pie_set_host_fraction", "pie_set_swap_path", "pie_set_attn_partition", "pie_set_swap_workgroups",
-    "pie_set_layer_compute_us",
+    "pie_set_layer_compute_us", "pie_set_attn_vector_alu",
     "pie_kv_append", "pie_attn_decode", "pie_attn_decode_static", "pie_attn_stream_probe_sync",
     "pie_step", "pie_set_async_submit", "pie_step_join_sync", "pie_prefetch_list", "pie_set_timing", "pie_set_cross_step_prefetch", "pie_set_host_presence_check", "pie_pool_sync", "pie_get_stats", "pie_get_layer_times",
     "pie_check_errors_sync", "pie_controller_create", "pie_controller_destroy", "pie_controller_config",
@@ -238,6 +238,9 @@ class Pool:
 
     def set_swap_workgroups(self, n: int):
         _check(_lib.pie_set_swap_workgroups(self._h, C.c_int32(n)), "set_swap_workgroups")
+
+    def set_attn_vector_alu(self, on: bool):
+        _check(_lib.pie_set_attn_vector_alu(self._h, C.c_int32(1 if on else 0)), "set_attn_vector_alu")
 
     def set_layer_compute_us(self, us: float):
         _check(_lib.pie_set_layer_compute_us(self._h, C.c_float(us)), "set_layer_compute_us")

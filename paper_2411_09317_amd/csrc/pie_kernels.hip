@@ -509,6 +509,22 @@ template <> struct Mfma<BF16> {
   }
 };
 
+// Two-element dot products on the vector ALU (v_dot2_f32_f16 / v_dot2_f32_bf16): c + a.x b.x + a.y b.y with the
+// products and the sum in fp32.  Used by the variant of the decode kernel that keeps off the matrix cores.
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+template <typename E> struct Dot2;
+template <> struct Dot2<F16> {
+  __device__ static float fma2(uint32_t a, uint32_t b, float c) {
+    return __builtin_amdgcn_fdot2(bits_as<f16x2>(a), bits_as<f16x2>(b), c, false);
+  }
+};
+template <> struct Dot2<BF16> {
+  __device__ static float fma2(uint32_t a, uint32_t b, float c) {
+    return __builtin_amdgcn_fdot2_f32_bf16(bits_as<bf16x2>(a), bits_as<bf16x2>(b), c, false);
+  }
+};
+
 // max / sum over the four lanes i, i ^ 16, i ^ 32, i ^ 48; every lane gets the result
 __device__ __forceinline__ float quad16_max(float x) {
   auto a = __builtin_amdgcn_permlane16_swap(__float_as_uint(x), __float_as_uint(x), false, false);
@@ -681,7 +697,12 @@ constexpr size_t mfma_lds_floats(int group) {
 #define PIE_MFMA_WAVES_PER_EU 2
 #endif
 
-template <typename E, int HD, bool SPLIT>
+// VALU: the same kernel with both products on the vector ALU instead (group == 1 only, where they are
+// matrix-vector products).  Lane (quad, i) then holds, of a K load, eight dims of token i - its share of that
+// token's score, summed over the four quads - and of a V load four tokens of two dims, which it multiplies with
+// those tokens' weights fetched from the lanes that own them; the output dims are summed over the quads when the
+// unit ends.
+template <typename E, int HD, bool SPLIT, bool VALU>
 __global__ __launch_bounds__(kWaves * 64) __attribute__((amdgpu_waves_per_eu(PIE_MFMA_WAVES_PER_EU, 8)))
 void k_attn_decode_mfma(const AttnArgs a) {
   using MM = Mfma<E>;
@@ -739,8 +760,9 @@ void k_attn_decode_mfma(const AttnArgs a) {
 #pragma unroll
     for (int kc = 0; kc < NKC; ++kc) {
       qr[kc] = make_uint4(0, 0, 0, 0);
-      if (col < G)
-        qr[kc] = *reinterpret_cast<const uint4*>(a.q + (((size_t)b * n_q_heads + g * G + col) * HD + 32 * kc + 8 * quad) * 2);
+      const int head = VALU ? 0 : col;            // on the vector ALU every lane works for the one head
+      if (head < G)
+        qr[kc] = *reinterpret_cast<const uint4*>(a.q + (((size_t)b * n_q_heads + g * G + head) * HD + 32 * kc + 8 * quad) * 2);
     }
   };
   // Two register sets: while one block is consumed the next is already in flight.
@@ -788,6 +810,75 @@ void k_attn_decode_mfma(const AttnArgs a) {
     f32x4 o[NO];
 #pragma unroll
     for (int n = 0; n < NO; ++n) o[n] = f32x4{0.f, 0.f, 0.f, 0.f};
+    float ov[NKC][2];                             // VALU: dims 32 i + (lane & 15) and 16 further, this quad's tokens
+#pragma unroll
+    for (int i = 0; i < NKC; ++i) ov[i][0] = ov[i][1] = 0.f;
+
+    // VALU form of one block: lane (quad, i = lane & 15).  K load kc holds token i, dims 32 kc + 8 quad ..;
+    // V load holds tokens 4 quad .. 4 quad + 3 of dims 32 ld + i (x, y) and 32 ld + 16 + i (z, w).
+    auto consume_valu = [&](uint4 (&kr)[NKC], uint4 (&vr)[NKC], int32_t it) {
+      const int32_t t_first = (jb0 + wave + kWaves * it) * kBlockTokens;
+      const bool present = __shfl(my_slot, it, 64) >= 0;
+      const int32_t limit = present ? tok1 : 0;
+      float d = 0.f;
+#pragma unroll
+      for (int kc = 0; kc < NKC; ++kc) {
+        d = Dot2<E>::fma2(kr[kc].x, qreg[kc].x, d);
+        d = Dot2<E>::fma2(kr[kc].y, qreg[kc].y, d);
+        d = Dot2<E>::fma2(kr[kc].z, qreg[kc].z, d);
+        d = Dot2<E>::fma2(kr[kc].w, qreg[kc].w, d);
+      }
+      float sc = quad16_sum(d) * a.scale_log2e;   // score of token t_first + i, on all four lanes of the token
+      if (t_first + col >= limit) sc = -INFINITY;
+      if (t_first + kBlockTokens > limit) {       // garbage rows must not reach the sum
+        const int32_t t_lane = t_first + 4 * quad;
+        uint32_t keep_lo = 0, keep_hi = 0;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const uint32_t bits = t_lane + r < limit ? (0xffffu << (16 * (r & 1))) : 0u;
+          if (r < 2) keep_lo |= bits; else keep_hi |= bits;
+        }
+#pragma unroll
+        for (int i = 0; i < NKC; ++i) {
+          vr[i].x &= keep_lo; vr[i].y &= keep_hi; vr[i].z &= keep_lo; vr[i].w &= keep_hi;
+        }
+      }
+      const float m_new = fmaxf(m, row16_max(sc));           // the same on every lane of the wave
+      if (m_new > m) {
+        const float corr = __builtin_amdgcn_exp2f(m - m_new);
+        l *= corr;
+#pragma unroll
+        for (int i = 0; i < NKC; ++i) { ov[i][0] *= corr; ov[i][1] *= corr; }
+        m = m_new;
+      }
+      const float p = __builtin_amdgcn_exp2f(sc - m);
+      l += p;                                     // token i only; summed over the sixteen tokens when the unit ends
+      f32x4 pq;                                   // the weights of this quad's four tokens
+#pragma unroll
+      for (int r = 0; r < 4; ++r) pq[r] = __shfl(p, 4 * quad + r, 64);
+      const uint2 p_hi = MM::round(pq);
+      uint2 p_lo = make_uint2(0, 0);
+      if (SPLIT) {
+        const f32x4 back = MM::widen(p_hi);
+        f32x4 rest;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) rest[r] = pq[r] - back[r];
+        p_lo = MM::round(rest);
+      }
+#pragma unroll
+      for (int i = 0; i < NKC; ++i) {
+        ov[i][0] = Dot2<E>::fma2(vr[i].x, p_hi.x, ov[i][0]);
+        ov[i][0] = Dot2<E>::fma2(vr[i].y, p_hi.y, ov[i][0]);
+        ov[i][1] = Dot2<E>::fma2(vr[i].z, p_hi.x, ov[i][1]);
+        ov[i][1] = Dot2<E>::fma2(vr[i].w, p_hi.y, ov[i][1]);
+        if (SPLIT) {
+          ov[i][0] = Dot2<E>::fma2(vr[i].x, p_lo.x, ov[i][0]);
+          ov[i][0] = Dot2<E>::fma2(vr[i].y, p_lo.y, ov[i][0]);
+          ov[i][1] = Dot2<E>::fma2(vr[i].z, p_lo.x, ov[i][1]);
+          ov[i][1] = Dot2<E>::fma2(vr[i].w, p_lo.y, ov[i][1]);
+        }
+      }
+    };
 
     auto consume = [&](uint4 (&kr)[NKC], uint4 (&vr)[NKC], int32_t it) {
       const int32_t t_first = (jb0 + wave + kWaves * it) * kBlockTokens;      // first token of the block
@@ -858,10 +949,10 @@ void k_attn_decode_mfma(const AttnArgs a) {
     for (int32_t it = 0; it < n_it; it += 2) {
       if (it == it_ticket && threadIdx.x == 0) after_next = 2 * gridDim.x + atomicAdd(a.counter, 1u);
       if (it + 1 < n_it) load_tile(kB, vB, my_slot, it + 1, g);
-      consume(kA, vA, it);
+      if constexpr (VALU) consume_valu(kA, vA, it); else consume(kA, vA, it);
       if (it + 1 < n_it) {
         if (it + 2 < n_it) load_tile(kA, vA, my_slot, it + 2, g);
-        consume(kB, vB, it + 1);
+        if constexpr (VALU) consume_valu(kB, vB, it + 1); else consume(kB, vB, it + 1);
       }
     }
     if (n_it <= 0 && threadIdx.x == 0) after_next = 2 * gridDim.x + atomicAdd(a.counter, 1u);
@@ -874,6 +965,26 @@ void k_attn_decode_mfma(const AttnArgs a) {
     }
 
     // merge the kWaves partial states: lane (quad, col) holds O[16 n + 4 quad + r][head col]
+    if constexpr (VALU) {
+      l = row16_sum(l);                           // over the sixteen tokens of a block position
+#pragma unroll
+      for (int i = 0; i < NKC; ++i) {             // over the four quads' tokens
+        ov[i][0] = quad16_sum(ov[i][0]);
+        ov[i][1] = quad16_sum(ov[i][1]);
+      }
+      if (lane == 0) {
+        s_m[wave * kMaxGroup] = m;
+        s_l[wave * kMaxGroup] = l;
+      }
+      if (quad == 0) {
+        float* row = s_acc + (size_t)wave * G * ROW;
+#pragma unroll
+        for (int i = 0; i < NKC; ++i) {
+          row[32 * i + col] = ov[i][0];
+          row[32 * i + 16 + col] = ov[i][1];
+        }
+      }
+    } else {
     l = quad16_sum(l);
     if (col < G) {
       if (quad == 0) {
@@ -883,6 +994,7 @@ void k_attn_decode_mfma(const AttnArgs a) {
       float* row = s_acc + ((size_t)wave * G + col) * ROW + 4 * quad;
 #pragma unroll
       for (int n = 0; n < NO; ++n) *reinterpret_cast<f32x4*>(row + 16 * n) = o[n];
+    }
     }
     __syncthreads();
     for (int idx = threadIdx.x; idx < G * HD; idx += kWaves * 64) {
@@ -1288,7 +1400,7 @@ int launch_attn_resolve(const pie_pool* p, const int32_t* d_table, const int32_t
   return PIE_OK;
 }
 
-template <typename E, int HD, bool SPLIT>
+template <typename E, int HD, bool SPLIT, bool VALU = false>
 static int launch_mfma(const pie_pool* p, AttnArgs a, int32_t layer_row, int32_t batch, int32_t n_q_heads,
                        hipStream_t s, hipEvent_t e0, hipEvent_t e1, hipEvent_t done) {
   const size_t lds = mfma_lds_floats<HD>(a.group) * sizeof(float);
@@ -1296,7 +1408,7 @@ static int launch_mfma(const pie_pool* p, AttnArgs a, int32_t layer_row, int32_t
   static int wgs_per_cu[kMaxGroup + 1] = {};
   if (wgs_per_cu[a.group] == 0) {
     int n = 0;
-    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_attn_decode_mfma<E, HD, SPLIT>, kWaves * 64, lds) != hipSuccess ||
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, k_attn_decode_mfma<E, HD, SPLIT, VALU>, kWaves * 64, lds) != hipSuccess ||
         n < 1) {
       (void)hipGetLastError();
       n = 2;
@@ -1311,10 +1423,10 @@ static int launch_mfma(const pie_pool* p, AttnArgs a, int32_t layer_row, int32_t
   // signal instead of a packet of its own behind it
   const bool reduce = a.n_parts > 1;
   if (done && !reduce)
-    hipExtLaunchKernelGGL((k_attn_decode_mfma<E, HD, SPLIT>), dim3(grid), dim3(kWaves * 64), (uint32_t)lds, s, nullptr,
-                          done, 0, a);
+    hipExtLaunchKernelGGL((k_attn_decode_mfma<E, HD, SPLIT, VALU>), dim3(grid), dim3(kWaves * 64), (uint32_t)lds, s,
+                          nullptr, done, 0, a);
   else
-    hipLaunchKernelGGL((k_attn_decode_mfma<E, HD, SPLIT>), dim3(grid), dim3(kWaves * 64), lds, s, a);
+    hipLaunchKernelGGL((k_attn_decode_mfma<E, HD, SPLIT, VALU>), dim3(grid), dim3(kWaves * 64), lds, s, a);
   PIE_HIP(hipGetLastError());
   if (e1) PIE_HIP(hipEventRecord(e1, s));
   if (reduce) {
@@ -1393,9 +1505,15 @@ int launch_attn_decode(const pie_pool* p, int32_t layer, const void* d_q, int32_
                    : launch_f32<64>(a, batch, c.n_q_heads, a.max_items, s, k_start, k_end, done);
     }
     case PIE_DTYPE_F16:
+      if (g == 1 && p->attn_valu)
+        return hd128 ? launch_mfma<F16, 128, false, true>(p, a, row, batch, c.n_q_heads, s, k_start, k_end, done)
+                     : launch_mfma<F16, 64, false, true>(p, a, row, batch, c.n_q_heads, s, k_start, k_end, done);
       return hd128 ? launch_mfma<F16, 128, false>(p, a, row, batch, c.n_q_heads, s, k_start, k_end, done)
                    : launch_mfma<F16, 64, false>(p, a, row, batch, c.n_q_heads, s, k_start, k_end, done);
     case PIE_DTYPE_BF16:
+      if (g == 1 && p->attn_valu)
+        return hd128 ? launch_mfma<BF16, 128, true, true>(p, a, row, batch, c.n_q_heads, s, k_start, k_end, done)
+                     : launch_mfma<BF16, 64, true, true>(p, a, row, batch, c.n_q_heads, s, k_start, k_end, done);
       return hd128 ? launch_mfma<BF16, 128, true>(p, a, row, batch, c.n_q_heads, s, k_start, k_end, done)
                    : launch_mfma<BF16, 64, true>(p, a, row, batch, c.n_q_heads, s, k_start, k_end, done);
     default: return PIE_EINVAL;

@@ -773,6 +773,14 @@ int pie_set_attn_partition(pie_pool* p, int32_t tokens) {
   return PIE_OK;
 }
 
+int pie_set_attn_vector_alu(pie_pool* p, int32_t on) {
+  if (!p) return PIE_EINVAL;
+  PIE_DRAIN(p);
+  if (on && (p->cfg.n_q_heads != p->cfg.n_kv_heads || p->cfg.dtype == PIE_DTYPE_F32)) return PIE_ESTATE;
+  p->attn_valu = on != 0;
+  return PIE_OK;
+}
+
 int pie_set_layer_compute_us(pie_pool* p, float us) {
   if (!p || !(us >= 0.f) || us > 1.0e6f) return PIE_EINVAL;
   PIE_DRAIN(p);

@@ -267,3 +267,39 @@ def test_stream_probe_runs_on_the_same_plan_and_leaves_no_trace():
     assert ms > 0.0 and lib.check_errors() == 0
     assert np.array_equal(run_attn(lib, case, table, 1), before)
     lib.close()
+
+
+@pytest.mark.parametrize("dtype,d", [(I.DTYPE_F16, 128), (I.DTYPE_BF16, 128), (I.DTYPE_F16, 64), (I.DTYPE_BF16, 64)])
+def test_mha_on_the_vector_alu_matches_the_oracle_and_the_matrix_core_kernel(dtype, d):
+    """pie_set_attn_vector_alu: the same attention with both products as two-element dot products on the vector
+    ALU.  Several partitions, ragged tails, poisoned unused rows and slots, a context of one token and an empty one;
+    refused for grouped queries and fp32."""
+    w = I.Workload("valu", 2, 6, 4, 4, d, dtype, ctx_lo=1, ctx_hi=1300, value_scale=1.0, seed=37)
+    case = I.make_case(w)
+    case.ctx_lens[0], case.ctx_lens[1] = 1, min(529, int(case.ctx_lens[1]))
+    case = _recase(case)
+    n = int(case.n_blocks.sum())
+    lib, mod, table = GH.make_pools(case, n + 5, 4, 4, fill=H.nan_fill(dtype))
+    lib.set_attn_partition(256)
+    for layer in (0, 1):
+        lib.set_attn_vector_alu(False)
+        on_matrix_cores = run_attn(lib, case, table, layer)
+        lib.set_attn_vector_alu(True)
+        got = run_attn(lib, case, table, layer)
+        ref = A.dense_attention(*H.dense_f64(case, layer), case.ctx_lens)
+        check(got, ref, dtype)
+        check(on_matrix_cores, ref, dtype)
+        assert GH.rowwise_rel_err(got, on_matrix_cores) <= REL[dtype]             # and with each other
+    from oracle import numfmt
+    assert np.array_equal(got[0], numfmt.to_f64(case.v_dense[0][1, 0], dtype))    # one token: exactly its value row
+    case.ctx_lens[2] = 0
+    got = run_attn(lib, case, table, 1)
+    assert (got[2] == 0).all() and np.isfinite(got).all()
+    lib.close()
+    gqa = B.Pool(1, 8, 2, 128, 16, I.DTYPE_F16, 4, 0, 0, device=GH.DEV)
+    f32 = B.Pool(1, 4, 4, 64, 16, I.DTYPE_F32, 4, 0, 0, device=GH.DEV)
+    for pool in (gqa, f32):
+        with pytest.raises(B.PieError) as e:
+            pool.set_attn_vector_alu(True)
+        assert e.value.code == B.ESTATE
+        pool.close()
