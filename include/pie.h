@@ -341,7 +341,9 @@ int pie_set_timing(pie_pool* pool, int32_t mode);
 /* Waits for everything the pool has enqueued on the streams it has seen. */
 int pie_pool_sync(pie_pool* pool);
 
-/* Summary of the last pie_step (timing must be on and the step complete: call after pie_pool_sync). */
+/* Summary of the last pie_step.  Its times are there when timing was on and the step has run: call after
+ * pie_pool_sync.  Nothing is waited for: with monitoring by device clock, PIE_ESTATE while the pool's streams
+ * still have work; with events, PIE_EHIP (hipErrorNotReady) from the event query. */
 int pie_get_stats(pie_pool* pool, pie_stats* out);
 
 /* Per-layer times in ms of the last pie_step; each array has n_layers entries (NULL to skip one).

@@ -240,15 +240,30 @@ int poll_moves(pie_elastic_pool* lp, hipStream_t cs) {
 // host: a swap-out first waits for the last computation on its layer; a swap-in takes chunks that are free,
 // i.e. whose previous tenant's swap-out the host has seen complete.  The incoming layer's block map goes out
 // on the compute stream, ahead of the layer's kernels.
+// The first n chunks of a layer to or from its image in CPU memory (kind 0: in, 1: out), one copy-engine transfer
+// per run of neighbouring chunks: a transfer costs the host some 10-20 us to enqueue whatever it carries, and a
+// layer's chunks mostly are neighbours.
+int copy_chunks(pie_elastic_pool* lp, int kind, char* host_image, const std::vector<int32_t>& c, size_t n, hipStream_t s) {
+  for (size_t i = 0; i < n;) {
+    size_t j = i + 1;
+    while (j < n && c[j] == c[j - 1] + 1) ++j;
+    const size_t bytes = (j - i) * lp->chunk_bytes;
+    char* h = host_image + i * lp->chunk_bytes;
+    if (kind == 0) PIE_HIP(hipMemcpyAsync(chunk_dev(lp, c[i]), h, bytes, hipMemcpyHostToDevice, s));
+    else PIE_HIP(hipMemcpyAsync(h, chunk_dev(lp, c[i]), bytes, hipMemcpyDeviceToHost, s));
+    i = j;
+  }
+  return PIE_OK;
+}
+
 int start_moves(pie_elastic_pool* lp, const pie_layer_action& a, hipStream_t cs, hipStream_t is, hipStream_t os) {
+  int rc_copy;
   if (a.out_layer >= 0) {
     if (lp->ev_layer_rec[a.out_layer]) PIE_HIP(hipEventSynchronize(lp->ev_layer[a.out_layer]));
     const std::vector<int32_t>& c = lp->book->chunks[a.out_layer];
     // only the chunks that hold live blocks travel; the others are simply given up
     const size_t n_carry = lp->live_chunks < 0 ? c.size() : std::min(c.size(), (size_t)lp->live_chunks);
-    for (size_t i = 0; i < n_carry; ++i)
-      PIE_HIP(hipMemcpyAsync(slot_host(lp, a.out_host_slot) + i * lp->chunk_bytes, chunk_dev(lp, c[i]), lp->chunk_bytes,
-                             hipMemcpyDeviceToHost, os));
+    if ((rc_copy = copy_chunks(lp, 1, slot_host(lp, a.out_host_slot), c, n_carry, os))) return rc_copy;
     PIE_HIP(hipEventRecord(lp->ev_out, os));
     lp->out_carried = (int32_t)n_carry;
     ++lp->stats.n_swap_out;
@@ -260,9 +275,7 @@ int start_moves(pie_elastic_pool* lp, const pie_layer_action& a, hipStream_t cs,
     if (rc) return rc;
     if ((rc = send_map(lp, a.in_layer, cs))) return rc;
     const std::vector<int32_t>& c = lp->book->chunks[a.in_layer];
-    for (int32_t i = 0; i < n_data; ++i)
-      PIE_HIP(hipMemcpyAsync(chunk_dev(lp, c[i]), slot_host(lp, a.in_host_slot) + (size_t)i * lp->chunk_bytes,
-                             lp->chunk_bytes, hipMemcpyHostToDevice, is));
+    if ((rc = copy_chunks(lp, 0, slot_host(lp, a.in_host_slot), c, (size_t)n_data, is))) return rc;
     PIE_HIP(hipEventRecord(lp->ev_in, is));
     ++lp->stats.n_swap_in;
     lp->stats.bytes_in += (uint64_t)n_data * lp->chunk_bytes;

@@ -1175,10 +1175,16 @@ static int elapsed(hipEvent_t a, hipEvent_t b, float* ms) {
   return PIE_OK;
 }
 
-// The clock table of the last step, copied to the host (the step's streams are waited for first).
+// The clock table of the last step, copied to the host.  The step must have run: nothing is waited for here.
 static int read_clock(pie_pool* p, std::vector<unsigned long long>& t) {
-  int rc = pie_pool_sync(p);
-  if (rc) return rc;
+  for (hipStream_t s : p->streams_seen) {
+    const hipError_t e = hipStreamQuery(s);
+    if (e == hipErrorNotReady) {
+      (void)hipGetLastError();
+      return PIE_ESTATE;                          // still running: call pie_pool_sync first
+    }
+    PIE_HIP(e);
+  }
   t.resize(((size_t)p->cfg.n_layers + 1) * kClockRow);
   PIE_HIP(hipMemcpy(t.data(), p->d_clock, t.size() * sizeof(unsigned long long), hipMemcpyDeviceToHost));
   return PIE_OK;
