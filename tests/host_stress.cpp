@@ -23,7 +23,7 @@ static void stress_pool(int iters) {
   const int H = cfg.n_gpu_blocks + cfg.n_host_blocks;
   std::vector<int32_t> buf(4 * H + 64), a(H + 8), b(H + 8);
   for (int it = 0; it < iters; ++it) {
-    const int op = ri(0, 9);
+    const int op = ri(0, 11);
     const int n = ri(-1, H + 2);
     if (ri(0, 3)) { std::vector<int32_t> perm(H); for (int i = 0; i < H; ++i) perm[i] = i; std::shuffle(perm.begin(), perm.end(), rng); std::copy(perm.begin(), perm.end(), buf.begin()); }
     else for (auto& x : buf) x = ri(-2, H + 1);
@@ -48,6 +48,22 @@ static void stress_pool(int iters) {
       }
       case 8: { pie_stats st; rc = pie_get_stats(p, &st); break; }
       case 9: { void* q = nullptr; rc = pie_block_address(p, ri(-1, 2), ri(-1, cfg.n_layers), ri(-1, H + 20), &q); break; }
+      case 10: {                                  // the newer calls on a pool without device memory: refused, nothing touched
+        int32_t tb[4] = {0, 1, 2, 3}, cx[1] = {20};
+        char q[16];
+        rc = pie_attn_decode_static(p, ri(-1, cfg.n_layers), q, tb, ri(-1, 4), cx, ri(-1, 1), q, nullptr);
+        REQUIRE(rc == PIE_ESTATE || rc == PIE_EINVAL || rc == PIE_OK);
+        REQUIRE(pie_set_async_submit(p, ri(0, 1)) == PIE_ESTATE);
+        REQUIRE(pie_step_join_sync(p) == PIE_OK);
+        break;
+      }
+      case 11: {
+        rc = pie_set_attn_vector_alu(p, ri(0, 1));
+        REQUIRE(rc == PIE_OK || rc == PIE_ESTATE);
+        rc = pie_set_swap_workgroups(p, ri(-1, 1030));
+        REQUIRE(rc == PIE_OK || rc == PIE_EINVAL);
+        break;
+      }
     }
     REQUIRE(rc <= 0 && rc >= -4);
     if (!rc) ++ok_count[0][op];
