@@ -167,21 +167,53 @@ def test_llama2_7b_shape_all_resident_then_thirty_percent_on_the_host():
         dw.pool.close()
 
 
-def test_llama3_8b_shape_gqa_bf16():
+def test_llama3_8b_shape_gqa_bf16_all_resident_then_ten_percent_on_the_host():
+    """The 8B-shaped workload at full size (bf16, four query heads per kv head, 64 KiB blocks, skewed contexts):
+    sampled outputs against the oracle, the leg with a tenth of the blocks on the host bit-identical to the
+    resident one, and the write-back checked in the home images on all three swap paths."""
     none = np.zeros(0, dtype=np.int32)
-    dw = WL.build(I.CONFIGS["cfg4"])
+    dw = WL.build(I.CONFIGS["cfg4"], host_capacity_fraction=0.12)
     try:
         run_steps(dw, none, none, n=2)
-        check_samples(dw, sample_pairs(dw, 6, 1))
+        samples = sample_pairs(dw, 6, 1)
+        check_samples(dw, samples)
+        resident = dw.out.clone()
+        dw.pool.set_host_fraction(0.10, dw.order, torch.cuda.Stream())
+        dw.pool.sync()
+        pf, dirty = dw.pool.prefetch_list(dw.table, dw.ctx_lens)
+        assert len(pf) == round(0.10 * dw.total_blocks) and len(dirty) > 0
+        dw.out.zero_()
+        run_steps(dw, pf, dirty, n=1)
+        assert torch.equal(dw.out.view(torch.int16), resident.view(torch.int16))
+        check_samples(dw, samples[:3])
+        for path, seed in ((B.SWAP_DMA, 21), (B.SWAP_KERNEL, 22), (B.SWAP_AUTO, 23)):
+            dw.pool.set_swap_path(path)
+            step_and_check_tail_blocks(dw, pf, dirty, seed, layers=(0, 13, 31))
+            check_samples(dw, samples[3:5])
     finally:
         dw.pool.close()
 
 
 def test_70b_shape_long_context_per_layer_shape_on_four_layers():
+    """The 70B shape's real per-layer size (batch 32 x 32768 tokens, 64 / 8 heads) on four layers: sampled outputs
+    against the oracle; then the share of the cache that cannot fit one GPU (21.5 %) on the host: outputs
+    bit-identical, the oracle reading the host pool, and the write-back in the home images."""
     none = np.zeros(0, dtype=np.int32)
-    dw = WL.build(I.CONFIGS["cfg5"], n_layers=4)
+    dw = WL.build(I.CONFIGS["cfg5"], n_layers=4, host_capacity_fraction=0.225)
     try:
         run_steps(dw, none, none, n=1)
         check_samples(dw, [(0, 0), (3, 17), (2, 31)])
+        resident = dw.out.clone()
+        hs = WL.per_sequence_host_order(dw, 0.215)
+        dw.pool.migrate(hs, B.HOST, torch.cuda.Stream())
+        dw.pool.sync()
+        pf, dirty = dw.pool.prefetch_list(dw.table, dw.ctx_lens)
+        assert len(pf) == len(hs) and abs(len(hs) / dw.total_blocks - 0.215) < 0.002
+        dw.out.zero_()
+        run_steps(dw, pf, dirty, n=1)
+        assert torch.equal(dw.out.view(torch.int16), resident.view(torch.int16))
+        check_samples(dw, [(1, 5), (3, 30)])
+        if len(dirty):
+            step_and_check_tail_blocks(dw, pf, dirty, 31, layers=(0, 3))
     finally:
         dw.pool.close()
