@@ -272,8 +272,9 @@ int pie_attn_stream_probe_sync(pie_pool* pool, int32_t layer, const int32_t* d_b
  * l = 0..L-1: layer l runs on compute_stream once its staged blocks are present; layer l+1's blocks are
  * prefetched on swap_in_stream into the other staging region meanwhile, and the token's rows for host-homed
  * tails are written into their staged copies on that stream, right behind the copy; layer l's dirty blocks
- * are written back on swap_out_stream after the layer.  Behind the last layer, layer 0's blocks are brought
- * in once more for the step that follows (see pie_set_cross_step_prefetch).
+ * are written back on swap_out_stream as soon as they are staged and appended to (the layer only reads them,
+ * so the write-back runs beside it).  Behind the last layer, layer 0's blocks are brought in once more for
+ * the step that follows (see pie_set_cross_step_prefetch).
  * d_q_all, d_out_all: [L][batch][n_q_heads][head_dim]; d_k_new, d_v_new: [L][batch][n_kv_heads][head_dim]
  * (NULL skips the append).  Argument errors are detected before anything is enqueued; a HIP error in the
  * middle (PIE_EHIP) leaves the step partly enqueued. */

@@ -354,8 +354,11 @@ static int swap_in_impl(pie_pool* p, int32_t layer, int32_t n, const int32_t* ha
   return PIE_OK;
 }
 
+// after_read: the copies wait for the layer's computation as well.  A caller whose computation only reads the
+// staged blocks (pie_step: the new token's rows are appended on the swap-in's own stream, behind the copy that
+// stages the block) passes false, and the blocks go home as soon as they are staged and appended to.
 static int swap_out_impl(pie_pool* p, int32_t layer, int32_t n, const int32_t* handles, hipStream_t s,
-                         const Mark& t0, const Mark& t1) {
+                         const Mark& t0, const Mark& t1, bool after_read = true) {
   if (layer < 0 || layer >= p->cfg.n_layers) return PIE_EINVAL;
   std::vector<uint8_t> seen;
   int rc = check_handles(p, n, handles, PIE_WHERE_HOST, seen);
@@ -374,7 +377,7 @@ static int swap_out_impl(pie_pool* p, int32_t layer, int32_t n, const int32_t* h
   const CopyPlan cp = plan_copy(p, src, dst);
   const bool on_host = n > 0 && cp.path == PIE_SWAP_DMA && !p->dma_stream_order;
   if ((rc = order_after(s, p->ev_in[r], p->ev_in_rec[r], on_host))) return rc;
-  if ((rc = order_after(s, p->ev_read[r], p->ev_read_rec[r], on_host))) return rc;
+  if (after_read && (rc = order_after(s, p->ev_read[r], p->ev_read_rec[r], on_host))) return rc;
   if ((rc = note(t0, s))) return rc;
   if ((rc = copy_blocks(p, 1, layer, src, dst, cp, s))) return rc;
   if ((rc = note(t1, s))) return rc;
@@ -1060,8 +1063,13 @@ static int step_body(pie_pool* p, const StepJob& j) {
       }
     }
     if (n_dirty > 0 && d_k_new) {
+      // The staged tail blocks are final once the swap stream has appended the new rows behind the copy that
+      // staged them; the attention only reads them.  So they go home as soon as this layer's swap-in has
+      // completed, beside the layer's computation, not after it: the write-back is then neither something
+      // the host waits for at the layer's end (with the next layer's kernels not yet queued) nor a link in
+      // the chain  layer l ends -> write back -> prefetch layer l + 2 into the same region.
       if ((rc = swap_out_impl(p, l, n_dirty, h_dirty, os, mark(p->lev[l].out_start, l, kClockOutStart),
-                              mark(p->lev[l].out_end, l, kClockOutEnd))))
+                              mark(p->lev[l].out_end, l, kClockOutEnd), false)))
         return rc;
       p->lev[l].out_used = timed || clocked;
     }
@@ -1204,15 +1212,15 @@ static int layer_times_from_clock(pie_pool* p, float* t_attn, float* t_kernel, f
     if (t_attn) t_attn[l] = span(at(l, kClockKernelStart), at(l, kClockLayerEnd));
     if (t_kernel) t_kernel[l] = span(at(l, kClockKernelStart), at(l, kClockKernelEnd));
     // A swap-in starts when the one before it on its stream has ended and the staging region is free, i.e.
-    // the layer two back has been computed; a write-back when its layer has been computed and the one
-    // before it has ended.
+    // the layer two back has been computed; a write-back when its layer's swap-in and the write-back before
+    // it have ended.
     if (t_in) {
       unsigned long long from = l >= 2 ? at(l - 2, kClockLayerEnd) : step_start;
       if (l >= 1 && p->lev[l - 1].in_used && at(l - 1, kClockInEnd) > from) from = at(l - 1, kClockInEnd);
       t_in[l] = p->lev[l].in_used ? span(from, at(l, kClockInEnd)) : 0.f;
     }
     if (t_out) {
-      unsigned long long from = at(l, kClockLayerEnd);
+      unsigned long long from = p->lev[l].in_used ? at(l, kClockInEnd) : step_start;
       if (l >= 1 && p->lev[l - 1].out_used && at(l - 1, kClockOutEnd) > from) from = at(l - 1, kClockOutEnd);
       t_out[l] = p->lev[l].out_used ? span(from, at(l, kClockOutEnd)) : 0.f;
     }
