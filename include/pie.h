@@ -268,12 +268,14 @@ int pie_attn_stream_probe_sync(pie_pool* pool, int32_t layer, const int32_t* d_b
  * any order - the host cannot read the device block table, so the caller names them (pie_prefetch_list
  * computes the list from a host copy of the table, ordered by host slot so that the copies are contiguous).
  * h_dirty: the n_dirty of those that receive this step's token (host-homed tail blocks).
- * The new token's rows go into the GPU-homed tail blocks of all layers first, in one launch.  Then, for
- * l = 0..L-1: layer l runs on compute_stream once its staged blocks are present; layer l+1's blocks are
- * prefetched on swap_in_stream into the other staging region meanwhile, and the token's rows for host-homed
- * tails are written into their staged copies on that stream, right behind the copy; layer l's dirty blocks
- * are written back on swap_out_stream as soon as they are staged and appended to (the layer only reads them,
- * so the write-back runs beside it).  Behind the last layer, layer 0's blocks are brought in once more for
+ * For l = 0..L-1: layer l runs on compute_stream once its staged blocks are present; layer l+1's blocks are
+ * prefetched on swap_in_stream into the other staging region meanwhile.  With a new token (d_k_new), the
+ * attention reads the context without it from the cache and takes the token itself from d_k_new / d_v_new, so
+ * no layer waits for the rows to be stored: those of the GPU-homed tail blocks of all layers are written by one
+ * launch on swap_out_stream beside the first layers (compute_stream is ordered after it when the step ends),
+ * those of host-homed tails into their staged copies on swap_in_stream, right behind the copy; layer l's dirty
+ * blocks are written back on swap_out_stream as soon as they are staged and appended to (the layer only reads
+ * them, so the write-back runs beside it).  Behind the last layer, layer 0's blocks are brought in once more for
  * the step that follows (see pie_set_cross_step_prefetch).
  * d_q_all, d_out_all: [L][batch][n_q_heads][head_dim]; d_k_new, d_v_new: [L][batch][n_kv_heads][head_dim]
  * (NULL skips the append).  Argument errors are detected before anything is enqueued; a HIP error in the
@@ -348,7 +350,7 @@ int pie_pool_sync(pie_pool* pool);
 int pie_get_stats(pie_pool* pool, pie_stats* out);
 
 /* Per-layer times in ms of the last pie_step; each array has n_layers entries (NULL to skip one).
- * t_attn: append + attention + reduction; t_kernel: the attention decode kernel alone; t_in / t_out: the
+ * t_attn: attention + reduction; t_kernel: the attention decode kernel alone; t_in / t_out: the
  * layer's prefetch / write-back; t_stall: how long the compute stream, free after the previous layer, still had
  * to wait for this layer's prefetch to finish (0 when the prefetch was hidden). */
 int pie_get_layer_times(pie_pool* pool, float* t_attn, float* t_kernel, float* t_in, float* t_out, float* t_stall);

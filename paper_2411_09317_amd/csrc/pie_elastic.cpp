@@ -515,7 +515,8 @@ int pie_elastic_step(pie_elastic_pool* lp, const void* d_q_all, const void* d_k_
   pie::note_stream(p, is);
   pie::note_stream(p, os);
   int rc;
-  if ((rc = pie::launch_attn_plan(p, d_ctx_lens, batch, max_blocks, cs))) return rc;
+  // with a new token the attention takes it from the new rows, the rest of the context from the cache
+  if ((rc = pie::launch_attn_plan(p, d_ctx_lens, batch, max_blocks, cs, false, nullptr, d_k_new != nullptr))) return rc;
   for (int32_t k = 0; k < lp->n; ++k) {
     // the presence check: wait until the layer is physically on the GPU
     if ((rc = poll_moves(lp, cs))) return rc;
@@ -548,7 +549,9 @@ int pie_elastic_step(pie_elastic_pool* lp, const void* d_q_all, const void* d_k_
                                        &view)))
       return rc;
     if ((rc = pie::launch_attn_decode(p, k, (const char*)d_q_all + k * q_stride, max_blocks, d_ctx_lens, batch,
-                                      (char*)d_out_all + k * q_stride, cs, nullptr, nullptr, k, nullptr, &view)))
+                                      (char*)d_out_all + k * q_stride, cs, nullptr, nullptr, k, nullptr, &view, nullptr,
+                                      nullptr, d_k_new ? (const char*)d_k_new + k * kv_stride : nullptr,
+                                      d_v_new ? (const char*)d_v_new + k * kv_stride : nullptr)))
       return rc;
     if (p->layer_compute_us > 0.f && (rc = pie::launch_busy(p->layer_compute_us, p->wall_clock_khz, cs))) return rc;
     PIE_HIP(hipEventRecord(lp->ev_layer[k], cs));

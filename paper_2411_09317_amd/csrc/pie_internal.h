@@ -152,8 +152,11 @@ struct pie_pool {
   hipEvent_t ev_compute = nullptr;                // last compute work
   hipEvent_t ev_migrate = nullptr;                // last migration
   hipEvent_t ev_map = nullptr;                    // last map update sent on the compute stream
+  hipEvent_t ev_app[2] = {nullptr, nullptr};      // last append into the staged copies of region r (swap-in stream)
+  hipEvent_t ev_append = nullptr;                 // a step's append into the GPU-homed tail blocks (write-back stream)
   bool ev_in_rec[2] = {false, false}, ev_read_rec[2] = {false, false}, ev_out_rec[2] = {false, false};
   bool ev_compute_rec = false, ev_migrate_rec = false, ev_map_rec = false, migrate_pending = false;
+  bool ev_app_rec[2] = {false, false};
   std::vector<hipStream_t> streams_seen;
 
   // options
@@ -235,7 +238,7 @@ int launch_kv_append(const pie_pool* p, int32_t layer, int32_t n_layers, const v
 int launch_chunk_map_fill(int32_t* d_map, int32_t n_handles, int32_t chunk_blocks, const ChunkList& list, hipStream_t s);
 // work: the scratch to use; NULL = the pool's own (in the caller's device buffer)
 int launch_attn_plan(const pie_pool* p, const int32_t* d_ctx, int32_t batch, int32_t max_blocks, hipStream_t s,
-                     bool reset_clock = false, const AttnWork* work = nullptr);
+                     bool reset_clock = false, const AttnWork* work = nullptr, bool without_last = false);
 int launch_attn_resolve(const pie_pool* p, const int32_t* d_table, const int32_t* d_ctx, int32_t batch,
                         int32_t max_blocks, bool region0, bool valid0, bool region1, bool valid1, hipStream_t s,
                         const LayerView* view = nullptr, const AttnWork* work = nullptr);
@@ -243,7 +246,8 @@ int launch_attn_decode(const pie_pool* p, int32_t layer, const void* d_q, int32_
                        int32_t batch, void* d_out, hipStream_t s, hipEvent_t k_start = nullptr,
                        hipEvent_t k_end = nullptr, int32_t ticket_index = -1,
                        unsigned long long* clock_row = nullptr, const LayerView* view = nullptr,
-                       hipEvent_t done = nullptr, const AttnWork* work = nullptr);
+                       hipEvent_t done = nullptr, const AttnWork* work = nullptr, const void* d_k_new = nullptr,
+                       const void* d_v_new = nullptr);
 int launch_stream_probe(const pie_pool* p, int32_t layer, int32_t max_blocks, int32_t batch, hipStream_t s);
 int attn_static_scratch(char** out);
 int attn_static_work(const pie_pool* p, int32_t batch, int32_t max_blocks, AttnWork* out);

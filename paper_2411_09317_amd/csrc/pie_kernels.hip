@@ -271,6 +271,17 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float x) {
   return (uint16_t)(u >> 16);
 }
 
+template <typename E> __device__ __forceinline__ float load_elem(const void* base, size_t idx);
+template <> __device__ __forceinline__ float load_elem<F32>(const void* base, size_t idx) {
+  return reinterpret_cast<const float*>(base)[idx];
+}
+template <> __device__ __forceinline__ float load_elem<F16>(const void* base, size_t idx) {
+  return __half2float(reinterpret_cast<const __half*>(base)[idx]);
+}
+template <> __device__ __forceinline__ float load_elem<BF16>(const void* base, size_t idx) {
+  return __uint_as_float((uint32_t)reinterpret_cast<const uint16_t*>(base)[idx] << 16);
+}
+
 template <typename E> __device__ __forceinline__ void store_elem(void* base, size_t idx, float v);
 template <> __device__ __forceinline__ void store_elem<F32>(void* base, size_t idx, float v) {
   reinterpret_cast<float*>(base)[idx] = v;
@@ -574,11 +585,12 @@ __device__ __forceinline__ int32_t clamp_ctx(int32_t ctx, int32_t max_blocks) {
 // items[i] = {sequence | part << 16, context length of the sequence}: item `part` covers the tokens
 // [part * part_tokens, min((part + 1) * part_tokens, context)).  hdr[0] = number of items.  Full items
 // (part_tokens tokens) come first, then one shorter item per sequence whose length is not a multiple of
-// part_tokens (or is <= 0, so that its output is still written), longest first.  Also zeroes the ticket
+// part_tokens (or is <= 0, so that its output is still written), longest first.  With minus = 1 "context" is the
+// context without its last token.  Also zeroes the ticket
 // counters of all layers and, if a clock table is given, resets its rows and notes the time in the row
 // after the last.
 __global__ __launch_bounds__(256) void k_attn_plan(const int32_t* __restrict__ ctx, int32_t batch, int32_t part_tokens,
-                                                   int32_t max_blocks, uint2* __restrict__ items,
+                                                   int32_t max_blocks, int32_t minus, uint2* __restrict__ items,
                                                    int32_t* __restrict__ hdr, uint32_t* __restrict__ counters,
                                                    int32_t n_counters, uint32_t* __restrict__ err,
                                                    unsigned long long* __restrict__ clock) {
@@ -589,8 +601,9 @@ __global__ __launch_bounds__(256) void k_attn_plan(const int32_t* __restrict__ c
   __shared__ int32_t s_total_full;
   for (int32_t b = threadIdx.x; b < batch; b += blockDim.x) {
     const int32_t raw = ctx[b];
-    const int32_t c = clamp_ctx(raw, max_blocks);
-    if (raw > c) atomicOr(err, PIE_DEVERR_BAD_HANDLE);   // the table cannot name that many blocks
+    const int32_t full = clamp_ctx(raw, max_blocks);
+    if (raw > full) atomicOr(err, PIE_DEVERR_BAD_HANDLE);   // the table cannot name that many blocks
+    const int32_t c = full > 0 ? full - minus : full;       // minus = 1: the last token is not read from the cache
     const int32_t nf = c > 0 ? c / part_tokens : 0;
     const int32_t rem = c > 0 ? c % part_tokens : 0;
     s_nf[b] = nf;
@@ -685,6 +698,12 @@ struct AttnArgs {
   int32_t max_items;         // entries the item list has room for (batch x n_parts)
   unsigned long long* clock;    // this launch's row of the clock table, or NULL
   unsigned long long* clock_wg; // with it: a (first, last moment) pair per workgroup, or NULL (atomics on the row)
+  // The newest token's key / value rows [B][Hkv][d], or NULL.  With them the items cover the context without
+  // its last token (the planning kernel was told so), every partition's state goes to the workspace, and the
+  // reduction kernel adds the last token from these rows: the attention then does not depend on the append
+  // that writes the rows into the cache.
+  const char* new_k;
+  const char* new_v;
 };
 
 // LDS floats the MFMA kernel needs for `group` query heads per kv head
@@ -1010,7 +1029,7 @@ void k_attn_decode_mfma(const AttnArgs a) {
         A = fmaf(wt, s_acc[((size_t)w * G + h) * ROW + dim], A);
       }
       const size_t orow = (size_t)b * n_q_heads + hq0 + h;
-      if (np_b == 1) {                           // the only partition of its sequence: this is the result
+      if (np_b == 1 && !a.new_k) {               // the only partition of its sequence: this is the result
         store_elem<E>(a.out, orow * HD + dim, L > 0.f ? A / L : 0.f);
       } else {
         float* w = a.ws + (orow * a.n_parts + part) * (HD + 2);
@@ -1202,7 +1221,7 @@ __global__ __launch_bounds__(kWaves * 64) void k_attn_decode_f32(const AttnArgs 
       A = fmaf(wt, s_acc[w][dim], A);
     }
     const size_t orow = (size_t)b * n_q_heads + hq;
-    if (np_b == 1) {                             // the only partition of its sequence: this is the result
+    if (np_b == 1 && !a.new_k) {                 // the only partition of its sequence: this is the result
       store_elem<F32>(a.out, orow * HD + dim, L > 0.f ? A / L : 0.f);
     } else {
       float* w = a.ws + (orow * a.n_parts + part) * (HD + 2);
@@ -1217,6 +1236,7 @@ __global__ __launch_bounds__(kWaves * 64) void k_attn_decode_f32(const AttnArgs 
 }
 
 // Reduction over the partitions of one (sequence, query head): out = sum_s 2^(m_s - M) acc_s / sum_s 2^(m_s - M) l_s.
+// With the newest token's rows given, that token is one more partition, (q . k_new, 1, v_new), computed here.
 // 256 threads: thread (sub, dim) = (tid / HD, tid % HD) merges the partitions sub, sub + 256/HD, ... online,
 // four loads in flight, and the 256/HD partial merges meet in LDS.
 template <typename E, int HD>
@@ -1226,11 +1246,23 @@ __global__ __launch_bounds__(256) void k_attn_reduce(const AttnArgs a, int32_t n
   __shared__ float s_M[NSUB], s_L[NSUB], s_A[NSUB][HD];
   const int32_t hq = blockIdx.x, b = blockIdx.y;
   const int dim = threadIdx.x % HD, sub = threadIdx.x / HD;
-  const int32_t ctx = clamp_ctx(a.ctx[b], a.max_blocks);
+  const int32_t full = clamp_ctx(a.ctx[b], a.max_blocks);
+  const bool with_new = a.new_k != nullptr;
+  const int32_t ctx = with_new && full > 0 ? full - 1 : full;   // the tokens the partitions covered
   int32_t np = ctx <= 0 ? 1 : (ctx + a.part_tokens - 1) / a.part_tokens;
   if (np > a.n_parts) np = a.n_parts;
-  if (np <= 1) return;                          // a lone partition wrote its result itself
+  if (np <= 1 && !with_new) return;             // a lone partition wrote its result itself
   const size_t row = (size_t)b * n_q_heads + hq;
+  // The newest token is one more partition, (s, 1, v_new) with s = q . k_new in the log2 domain like the
+  // partitions' maxima.  Its rows are requested now and used after the partitions have been merged.
+  __shared__ float s_dot[(HD + 63) / 64];
+  const bool add_new = with_new && full > 0;
+  float qk = 0.f, v_new = 0.f;
+  if (add_new && sub == 0) {
+    const size_t kv_row = ((size_t)b * a.n_kv_heads + hq / a.group) * HD;
+    qk = load_elem<E>(a.q, row * HD + dim) * load_elem<E>(a.new_k, kv_row + dim);
+    v_new = load_elem<E>(a.new_v, kv_row + dim);
+  }
   const float* w = a.ws + row * a.n_parts * (HD + 2);
   float M = kNegBig, L = 0.f, A = 0.f;
   for (int32_t s0 = sub; s0 < np; s0 += NSUB * UNR) {
@@ -1263,6 +1295,10 @@ __global__ __launch_bounds__(256) void k_attn_reduce(const AttnArgs a, int32_t n
     s_L[sub] = L;
   }
   s_A[sub][dim] = A;
+  if (add_new && sub == 0) {                     // HD / 64 waves hold the products: each leaves its sum
+    const float wave_sum = quad16_sum(row16_sum(qk));
+    if ((threadIdx.x & 63) == 0) s_dot[threadIdx.x >> 6] = wave_sum;
+  }
   __syncthreads();
   if (sub == 0) {
     float Mt = s_M[0];
@@ -1274,6 +1310,16 @@ __global__ __launch_bounds__(256) void k_attn_reduce(const AttnArgs a, int32_t n
       const float wt = __builtin_amdgcn_exp2f(s_M[i] - Mt);
       Lt = fmaf(wt, s_L[i], Lt);
       At = fmaf(wt, s_A[i][dim], At);
+    }
+    if (add_new) {
+      float d = s_dot[0];
+#pragma unroll
+      for (int i = 1; i < (HD + 63) / 64; ++i) d += s_dot[i];
+      const float s_new = d * a.scale_log2e;
+      const float m2 = fmaxf(Mt, s_new);
+      const float w_old = __builtin_amdgcn_exp2f(Mt - m2), w_new = __builtin_amdgcn_exp2f(s_new - m2);
+      Lt = fmaf(Lt, w_old, w_new);
+      At = fmaf(At, w_old, w_new * v_new);
     }
     store_elem<E>(a.out, row * HD + dim, Lt > 0.f ? At / Lt : 0.f);
   }
@@ -1355,10 +1401,11 @@ static int32_t part_tokens_of(const pie_pool* p) {
 }
 
 int launch_attn_plan(const pie_pool* p, const int32_t* d_ctx, int32_t batch, int32_t max_blocks, hipStream_t s,
-                     bool reset_clock, const AttnWork* work) {
+                     bool reset_clock, const AttnWork* work, bool without_last) {
   const AttnWork w = work ? *work : pool_work(p);
   if (batch > kMaxPlanBatch || batch > w.lay_batch || max_blocks > w.lay_max_blocks) return PIE_EINVAL;
-  hipLaunchKernelGGL(k_attn_plan, dim3(1), dim3(256), 0, s, d_ctx, batch, part_tokens_of(p), max_blocks, plan_items(w),
+  hipLaunchKernelGGL(k_attn_plan, dim3(1), dim3(256), 0, s, d_ctx, batch, part_tokens_of(p), max_blocks,
+                     without_last ? 1 : 0, plan_items(w),
                      plan_hdr(w), plan_counters(w), w.n_counters, p->d_err, reset_clock ? p->d_clock : nullptr);
   PIE_HIP(hipGetLastError());
   return PIE_OK;
@@ -1421,7 +1468,7 @@ static int launch_mfma(const pie_pool* p, AttnArgs a, int32_t layer_row, int32_t
   if (e0) PIE_HIP(hipEventRecord(e0, s));
   // `done` (an event that completes with the layer's last kernel) rides on that kernel's own completion
   // signal instead of a packet of its own behind it
-  const bool reduce = a.n_parts > 1;
+  const bool reduce = a.n_parts > 1 || a.new_k;
   if (done && !reduce)
     hipExtLaunchKernelGGL((k_attn_decode_mfma<E, HD, SPLIT, VALU>), dim3(grid), dim3(kWaves * 64), (uint32_t)lds, s,
                           nullptr, done, 0, a);
@@ -1448,7 +1495,7 @@ static int launch_f32(const AttnArgs& a, int32_t batch, int32_t n_q_heads, int32
   hipLaunchKernelGGL((k_attn_decode_f32<HD>), dim3(max_items, n_q_heads), dim3(kWaves * 64), 0, s, a);
   PIE_HIP(hipGetLastError());
   if (e1) PIE_HIP(hipEventRecord(e1, s));
-  if (a.n_parts > 1) {
+  if (a.n_parts > 1 || a.new_k) {
     hipLaunchKernelGGL((k_attn_reduce<F32, HD>), dim3(n_q_heads, batch), dim3(256), 0, s, a, n_q_heads);
     PIE_HIP(hipGetLastError());
   }
@@ -1457,11 +1504,13 @@ static int launch_f32(const AttnArgs& a, int32_t batch, int32_t n_q_heads, int32
 }
 
 // Needs launch_attn_plan and launch_attn_resolve (for region layer & 1) earlier on the same stream, with the
-// same batch, table width and context lengths.
+// same batch, table width and context lengths.  d_k_new / d_v_new: the newest token's rows of this layer, taken
+// from there instead of from the cache (the planning launch must have been told: without_last); NULL = the cache
+// holds every token.
 int launch_attn_decode(const pie_pool* p, int32_t layer, const void* d_q, int32_t max_blocks, const int32_t* d_ctx,
                        int32_t batch, void* d_out, hipStream_t s, hipEvent_t k_start, hipEvent_t k_end,
                        int32_t ticket_index, unsigned long long* clock_row, const LayerView* view, hipEvent_t done,
-                       const AttnWork* work) {
+                       const AttnWork* work, const void* d_k_new, const void* d_v_new) {
   const pie_config& c = p->cfg;
   const AttnWork w = work ? *work : pool_work(p);
   if (((uintptr_t)d_q | (uintptr_t)d_out) % 16) return PIE_EINVAL;
@@ -1497,6 +1546,9 @@ int launch_attn_decode(const pie_pool* p, int32_t layer, const void* d_q, int32_
   a.max_items = batch * n_parts;
   a.clock = clock_row;
   a.clock_wg = nullptr;         // set by the launcher of a persistent grid that fits the per-workgroup words
+  if ((d_k_new == nullptr) != (d_v_new == nullptr)) return PIE_EINVAL;
+  a.new_k = (const char*)d_k_new;
+  a.new_v = (const char*)d_v_new;
   const bool hd128 = c.head_dim == 128;
   const int32_t row = clock_row ? (int32_t)((clock_row - p->d_clock) / kClockRow) : 0;
   switch (c.dtype) {

@@ -379,7 +379,8 @@ int pie_layer_step(pie_layer_pool* lp, const void* d_q_all, const void* d_k_new,
   for (int32_t k = 0; k < lp->n_layers; ++k) {
     // one ticket counter per launch since the last planning kernel; there are as many as GPU slots
     if (k % n_slots == 0) {
-      if ((rc = pie::launch_attn_plan(p, d_ctx_lens, batch, max_blocks, cs))) return rc;
+      // with a new token the attention takes it from the new rows, the rest of the context from the cache
+      if ((rc = pie::launch_attn_plan(p, d_ctx_lens, batch, max_blocks, cs, false, nullptr, d_k_new != nullptr))) return rc;
       if (k == 0 && (rc = pie::launch_attn_resolve(p, d_block_table, d_ctx_lens, batch, max_blocks, true, false, true,
                                                    false, cs)))
         return rc;
@@ -411,7 +412,10 @@ int pie_layer_step(pie_layer_pool* lp, const void* d_q_all, const void* d_k_new,
         return rc;
     }
     if ((rc = pie::launch_attn_decode(p, slot, (const char*)d_q_all + k * q_stride, max_blocks, d_ctx_lens, batch,
-                                      (char*)d_out_all + k * q_stride, cs, nullptr, nullptr, k % n_slots)))
+                                      (char*)d_out_all + k * q_stride, cs, nullptr, nullptr, k % n_slots, nullptr,
+                                      nullptr, nullptr, nullptr,
+                                      d_k_new ? (const char*)d_k_new + k * kv_stride : nullptr,
+                                      d_v_new ? (const char*)d_v_new + k * kv_stride : nullptr)))
       return rc;
     if (p->layer_compute_us > 0.f && (rc = pie::launch_busy(p->layer_compute_us, p->wall_clock_khz, cs))) return rc;
     PIE_HIP(hipEventRecord(lp->ev_slot[slot], cs));

@@ -283,7 +283,7 @@ static void publish_stage_list(pie_pool* p, int r, int32_t n, const int32_t* han
 }
 
 // The new token's rows for the tail blocks that a prefetch brings in: written into the staged copies on the
-// swap stream right behind the copy, so that the compute stream does not have to.
+// swap stream right behind the copy, so that the write-back takes them home.
 struct StagedAppend {
   const void* d_k;
   const void* d_v;
@@ -337,6 +337,7 @@ static int swap_in_impl(pie_pool* p, int32_t layer, int32_t n, const int32_t* ha
   int rc;
   if ((rc = order_after(s, p->ev_read[r], p->ev_read_rec[r], on_host))) return rc;
   if ((rc = order_after(s, p->ev_out[r], p->ev_out_rec[r], on_host))) return rc;
+  if ((rc = order_after(s, p->ev_app[r], p->ev_app_rec[r], on_host))) return rc;
   if ((rc = order_after(s, p->ev_migrate, p->ev_migrate_rec, on_host))) return rc;
   if (job && (rc = order_after(s, p->ev_map, p->ev_map_rec, on_host))) return rc;   // the append reads the map
   if (!skip_copy) {
@@ -344,12 +345,18 @@ static int swap_in_impl(pie_pool* p, int32_t layer, int32_t n, const int32_t* ha
     if ((rc = copy_blocks(p, 0, layer, src, dst, cp, s))) return rc;
     if ((rc = note(t1, s))) return rc;
   }
-  if (job && (rc = launch_kv_append(p, layer, 1, job->d_k, job->d_v, job->d_table, job->max_blocks, job->d_ctx,
-                                    job->batch, kAppendStaged, s)))
-    return rc;
-  // phase two happens when this event completes
+  // phase two happens when this event completes: the blocks are there
   PIE_HIP(hipEventRecord(p->ev_in[r], s));
   p->ev_in_rec[r] = true;
+  // The newest token's rows go into the staged tail blocks behind the copy.  The step's attention takes that
+  // token from the rows themselves, so it does not wait for this; the write-back does.
+  if (job) {
+    if ((rc = launch_kv_append(p, layer, 1, job->d_k, job->d_v, job->d_table, job->max_blocks, job->d_ctx,
+                               job->batch, kAppendStaged, s)))
+      return rc;
+    PIE_HIP(hipEventRecord(p->ev_app[r], s));
+    p->ev_app_rec[r] = true;
+  }
   if (!skip_copy) p->bytes_in += (uint64_t)n * p->block_bytes;
   return PIE_OK;
 }
@@ -377,6 +384,7 @@ static int swap_out_impl(pie_pool* p, int32_t layer, int32_t n, const int32_t* h
   const CopyPlan cp = plan_copy(p, src, dst);
   const bool on_host = n > 0 && cp.path == PIE_SWAP_DMA && !p->dma_stream_order;
   if ((rc = order_after(s, p->ev_in[r], p->ev_in_rec[r], on_host))) return rc;
+  if ((rc = order_after(s, p->ev_app[r], p->ev_app_rec[r], on_host))) return rc;
   if (after_read && (rc = order_after(s, p->ev_read[r], p->ev_read_rec[r], on_host))) return rc;
   if ((rc = note(t0, s))) return rc;
   if ((rc = copy_blocks(p, 1, layer, src, dst, cp, s))) return rc;
@@ -508,7 +516,7 @@ int pie_pool_init(const pie_config* cfg, void* d_base, size_t d_bytes, void* h_p
       p->h_kv_dev = (char*)dev_ptr;
     }
     hipEvent_t* evs[] = {&p->ev_in[0], &p->ev_in[1], &p->ev_read[0], &p->ev_read[1], &p->ev_out[0], &p->ev_out[1],
-                         &p->ev_compute, &p->ev_migrate, &p->ev_map};
+                         &p->ev_compute, &p->ev_migrate, &p->ev_map, &p->ev_app[0], &p->ev_app[1], &p->ev_append};
     for (hipEvent_t* e : evs) {
       hipError_t err = hipEventCreateWithFlags(e, hipEventDisableTiming);
       if (err != hipSuccess) { g_last_hip_error = (int)err; (void)hipGetLastError(); return fail(PIE_EHIP); }
@@ -563,7 +571,8 @@ int pie_pool_destroy(pie_pool* p) {
   if (p->device) {
     for (hipStream_t s : p->streams_seen) (void)hipStreamSynchronize(s);
     hipEvent_t evs[] = {p->ev_in[0], p->ev_in[1], p->ev_read[0], p->ev_read[1], p->ev_out[0], p->ev_out[1],
-                        p->ev_compute, p->ev_migrate, p->ev_map, p->ev_step_start, p->ev_pre_end[0], p->ev_pre_end[1]};
+                        p->ev_compute, p->ev_migrate, p->ev_map, p->ev_step_start, p->ev_pre_end[0], p->ev_pre_end[1],
+                        p->ev_app[0], p->ev_app[1], p->ev_append};
     for (hipEvent_t e : evs)
       if (e) (void)hipEventDestroy(e);
     for (auto& le : p->lev) {
@@ -978,16 +987,27 @@ static int step_body(pie_pool* p, const StepJob& j) {
   if (L > 1) publish_stage_list(p, 1, n_prefetch, h_prefetch);
   if ((rc = wait_if(cs, p->ev_migrate, p->ev_migrate_rec))) return rc;
   if ((rc = flush_map(p, cs))) return rc;
-  if ((rc = launch_attn_plan(p, d_ctx_lens, batch, max_blocks, cs, clocked))) return rc;
+  // With a new token, the attention reads the context without it from the cache and takes the token itself from
+  // the new rows (the reduction kernel adds it), so no layer waits for the appends that store the rows: the one
+  // launch for the GPU-homed tail blocks of every layer runs on the write-back stream beside the first layers
+  // (the compute stream waits for it when the step ends, and then only if the host does not see it finished),
+  // and the host-homed tails get theirs on the swap-in stream, behind the copy that stages them for a layer.
+  const bool with_new = d_k_new != nullptr;
+  const bool staged_tails = with_new && n_dirty > 0;
+  if (with_new) {                                // the appends read the maps sent above
+    PIE_HIP(hipEventRecord(p->ev_map, cs));
+    p->ev_map_rec = true;
+  }
+  if ((rc = launch_attn_plan(p, d_ctx_lens, batch, max_blocks, cs, clocked, nullptr, with_new))) return rc;
   if ((rc = launch_attn_resolve(p, d_block_table, d_ctx_lens, batch, max_blocks, true, true, L > 1, true, cs)))
     return rc;
-  // The new token's rows of every layer go into the GPU-homed tail blocks with one launch up front.  The
-  // tails that are host-homed get theirs on the swap stream, behind the copy that stages them for a layer.
-  const bool staged_tails = d_k_new && n_dirty > 0;
-  if (d_k_new) {
+  if (with_new) {
+    note_stream(p, os);
+    if (os != cs) PIE_HIP(hipStreamWaitEvent(os, p->ev_map, 0));
     if ((rc = launch_kv_append(p, 0, L, d_k_new, d_v_new, d_block_table, max_blocks, d_ctx_lens, batch,
-                               staged_tails ? kAppendGpuHomed : kAppendGpuStrict, cs)))
+                               staged_tails ? kAppendGpuHomed : kAppendGpuStrict, os)))
       return rc;
+    PIE_HIP(hipEventRecord(p->ev_append, os));
   }
   StagedAppend job{nullptr, nullptr, d_block_table, d_ctx_lens, max_blocks, batch};
   auto job_for = [&](int32_t l) -> const StagedAppend* {
@@ -996,10 +1016,6 @@ static int step_body(pie_pool* p, const StepJob& j) {
     job.d_v = (const char*)d_v_new + l * kv_stride;
     return &job;
   };
-  if (staged_tails) {                            // the swap stream's appends read the maps sent above
-    PIE_HIP(hipEventRecord(p->ev_map, cs));
-    p->ev_map_rec = true;
-  }
   // layer 0's blocks have no earlier layer to hide behind
   if (n_prefetch > 0) {
     if ((rc = swap_in_impl(p, 0, n_prefetch, h_prefetch, is, true, mark(p->lev[0].in_start, 0, kClockInStart),
@@ -1040,7 +1056,9 @@ static int step_body(pie_pool* p, const StepJob& j) {
     if ((rc = launch_attn_decode(p, l, (const char*)d_q_all + l * q_stride, max_blocks, d_ctx_lens, batch,
                                  (char*)d_out_all + l * q_stride, cs, timed ? p->lev[l].k_start : nullptr,
                                  timed ? p->lev[l].k_end : nullptr, -1, clock_row(l), nullptr,
-                                 standin ? nullptr : read_done)))
+                                 standin ? nullptr : read_done, nullptr,
+                                 with_new ? (const char*)d_k_new + l * kv_stride : nullptr,
+                                 with_new ? (const char*)d_v_new + l * kv_stride : nullptr)))
       return rc;
     if (standin && (rc = launch_busy(p->layer_compute_us, p->wall_clock_khz, cs, clock_row(l), read_done)))
       return rc;
@@ -1087,6 +1105,16 @@ static int step_body(pie_pool* p, const StepJob& j) {
     p->pre_timed = p->timing;
   }
   if (clocked && (rc = launch_clock_fold(p->d_clock, L, cs))) return rc;
+  // Whatever follows this step on the compute stream, or waits for the step's compute work, finds the new rows
+  // in the GPU-homed tail blocks.  That launch ran beside the first layers: usually the host sees it finished.
+  if (with_new && os != cs) {
+    const hipError_t e = hipEventQuery(p->ev_append);
+    if (e != hipSuccess) {
+      (void)hipGetLastError();
+      if (e != hipErrorNotReady) { g_last_hip_error = (int)e; return PIE_EHIP; }
+      PIE_HIP(hipStreamWaitEvent(cs, p->ev_append, 0));
+    }
+  }
   // later migrations wait for the step's compute work
   PIE_HIP(hipEventRecord(p->ev_compute, cs));
   p->ev_compute_rec = true;

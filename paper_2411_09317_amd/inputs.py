@@ -198,9 +198,11 @@ class DecodeCase:
         return int(self.n_blocks.max()) if len(self.n_blocks) else 0
 
 
-def make_case(w: Workload, host_fraction: float | None = None) -> DecodeCase:
-    """Draw a whole decode case on the host (use only for sizes that fit RAM)."""
-    ctx = draw_ctx_lens(w)
+def make_case(w: Workload, host_fraction: float | None = None, ctx_lens=None) -> DecodeCase:
+    """Draw a whole decode case on the host (use only for sizes that fit RAM).  ctx_lens: given context
+    lengths (one per sequence of the workload's batch) instead of drawn ones."""
+    ctx = draw_ctx_lens(w) if ctx_lens is None else np.asarray(ctx_lens, dtype=np.int32)
+    assert ctx.shape == (w.batch,)
     nb = blocks_needed(ctx, w.block_tokens)
     mask = draw_host_mask(w, nb, host_fraction)
     q = to_storage(draw_values(w, (w.n_layers, w.batch, w.n_q_heads, w.head_dim), 10), w.dtype)

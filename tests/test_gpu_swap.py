@@ -215,6 +215,43 @@ def test_step_matches_oracle_for_any_residency(path, dtype, hq, hkv, d):
     assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
 
 
+@pytest.mark.parametrize("dtype,hq,hkv,d,part", [(I.DTYPE_F16, 8, 4, 128, 256), (I.DTYPE_F16, 4, 4, 64, 512),
+                                                 (I.DTYPE_BF16, 8, 1, 128, 256), (I.DTYPE_F32, 4, 2, 64, 256)])
+def test_step_takes_the_newest_token_from_its_rows_at_every_edge_of_the_context(dtype, hq, hkv, d, part):
+    """pie_step reads the context without its last token from the cache and that token from k_new / v_new.
+    Contexts at the edges of that split: the token alone (1), alone in a fresh block (17, 257), first of a new
+    partition (part + 1), last of one (part), and ordinary ones; all resident, and with every second tail block
+    and a third of the others on the host.  Against the float64 oracle, and residency changes no bit."""
+    ctx = [1, 2, 15, 16, 17, part - 1, part, part + 1, part + 17, 2 * part, 2 * part + 1, 3 * part - 5, 700, 33]
+    w = I.scaled(W, dtype=dtype, n_q_heads=hq, n_kv_heads=hkv, head_dim=d, n_layers=3, batch=len(ctx))
+    tol = {I.DTYPE_F32: 1e-5, I.DTYPE_F16: 2e-3, I.DTYPE_BF16: 1e-2}[dtype]
+    streams = (torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream())
+    outs = []
+    for f in (0.0, 0.3):
+        case = I.make_case(w, host_fraction=f, ctx_lens=ctx)
+        if f > 0:
+            host_tails(case)
+        n = int(case.n_blocks.sum())
+        lib, mod, table = GH.make_pools(case, n, n, n, upto_ctx=case.ctx_lens - 1, fill=H.nan_fill(dtype))
+        lib.set_attn_partition(part)
+        got, pf, dirty = run_step(lib, case, table, streams)
+        assert lib.check_errors() == 0
+        assert np.isfinite(got).all()
+        assert f == 0 or len(dirty) > 0
+        for l in range(w.n_layers):
+            ref = A.dense_attention(*H.dense_f64(case, l), case.ctx_lens)
+            assert GH.rowwise_rel_err(got[l], ref) <= tol
+            assert np.abs(got[l] - ref).max() <= (1e-5 if dtype == I.DTYPE_F32 else 2e-2)
+            # a context of one token: the output is that token's value row
+            v0 = H.dense_f64(case, l)[2][0][0]                         # [Hkv][d] of sequence 0's only token
+            assert np.allclose(got[l][0].astype(np.float64), np.repeat(v0, hq // hkv, axis=0), rtol=tol, atol=1e-6)
+        mod.step(case.q, *new_token_rows(case), table, case.ctx_lens)
+        assert_images_equal(lib, mod, staging=False)
+        outs.append(got)
+        lib.close()
+    assert np.array_equal(outs[0], outs[1])
+
+
 def test_two_steps_in_a_row_and_timing_stats():
     w = I.scaled(W, n_layers=4)
     case = host_tails(I.make_case(w))
