@@ -214,6 +214,34 @@ def host_time_in_step(dw, streams, pf, dirty, n=10):
     return res
 
 
+def dirty_tail_leg(w, dw, streams, f, tail_share, base_step_ms, n_steps=10):
+    """Below the knee, with write-backs: the same number of host blocks as the fixed-fraction leg, but a share of
+    them are tail blocks (they receive the step's token, so every layer stages them, appends to the staged copy
+    and writes them back).  The seeded demotion order rarely names a tail at such a small fraction, so that leg
+    has nothing to write back; this one says what the write-back costs.  All blocks must be GPU-homed on entry
+    and are again on return."""
+    from paper_2411_09317_amd import binding as B
+    T = w.block_tokens
+    n_host = int(round(f * dw.total_blocks))
+    n_tail = max(1, int(round(tail_share * n_host)))
+    tails = [int(dw.table[b, (int(dw.ctx_lens[b]) - 1) // T]) for b in range(w.batch)][:n_tail]
+    tail_set = set(tails)
+    others = [int(h) for h in dw.order if int(h) not in tail_set][:n_host - len(tails)]
+    hs = np.asarray(tails + others, dtype=np.int32)
+    dw.pool.migrate(hs, B.HOST, streams[1])
+    dw.pool.sync()
+    pf, dirty = dw.pool.prefetch_list(dw.table, dw.ctx_lens)
+    assert len(dirty) == len(tails) and len(pf) == len(hs)
+    timed_steps(dw, streams, 2, pf, dirty)
+    s = timed_steps(dw, streams, n_steps, pf, dirty) / n_steps
+    assert dw.pool.check_errors() == 0
+    dw.pool.migrate(hs, B.GPU, streams[1])
+    dw.pool.sync()
+    return {"host_blocks": len(hs), "dirty_tail_blocks": len(tails), "ms_per_step": s * 1e3,
+            "tokens_per_s": w.batch / s, "inflation_e2e": s * 1e3 / base_step_ms - 1.0,
+            "bytes_out_per_layer": len(tails) * w.block_bytes}
+
+
 def scattered_kernel_leg(w, dw, streams, f_small, f_link, base_kernel_ms, base_step_ms, achieved):
     """The gather kernel on a host pool full of holes: twice the blocks go to the host and every other one comes
     back, so a layer's prefetch is as many pieces as blocks and the copy engine would pay its per-call cost for
@@ -902,6 +930,9 @@ def main():
             dw, streams, *dw.pool.prefetch_list(dw.table, dw.ctx_lens))
         dw.pool.set_host_fraction(0.0, dw.order, streams[1])
         dw.pool.sync()
+        # the same number of host blocks with a quarter of them tail blocks: what the dirty write-back costs
+        result["swap_below_knee"]["with_dirty_tails"] = dirty_tail_leg(w, dw, streams, args.below_knee_fraction, 0.25,
+                                                                       base_step_ms)
         # and through the gather kernel, on a host pool full of holes
         result["swap_kernel"] = scattered_kernel_leg(w, dw, streams, args.below_knee_fraction, args.scatter_link_fraction,
                                                      base_kernel_ms, base_step_ms, achieved)
