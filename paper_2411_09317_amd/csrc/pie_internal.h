@@ -152,11 +152,9 @@ struct pie_pool {
   hipEvent_t ev_compute = nullptr;                // last compute work
   hipEvent_t ev_migrate = nullptr;                // last migration
   hipEvent_t ev_map = nullptr;                    // last map update sent on the compute stream
-  hipEvent_t ev_app[2] = {nullptr, nullptr};      // last append into the staged copies of region r (swap-in stream)
   hipEvent_t ev_append = nullptr;                 // a step's append into the GPU-homed tail blocks (write-back stream)
   bool ev_in_rec[2] = {false, false}, ev_read_rec[2] = {false, false}, ev_out_rec[2] = {false, false};
   bool ev_compute_rec = false, ev_migrate_rec = false, ev_map_rec = false, migrate_pending = false;
-  bool ev_app_rec[2] = {false, false};
   std::vector<hipStream_t> streams_seen;
 
   // options

@@ -283,7 +283,9 @@ static void publish_stage_list(pie_pool* p, int r, int32_t n, const int32_t* han
 }
 
 // The new token's rows for the tail blocks that a prefetch brings in: written into the staged copies on the
-// swap stream right behind the copy, so that the write-back takes them home.
+// write-back stream once the copy has arrived, so that the write-back takes them home.  (Not on the swap-in
+// stream behind the copy: the next layer's copy on that stream would wait for the kernel, and the link would
+// idle between any two transfers for as long as a kernel behind a copy-engine transfer takes to start.)
 struct StagedAppend {
   const void* d_k;
   const void* d_v;
@@ -305,10 +307,9 @@ static int note(const Mark& m, hipStream_t s) {
 }
 
 // skip_copy: the region already holds exactly these blocks of this layer (brought in behind the previous
-// step's last layer); only the ordering, the staged append and the completion event are enqueued.
+// step's last layer); only the ordering and the completion event are enqueued.
 static int swap_in_impl(pie_pool* p, int32_t layer, int32_t n, const int32_t* handles, hipStream_t s,
-                        bool validated, const Mark& t0, const Mark& t1, const StagedAppend* job = nullptr,
-                        bool skip_copy = false) {
+                        bool validated, const Mark& t0, const Mark& t1, bool skip_copy = false) {
   const int r = layer & 1;
   p->pre_valid = false;
   if (!validated) {
@@ -337,35 +338,26 @@ static int swap_in_impl(pie_pool* p, int32_t layer, int32_t n, const int32_t* ha
   int rc;
   if ((rc = order_after(s, p->ev_read[r], p->ev_read_rec[r], on_host))) return rc;
   if ((rc = order_after(s, p->ev_out[r], p->ev_out_rec[r], on_host))) return rc;
-  if ((rc = order_after(s, p->ev_app[r], p->ev_app_rec[r], on_host))) return rc;
   if ((rc = order_after(s, p->ev_migrate, p->ev_migrate_rec, on_host))) return rc;
-  if (job && (rc = order_after(s, p->ev_map, p->ev_map_rec, on_host))) return rc;   // the append reads the map
   if (!skip_copy) {
     if ((rc = note(t0, s))) return rc;
     if ((rc = copy_blocks(p, 0, layer, src, dst, cp, s))) return rc;
     if ((rc = note(t1, s))) return rc;
   }
-  // phase two happens when this event completes: the blocks are there
+  // phase two happens when this event completes
   PIE_HIP(hipEventRecord(p->ev_in[r], s));
   p->ev_in_rec[r] = true;
-  // The newest token's rows go into the staged tail blocks behind the copy.  The step's attention takes that
-  // token from the rows themselves, so it does not wait for this; the write-back does.
-  if (job) {
-    if ((rc = launch_kv_append(p, layer, 1, job->d_k, job->d_v, job->d_table, job->max_blocks, job->d_ctx,
-                               job->batch, kAppendStaged, s)))
-      return rc;
-    PIE_HIP(hipEventRecord(p->ev_app[r], s));
-    p->ev_app_rec[r] = true;
-  }
   if (!skip_copy) p->bytes_in += (uint64_t)n * p->block_bytes;
   return PIE_OK;
 }
 
 // after_read: the copies wait for the layer's computation as well.  A caller whose computation only reads the
-// staged blocks (pie_step: the new token's rows are appended on the swap-in's own stream, behind the copy that
-// stages the block) passes false, and the blocks go home as soon as they are staged and appended to.
+// staged blocks (pie_step: the new token's rows are appended by `job`, below) passes false, and the blocks go
+// home as soon as they are staged and appended to.
+// job: the newest token's rows, to be written into the staged tail blocks first (on this stream, ahead of the
+// copies that take the blocks home; the stream must have seen the map updates the append reads).
 static int swap_out_impl(pie_pool* p, int32_t layer, int32_t n, const int32_t* handles, hipStream_t s,
-                         const Mark& t0, const Mark& t1, bool after_read = true) {
+                         const Mark& t0, const Mark& t1, bool after_read = true, const StagedAppend* job = nullptr) {
   if (layer < 0 || layer >= p->cfg.n_layers) return PIE_EINVAL;
   std::vector<uint8_t> seen;
   int rc = check_handles(p, n, handles, PIE_WHERE_HOST, seen);
@@ -384,8 +376,10 @@ static int swap_out_impl(pie_pool* p, int32_t layer, int32_t n, const int32_t* h
   const CopyPlan cp = plan_copy(p, src, dst);
   const bool on_host = n > 0 && cp.path == PIE_SWAP_DMA && !p->dma_stream_order;
   if ((rc = order_after(s, p->ev_in[r], p->ev_in_rec[r], on_host))) return rc;
-  if ((rc = order_after(s, p->ev_app[r], p->ev_app_rec[r], on_host))) return rc;
   if (after_read && (rc = order_after(s, p->ev_read[r], p->ev_read_rec[r], on_host))) return rc;
+  if (job && (rc = launch_kv_append(p, layer, 1, job->d_k, job->d_v, job->d_table, job->max_blocks, job->d_ctx,
+                                    job->batch, kAppendStaged, s)))
+    return rc;
   if ((rc = note(t0, s))) return rc;
   if ((rc = copy_blocks(p, 1, layer, src, dst, cp, s))) return rc;
   if ((rc = note(t1, s))) return rc;
@@ -516,7 +510,7 @@ int pie_pool_init(const pie_config* cfg, void* d_base, size_t d_bytes, void* h_p
       p->h_kv_dev = (char*)dev_ptr;
     }
     hipEvent_t* evs[] = {&p->ev_in[0], &p->ev_in[1], &p->ev_read[0], &p->ev_read[1], &p->ev_out[0], &p->ev_out[1],
-                         &p->ev_compute, &p->ev_migrate, &p->ev_map, &p->ev_app[0], &p->ev_app[1], &p->ev_append};
+                         &p->ev_compute, &p->ev_migrate, &p->ev_map, &p->ev_append};
     for (hipEvent_t* e : evs) {
       hipError_t err = hipEventCreateWithFlags(e, hipEventDisableTiming);
       if (err != hipSuccess) { g_last_hip_error = (int)err; (void)hipGetLastError(); return fail(PIE_EHIP); }
@@ -572,7 +566,7 @@ int pie_pool_destroy(pie_pool* p) {
     for (hipStream_t s : p->streams_seen) (void)hipStreamSynchronize(s);
     hipEvent_t evs[] = {p->ev_in[0], p->ev_in[1], p->ev_read[0], p->ev_read[1], p->ev_out[0], p->ev_out[1],
                         p->ev_compute, p->ev_migrate, p->ev_map, p->ev_step_start, p->ev_pre_end[0], p->ev_pre_end[1],
-                        p->ev_app[0], p->ev_app[1], p->ev_append};
+                        p->ev_append};
     for (hipEvent_t e : evs)
       if (e) (void)hipEventDestroy(e);
     for (auto& le : p->lev) {
@@ -991,7 +985,8 @@ static int step_body(pie_pool* p, const StepJob& j) {
   // the new rows (the reduction kernel adds it), so no layer waits for the appends that store the rows: the one
   // launch for the GPU-homed tail blocks of every layer runs on the write-back stream beside the first layers
   // (the compute stream waits for it when the step ends, and then only if the host does not see it finished),
-  // and the host-homed tails get theirs on the swap-in stream, behind the copy that stages them for a layer.
+  // and the host-homed tails get theirs on the same stream once the copy that stages them for a layer has
+  // arrived, just ahead of their write-back.
   const bool with_new = d_k_new != nullptr;
   const bool staged_tails = with_new && n_dirty > 0;
   if (with_new) {                                // the appends read the maps sent above
@@ -1019,7 +1014,7 @@ static int step_body(pie_pool* p, const StepJob& j) {
   // layer 0's blocks have no earlier layer to hide behind
   if (n_prefetch > 0) {
     if ((rc = swap_in_impl(p, 0, n_prefetch, h_prefetch, is, true, mark(p->lev[0].in_start, 0, kClockInStart),
-                           mark(p->lev[0].in_end, 0, kClockInEnd), job_for(0), pre_hit)))
+                           mark(p->lev[0].in_end, 0, kClockInEnd), pre_hit)))
       return rc;
     p->lev[0].in_used = (timed || clocked) && !pre_hit;
   }
@@ -1071,7 +1066,7 @@ static int step_body(pie_pool* p, const StepJob& j) {
       // already hold this layer's work then.
       if ((rc = swap_in_impl(p, l + 1, n_prefetch, h_prefetch, is, true,
                              mark(p->lev[l + 1].in_start, l + 1, kClockInStart),
-                             mark(p->lev[l + 1].in_end, l + 1, kClockInEnd), job_for(l + 1))))
+                             mark(p->lev[l + 1].in_end, l + 1, kClockInEnd))))
         return rc;
       p->lev[l + 1].in_used = timed || clocked;
       if (p->in_on_host[(l + 1) & 1]) {            // the host has just waited for layer l - 1 to end
@@ -1081,26 +1076,24 @@ static int step_body(pie_pool* p, const StepJob& j) {
       }
     }
     if (n_dirty > 0 && d_k_new) {
-      // The staged tail blocks are final once the swap stream has appended the new rows behind the copy that
-      // staged them; the attention only reads them.  So they go home as soon as this layer's swap-in has
-      // completed, beside the layer's computation, not after it: the write-back is then neither something
+      // The attention only reads the staged tail blocks.  So they get the new rows and go home as soon as this
+      // layer's swap-in has completed, beside the layer's computation, not after it: the write-back is then neither something
       // the host waits for at the layer's end (with the next layer's kernels not yet queued) nor a link in
       // the chain  layer l ends -> write back -> prefetch layer l + 2 into the same region.
       if ((rc = swap_out_impl(p, l, n_dirty, h_dirty, os, mark(p->lev[l].out_start, l, kClockOutStart),
-                              mark(p->lev[l].out_end, l, kClockOutEnd), false)))
+                              mark(p->lev[l].out_end, l, kClockOutEnd), false, job_for(l))))
         return rc;
       p->lev[l].out_used = timed || clocked;
     }
   }
   // The next step will most likely touch the same host blocks: bring layer 0's in now, behind this step's
-  // last layer, into the region the layer before last has just left (the staged append of the next token's
-  // rows waits for the next step).  If anything about those blocks changes first, the copy is repeated.
+  // last layer, into the region the layer before last has just left.  If anything about those blocks changes first, the copy is repeated.
   if (p->cross_step_prefetch && n_prefetch > 0 && L >= 2) {
     Mark m1;                                     // two marks in turn: the step that uses the copy reads its mark
     p->pre_idx ^= 1;                             // after this step has written the other one
     if (timed) m1.ev = p->ev_pre_end[p->pre_idx];
     if (clocked) m1.clk = p->d_clock + (size_t)L * kClockRow + 1 + p->pre_idx;
-    if ((rc = swap_in_impl(p, 0, n_prefetch, h_prefetch, is, true, Mark(), m1, nullptr))) return rc;
+    if ((rc = swap_in_impl(p, 0, n_prefetch, h_prefetch, is, true, Mark(), m1))) return rc;
     p->pre_valid = true;
     p->pre_timed = p->timing;
   }
