@@ -252,6 +252,33 @@ def test_step_takes_the_newest_token_from_its_rows_at_every_edge_of_the_context(
     assert np.array_equal(outs[0], outs[1])
 
 
+@pytest.mark.parametrize("path", PATHS)
+def test_step_on_one_stream_and_on_the_default_stream_gives_the_same_bits_and_bytes(path):
+    """The three streams may be one: a single stream for everything, or none given (the default stream).  The
+    appends, copies and write-backs then simply queue up in order; outputs and both pools' bytes are those of the
+    three-stream step."""
+    w = I.scaled(W, n_layers=4)
+    outs = []
+    for streams in ("three", "one", "default"):
+        case = host_tails(I.make_case(w))
+        n = int(case.n_blocks.sum())
+        lib, mod, table = GH.make_pools(case, n, n, n, upto_ctx=case.ctx_lens - 1, fill=H.nan_fill(w.dtype))
+        lib.set_swap_path(path)
+        one = torch.cuda.Stream()
+        ss = {"three": (torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream()), "one": (one, one, one),
+              "default": (None, None, None)}[streams]
+        for _ in range(2):                                             # the second step finds layer 0 staged
+            got, pf, dirty = run_step(lib, case, table, ss)
+        assert lib.check_errors() == 0 and len(dirty) > 0
+        mod.step(case.q, *new_token_rows(case), table, case.ctx_lens)
+        assert_images_equal(lib, mod, staging=False)
+        outs.append(got)
+        lib.close()
+    assert np.array_equal(outs[0], outs[1]) and np.array_equal(outs[0], outs[2])
+    ref = A.dense_attention(*H.dense_f64(case, 0), case.ctx_lens)
+    assert GH.rowwise_rel_err(outs[0][0], ref) <= 2e-3
+
+
 def test_two_steps_in_a_row_and_timing_stats():
     w = I.scaled(W, n_layers=4)
     case = host_tails(I.make_case(w))
