@@ -1237,15 +1237,22 @@ __global__ __launch_bounds__(kWaves * 64) void k_attn_decode_f32(const AttnArgs 
 
 // Reduction over the partitions of one (sequence, query head): out = sum_s 2^(m_s - M) acc_s / sum_s 2^(m_s - M) l_s.
 // With the newest token's rows given, that token is one more partition, (q . k_new, 1, v_new), computed here.
-// 256 threads: thread (sub, dim) = (tid / HD, tid % HD) merges the partitions sub, sub + 256/HD, ... online,
-// four loads in flight, and the 256/HD partial merges meet in LDS.
-template <typename E, int HD>
+// 256 threads = 256 / HD groups of HD threads (thread (sub, dim) = (tid / HD, tid % HD)), four loads in flight.
+// BY_HEAD (few partitions): every group takes a query head of its own and all of its partitions.  Otherwise
+// (long contexts) the groups share one head, group sub merging the partitions sub, sub + 256/HD, ... online, and
+// the partial merges meet in LDS.
+template <typename E, int HD, bool BY_HEAD>
 __global__ __launch_bounds__(256) void k_attn_reduce(const AttnArgs a, int32_t n_q_heads) {
   constexpr int NSUB = 256 / HD;
   constexpr int UNR = 4;
+  constexpr int WPH = (HD + 63) / 64;             // waves per group
+  constexpr int STRIDE = BY_HEAD ? 1 : NSUB;
   __shared__ float s_M[NSUB], s_L[NSUB], s_A[NSUB][HD];
-  const int32_t hq = blockIdx.x, b = blockIdx.y;
+  __shared__ float s_dot[NSUB][WPH];
+  const int32_t b = blockIdx.y;
   const int dim = threadIdx.x % HD, sub = threadIdx.x / HD;
+  const int32_t hq = BY_HEAD ? (int32_t)blockIdx.x * NSUB + sub : (int32_t)blockIdx.x;
+  const bool owner = BY_HEAD || sub == 0;         // writes the head's output
   const int32_t full = clamp_ctx(a.ctx[b], a.max_blocks);
   const bool with_new = a.new_k != nullptr;
   const int32_t ctx = with_new && full > 0 ? full - 1 : full;   // the tokens the partitions covered
@@ -1255,21 +1262,20 @@ __global__ __launch_bounds__(256) void k_attn_reduce(const AttnArgs a, int32_t n
   const size_t row = (size_t)b * n_q_heads + hq;
   // The newest token is one more partition, (s, 1, v_new) with s = q . k_new in the log2 domain like the
   // partitions' maxima.  Its rows are requested now and used after the partitions have been merged.
-  __shared__ float s_dot[(HD + 63) / 64];
   const bool add_new = with_new && full > 0;
   float qk = 0.f, v_new = 0.f;
-  if (add_new && sub == 0) {
+  if (add_new && owner) {
     const size_t kv_row = ((size_t)b * a.n_kv_heads + hq / a.group) * HD;
     qk = load_elem<E>(a.q, row * HD + dim) * load_elem<E>(a.new_k, kv_row + dim);
     v_new = load_elem<E>(a.new_v, kv_row + dim);
   }
   const float* w = a.ws + row * a.n_parts * (HD + 2);
   float M = kNegBig, L = 0.f, A = 0.f;
-  for (int32_t s0 = sub; s0 < np; s0 += NSUB * UNR) {
+  for (int32_t s0 = BY_HEAD ? 0 : sub; s0 < np; s0 += STRIDE * UNR) {
     float mi[UNR], li[UNR], ai[UNR];
 #pragma unroll
     for (int u = 0; u < UNR; ++u) {
-      const int32_t sp = s0 + u * NSUB;
+      const int32_t sp = s0 + u * STRIDE;
       const bool live = sp < np;
       const float* wp = w + (size_t)(live ? sp : s0) * (HD + 2);
       mi[u] = live ? wp[0] : kNegBig;
@@ -1290,31 +1296,41 @@ __global__ __launch_bounds__(256) void k_attn_reduce(const AttnArgs a, int32_t n
     }
     M = m_new;
   }
-  if (dim == 0) {
-    s_M[sub] = M;
-    s_L[sub] = L;
+  float Mt = M, Lt = L, At = A;
+  if constexpr (!BY_HEAD) {
+    if (dim == 0) {
+      s_M[sub] = M;
+      s_L[sub] = L;
+    }
+    s_A[sub][dim] = A;
   }
-  s_A[sub][dim] = A;
-  if (add_new && sub == 0) {                     // HD / 64 waves hold the products: each leaves its sum
-    const float wave_sum = quad16_sum(row16_sum(qk));
-    if ((threadIdx.x & 63) == 0) s_dot[threadIdx.x >> 6] = wave_sum;
+  float dot = 0.f;
+  if (add_new && owner) {                        // HD / 64 waves hold a head's products: each has its sum
+    dot = quad16_sum(row16_sum(qk));             // (in every lane)
+    if (WPH > 1 && (threadIdx.x & 63) == 0) s_dot[sub][(threadIdx.x >> 6) % WPH] = dot;
   }
-  __syncthreads();
-  if (sub == 0) {
-    float Mt = s_M[0];
+  if (!BY_HEAD || (add_new && WPH > 1)) __syncthreads();
+  if (owner) {
+    if constexpr (!BY_HEAD) {
+      Mt = s_M[0];
 #pragma unroll
-    for (int i = 1; i < NSUB; ++i) Mt = fmaxf(Mt, s_M[i]);
-    float Lt = 0.f, At = 0.f;
+      for (int i = 1; i < NSUB; ++i) Mt = fmaxf(Mt, s_M[i]);
+      Lt = 0.f;
+      At = 0.f;
 #pragma unroll
-    for (int i = 0; i < NSUB; ++i) {
-      const float wt = __builtin_amdgcn_exp2f(s_M[i] - Mt);
-      Lt = fmaf(wt, s_L[i], Lt);
-      At = fmaf(wt, s_A[i][dim], At);
+      for (int i = 0; i < NSUB; ++i) {
+        const float wt = __builtin_amdgcn_exp2f(s_M[i] - Mt);
+        Lt = fmaf(wt, s_L[i], Lt);
+        At = fmaf(wt, s_A[i][dim], At);
+      }
     }
     if (add_new) {
-      float d = s_dot[0];
+      float d = dot;
+      if constexpr (WPH > 1) {
+        d = s_dot[sub][0];
 #pragma unroll
-      for (int i = 1; i < (HD + 63) / 64; ++i) d += s_dot[i];
+        for (int i = 1; i < WPH; ++i) d += s_dot[sub][i];
+      }
       const float s_new = d * a.scale_log2e;
       const float m2 = fmaxf(Mt, s_new);
       const float w_old = __builtin_amdgcn_exp2f(Mt - m2), w_new = __builtin_amdgcn_exp2f(s_new - m2);
@@ -1325,7 +1341,7 @@ __global__ __launch_bounds__(256) void k_attn_reduce(const AttnArgs a, int32_t n
   }
   // the last workgroups dispatched are the last to end, to within a few of them: those of the last sequence
   // and one per 16 sequences note the time
-  if (a.clock && threadIdx.x == 0 && (b == (int32_t)gridDim.y - 1 || (hq == 0 && (b & 15) == 15)))
+  if (a.clock && threadIdx.x == 0 && (b == (int32_t)gridDim.y - 1 || (blockIdx.x == 0 && (b & 15) == 15)))
     atomicMax(&a.clock[kClockLayerEnd], wall_clock64());
 }
 
@@ -1447,6 +1463,19 @@ int launch_attn_resolve(const pie_pool* p, const int32_t* d_table, const int32_t
   return PIE_OK;
 }
 
+// done: an event that is to complete with this kernel (it rides on the kernel's own completion signal), or NULL
+template <typename E, int HD>
+static void launch_reduce(const AttnArgs& a, int32_t batch, int32_t n_q_heads, hipStream_t s, hipEvent_t done) {
+  constexpr int NSUB = 256 / HD;
+  // up to eight partitions per sequence: a group of HD threads per query head; beyond, the groups share a head
+  const bool by_head = a.n_parts <= 8 && n_q_heads % NSUB == 0;
+  const dim3 grid(by_head ? n_q_heads / NSUB : n_q_heads, batch);
+  if (by_head)
+    hipExtLaunchKernelGGL((k_attn_reduce<E, HD, true>), grid, dim3(256), 0, s, nullptr, done, 0, a, n_q_heads);
+  else
+    hipExtLaunchKernelGGL((k_attn_reduce<E, HD, false>), grid, dim3(256), 0, s, nullptr, done, 0, a, n_q_heads);
+}
+
 template <typename E, int HD, bool SPLIT, bool VALU = false>
 static int launch_mfma(const pie_pool* p, AttnArgs a, int32_t layer_row, int32_t batch, int32_t n_q_heads,
                        hipStream_t s, hipEvent_t e0, hipEvent_t e1, hipEvent_t done) {
@@ -1476,14 +1505,8 @@ static int launch_mfma(const pie_pool* p, AttnArgs a, int32_t layer_row, int32_t
     hipLaunchKernelGGL((k_attn_decode_mfma<E, HD, SPLIT, VALU>), dim3(grid), dim3(kWaves * 64), lds, s, a);
   PIE_HIP(hipGetLastError());
   if (e1) PIE_HIP(hipEventRecord(e1, s));
-  if (reduce) {
-    if (done)
-      hipExtLaunchKernelGGL((k_attn_reduce<E, HD>), dim3(n_q_heads, batch), dim3(256), 0, s, nullptr, done, 0, a,
-                            n_q_heads);
-    else
-      hipLaunchKernelGGL((k_attn_reduce<E, HD>), dim3(n_q_heads, batch), dim3(256), 0, s, a, n_q_heads);
-    PIE_HIP(hipGetLastError());
-  }
+  if (reduce) launch_reduce<E, HD>(a, batch, n_q_heads, s, done);
+  PIE_HIP(hipGetLastError());
   return PIE_OK;
 }
 
@@ -1496,7 +1519,7 @@ static int launch_f32(const AttnArgs& a, int32_t batch, int32_t n_q_heads, int32
   PIE_HIP(hipGetLastError());
   if (e1) PIE_HIP(hipEventRecord(e1, s));
   if (a.n_parts > 1 || a.new_k) {
-    hipLaunchKernelGGL((k_attn_reduce<F32, HD>), dim3(n_q_heads, batch), dim3(256), 0, s, a, n_q_heads);
+    launch_reduce<F32, HD>(a, batch, n_q_heads, s, nullptr);
     PIE_HIP(hipGetLastError());
   }
   if (done) PIE_HIP(hipEventRecord(done, s));     // the fp32 path is not tuned: an ordinary record

@@ -65,7 +65,9 @@ def test_controller_grows_while_swaps_stay_hidden_and_gives_back_when_they_do_no
         assert levels[0] == 0 and level >= 2, levels
         assert all(b - a in (0, 1) for a, b in zip(levels, levels[1:])), levels      # one level at a time, no retreat
         assert len(set(levels[-20:])) == 1, levels                                    # settled
-        _, lt, st = trace[-1]
+        # the settled level's times: the smallest of its last five steps, layer by layer (one step in which the
+        # host thread lost the processor for a while would otherwise decide the asserts below)
+        lt = {k: np.min(np.stack([t[1][k] for t in trace[-5:]]), axis=0) for k in trace[-1][1]}
         # the constraint holds where it settled (layer 0's prefetch has nothing to hide behind)
         assert (lt["swap_in"][1:] <= lt["attn"][1:]).all()
         assert lt["stall"][1:].sum() <= 0.01 * lt["attn"].sum()

@@ -339,7 +339,9 @@ def test_monitoring_by_device_clock_agrees_with_events_and_changes_no_result(pat
     lib.set_layer_compute_us(150.0)
     streams = (torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream())
     res = {}
-    for mode in (B.TIMING_OFF, B.TIMING_EVENTS, B.TIMING_CLOCK, B.TIMING_EVENTS, B.TIMING_CLOCK):
+    # every figure is the smallest of a few steps: a host thread that loses the processor for a scheduling quantum
+    # in the middle of a step (the copy-engine path is paced by the host) adds milliseconds to whatever was running
+    for mode in (B.TIMING_OFF,) + (B.TIMING_EVENTS, B.TIMING_CLOCK) * 4:
         got, pf, dirty = run_step(lib, case, table, streams, timing=mode)
         if mode == B.TIMING_OFF:
             with pytest.raises(B.PieError) as e:
@@ -349,7 +351,11 @@ def test_monitoring_by_device_clock_agrees_with_events_and_changes_no_result(pat
             continue
         assert np.array_equal(got, base)
         st = lib.stats()
-        res[mode] = (lib.layer_times(), st.step_ms, st.attn_ms, st.swap_in_ms, st.stall_ms)
+        new = (lib.layer_times(), st.step_ms, st.attn_ms, st.swap_in_ms, st.stall_ms)
+        if mode in res:
+            old = res[mode]
+            new = ({k: np.minimum(old[0][k], new[0][k]) for k in new[0]},) + tuple(min(a, b) for a, b in zip(old[1:], new[1:]))
+        res[mode] = new
     assert lib.check_errors() == 0
     (le, step_e, attn_e, in_e, stall_e), (lc, step_c, attn_c, in_c, stall_c) = res[B.TIMING_EVENTS], res[B.TIMING_CLOCK]
     for key in ("attn", "kernel", "swap_in", "swap_out"):
