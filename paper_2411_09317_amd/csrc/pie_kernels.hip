@@ -282,6 +282,19 @@ template <> __device__ __forceinline__ float load_elem<BF16>(const void* base, s
   return __uint_as_float((uint32_t)reinterpret_cast<const uint16_t*>(base)[idx] << 16);
 }
 
+// two consecutive elements, idx even
+template <typename E> __device__ __forceinline__ float2 load_elem2(const void* base, size_t idx);
+template <> __device__ __forceinline__ float2 load_elem2<F32>(const void* base, size_t idx) {
+  return *reinterpret_cast<const float2*>(reinterpret_cast<const float*>(base) + idx);
+}
+template <> __device__ __forceinline__ float2 load_elem2<F16>(const void* base, size_t idx) {
+  return __half22float2(*reinterpret_cast<const __half2*>(reinterpret_cast<const __half*>(base) + idx));
+}
+template <> __device__ __forceinline__ float2 load_elem2<BF16>(const void* base, size_t idx) {
+  const uint32_t u = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const uint16_t*>(base) + idx);
+  return make_float2(__uint_as_float(u << 16), __uint_as_float(u & 0xffff0000u));
+}
+
 template <typename E> __device__ __forceinline__ void store_elem(void* base, size_t idx, float v);
 template <> __device__ __forceinline__ void store_elem<F32>(void* base, size_t idx, float v) {
   reinterpret_cast<float*>(base)[idx] = v;
@@ -291,6 +304,18 @@ template <> __device__ __forceinline__ void store_elem<F16>(void* base, size_t i
 }
 template <> __device__ __forceinline__ void store_elem<BF16>(void* base, size_t idx, float v) {
   reinterpret_cast<uint16_t*>(base)[idx] = f32_to_bf16_bits(v);
+}
+
+template <typename E> __device__ __forceinline__ void store_elem2(void* base, size_t idx, float2 v);
+template <> __device__ __forceinline__ void store_elem2<F32>(void* base, size_t idx, float2 v) {
+  *reinterpret_cast<float2*>(reinterpret_cast<float*>(base) + idx) = v;
+}
+template <> __device__ __forceinline__ void store_elem2<F16>(void* base, size_t idx, float2 v) {
+  *reinterpret_cast<__half2*>(reinterpret_cast<__half*>(base) + idx) = __floats2half2_rn(v.x, v.y);
+}
+template <> __device__ __forceinline__ void store_elem2<BF16>(void* base, size_t idx, float2 v) {
+  *reinterpret_cast<uint32_t*>(reinterpret_cast<uint16_t*>(base) + idx) =
+      (uint32_t)f32_to_bf16_bits(v.x) | ((uint32_t)f32_to_bf16_bits(v.y) << 16);
 }
 
 // ---------------------------------------------------------------------------------------------------
@@ -1236,47 +1261,127 @@ __global__ __launch_bounds__(kWaves * 64) void k_attn_decode_f32(const AttnArgs 
 }
 
 // Reduction over the partitions of one (sequence, query head): out = sum_s 2^(m_s - M) acc_s / sum_s 2^(m_s - M) l_s.
-// With the newest token's rows given, that token is one more partition, (q . k_new, 1, v_new), computed here.
-// 256 threads = 256 / HD groups of HD threads (thread (sub, dim) = (tid / HD, tid % HD)), four loads in flight.
-// BY_HEAD (few partitions): every group takes a query head of its own and all of its partitions.  Otherwise
-// (long contexts) the groups share one head, group sub merging the partitions sub, sub + 256/HD, ... online, and
-// the partial merges meet in LDS.
-template <typename E, int HD, bool BY_HEAD>
-__global__ __launch_bounds__(256) void k_attn_reduce(const AttnArgs a, int32_t n_q_heads) {
-  constexpr int NSUB = 256 / HD;
-  constexpr int UNR = 4;
-  constexpr int WPH = (HD + 63) / 64;             // waves per group
-  constexpr int STRIDE = BY_HEAD ? 1 : NSUB;
-  __shared__ float s_M[NSUB], s_L[NSUB], s_A[NSUB][HD];
-  __shared__ float s_dot[NSUB][WPH];
-  const int32_t b = blockIdx.y;
-  const int dim = threadIdx.x % HD, sub = threadIdx.x / HD;
-  const int32_t hq = BY_HEAD ? (int32_t)blockIdx.x * NSUB + sub : (int32_t)blockIdx.x;
-  const bool owner = BY_HEAD || sub == 0;         // writes the head's output
+// With the newest token's rows given, that token is one more partition, (q . k_new, 1, v_new), computed here:
+// s = q . k_new in the log2 domain like the partitions' maxima; the rows are requested first and used after the
+// partitions have been merged.
+//
+// Two forms.  k_attn_reduce_heads, for up to eight partitions per sequence: head_dim / 2 threads per query head,
+// two dims each, 512 / head_dim heads per workgroup, no LDS and no barrier (the launch is as short as its number
+// of workgroups allows: the 8B workload has 8 192 rows).  k_attn_reduce, for long contexts: 256 threads per
+// head, thread (sub, dim) = (tid / HD, tid % HD) merging the partitions sub, sub + 256/HD, ... online, four
+// loads in flight, and the 256/HD partial merges meet in LDS.
+
+struct ReduceRow {
+  int32_t np;        // partitions to merge
+  bool add_new;      // and the newest token
+  bool skip;         // nothing to do: a lone partition wrote the result itself
+};
+__device__ __forceinline__ ReduceRow reduce_row(const AttnArgs& a, int32_t b) {
   const int32_t full = clamp_ctx(a.ctx[b], a.max_blocks);
   const bool with_new = a.new_k != nullptr;
   const int32_t ctx = with_new && full > 0 ? full - 1 : full;   // the tokens the partitions covered
   int32_t np = ctx <= 0 ? 1 : (ctx + a.part_tokens - 1) / a.part_tokens;
   if (np > a.n_parts) np = a.n_parts;
-  if (np <= 1 && !with_new) return;             // a lone partition wrote its result itself
+  return {np, with_new && full > 0, np <= 1 && !with_new};
+}
+
+template <typename E, int HD>
+__global__ __launch_bounds__(256) void k_attn_reduce_heads(const AttnArgs a, int32_t n_q_heads) {
+  constexpr int TPH = HD / 2;                     // threads per head: a wave or half a wave
+  constexpr int HPW = 256 / TPH;
+  constexpr int UNR = 4;
+  static_assert(TPH == 64 || TPH == 32, "a head's threads must be a wave or half a wave");
+  const int32_t b = blockIdx.y;
+  const int d0 = 2 * (threadIdx.x % TPH);
+  const int32_t hq = (int32_t)blockIdx.x * HPW + threadIdx.x / TPH;
+  const ReduceRow r = reduce_row(a, b);
+  if (r.skip) return;
+  if (hq < n_q_heads) {
+    const size_t row = (size_t)b * n_q_heads + hq;
+    float qk = 0.f;
+    float2 v_new = make_float2(0.f, 0.f);
+    if (r.add_new) {
+      const size_t kv_row = ((size_t)b * a.n_kv_heads + hq / a.group) * HD;
+      const float2 q2 = load_elem2<E>(a.q, row * HD + d0), k2 = load_elem2<E>(a.new_k, kv_row + d0);
+      qk = fmaf(q2.x, k2.x, q2.y * k2.y);
+      v_new = load_elem2<E>(a.new_v, kv_row + d0);
+    }
+    const float* w = a.ws + row * a.n_parts * (HD + 2);
+    float M = kNegBig, L = 0.f;
+    float2 A = make_float2(0.f, 0.f);
+    for (int32_t s0 = 0; s0 < r.np; s0 += UNR) {
+      float mi[UNR], li[UNR];
+      float2 ai[UNR];
+#pragma unroll
+      for (int u = 0; u < UNR; ++u) {
+        const bool live = s0 + u < r.np;
+        const float* wp = w + (size_t)(live ? s0 + u : s0) * (HD + 2);
+        mi[u] = live ? wp[0] : kNegBig;
+        li[u] = live ? wp[1] : 0.f;
+        ai[u] = live ? *reinterpret_cast<const float2*>(wp + 2 + d0) : make_float2(0.f, 0.f);
+      }
+      float m_new = M;
+#pragma unroll
+      for (int u = 0; u < UNR; ++u) m_new = fmaxf(m_new, mi[u]);
+      const float corr = __builtin_amdgcn_exp2f(M - m_new);
+      L *= corr;
+      A.x *= corr;
+      A.y *= corr;
+#pragma unroll
+      for (int u = 0; u < UNR; ++u) {
+        const float wt = __builtin_amdgcn_exp2f(mi[u] - m_new);
+        L = fmaf(wt, li[u], L);
+        A.x = fmaf(wt, ai[u].x, A.x);
+        A.y = fmaf(wt, ai[u].y, A.y);
+      }
+      M = m_new;
+    }
+    if (r.add_new) {
+      float d = row16_sum(qk);                    // over the head's threads: rows of 16 lanes, then the rows
+      if constexpr (TPH == 64) d = quad16_sum(d);
+      else d += __shfl_xor(d, 16, 64);
+      const float s_new = d * a.scale_log2e;
+      const float m2 = fmaxf(M, s_new);
+      const float w_old = __builtin_amdgcn_exp2f(M - m2), w_new = __builtin_amdgcn_exp2f(s_new - m2);
+      L = fmaf(L, w_old, w_new);
+      A.x = fmaf(A.x, w_old, w_new * v_new.x);
+      A.y = fmaf(A.y, w_old, w_new * v_new.y);
+    }
+    const float inv = L > 0.f ? 1.f / L : 0.f;
+    store_elem2<E>(a.out, row * HD + d0, make_float2(L > 0.f ? A.x * inv : 0.f, L > 0.f ? A.y * inv : 0.f));
+  }
+  // the last workgroups dispatched are the last to end, to within a few of them: those of the last sequence
+  // and one per 16 sequences note the time
+  if (a.clock && threadIdx.x == 0 && (b == (int32_t)gridDim.y - 1 || (blockIdx.x == 0 && (b & 15) == 15)))
+    atomicMax(&a.clock[kClockLayerEnd], wall_clock64());
+}
+
+template <typename E, int HD>
+__global__ __launch_bounds__(256) void k_attn_reduce(const AttnArgs a, int32_t n_q_heads) {
+  constexpr int NSUB = 256 / HD;
+  constexpr int UNR = 4;
+  constexpr int WPH = (HD + 63) / 64;             // waves that hold a head's q . k_new products
+  __shared__ float s_M[NSUB], s_L[NSUB], s_A[NSUB][HD];
+  __shared__ float s_dot[WPH];
+  const int32_t hq = blockIdx.x, b = blockIdx.y;
+  const int dim = threadIdx.x % HD, sub = threadIdx.x / HD;
+  const ReduceRow r = reduce_row(a, b);
+  if (r.skip) return;
   const size_t row = (size_t)b * n_q_heads + hq;
-  // The newest token is one more partition, (s, 1, v_new) with s = q . k_new in the log2 domain like the
-  // partitions' maxima.  Its rows are requested now and used after the partitions have been merged.
-  const bool add_new = with_new && full > 0;
   float qk = 0.f, v_new = 0.f;
-  if (add_new && owner) {
+  if (r.add_new && sub == 0) {
     const size_t kv_row = ((size_t)b * a.n_kv_heads + hq / a.group) * HD;
     qk = load_elem<E>(a.q, row * HD + dim) * load_elem<E>(a.new_k, kv_row + dim);
     v_new = load_elem<E>(a.new_v, kv_row + dim);
   }
   const float* w = a.ws + row * a.n_parts * (HD + 2);
   float M = kNegBig, L = 0.f, A = 0.f;
-  for (int32_t s0 = BY_HEAD ? 0 : sub; s0 < np; s0 += STRIDE * UNR) {
+  for (int32_t s0 = sub; s0 < r.np; s0 += NSUB * UNR) {
     float mi[UNR], li[UNR], ai[UNR];
 #pragma unroll
     for (int u = 0; u < UNR; ++u) {
-      const int32_t sp = s0 + u * STRIDE;
-      const bool live = sp < np;
+      const int32_t sp = s0 + u * NSUB;
+      const bool live = sp < r.np;
       const float* wp = w + (size_t)(live ? sp : s0) * (HD + 2);
       mi[u] = live ? wp[0] : kNegBig;
       li[u] = live ? wp[1] : 0.f;
@@ -1296,41 +1401,31 @@ __global__ __launch_bounds__(256) void k_attn_reduce(const AttnArgs a, int32_t n
     }
     M = m_new;
   }
-  float Mt = M, Lt = L, At = A;
-  if constexpr (!BY_HEAD) {
-    if (dim == 0) {
-      s_M[sub] = M;
-      s_L[sub] = L;
-    }
-    s_A[sub][dim] = A;
+  if (dim == 0) {
+    s_M[sub] = M;
+    s_L[sub] = L;
   }
-  float dot = 0.f;
-  if (add_new && owner) {                        // HD / 64 waves hold a head's products: each has its sum
-    dot = quad16_sum(row16_sum(qk));             // (in every lane)
-    if (WPH > 1 && (threadIdx.x & 63) == 0) s_dot[sub][(threadIdx.x >> 6) % WPH] = dot;
+  s_A[sub][dim] = A;
+  if (r.add_new && sub == 0) {                   // HD / 64 waves hold the products: each leaves its sum
+    const float wave_sum = quad16_sum(row16_sum(qk));
+    if ((threadIdx.x & 63) == 0) s_dot[threadIdx.x >> 6] = wave_sum;
   }
-  if (!BY_HEAD || (add_new && WPH > 1)) __syncthreads();
-  if (owner) {
-    if constexpr (!BY_HEAD) {
-      Mt = s_M[0];
+  __syncthreads();
+  if (sub == 0) {
+    float Mt = s_M[0];
 #pragma unroll
-      for (int i = 1; i < NSUB; ++i) Mt = fmaxf(Mt, s_M[i]);
-      Lt = 0.f;
-      At = 0.f;
+    for (int i = 1; i < NSUB; ++i) Mt = fmaxf(Mt, s_M[i]);
+    float Lt = 0.f, At = 0.f;
 #pragma unroll
-      for (int i = 0; i < NSUB; ++i) {
-        const float wt = __builtin_amdgcn_exp2f(s_M[i] - Mt);
-        Lt = fmaf(wt, s_L[i], Lt);
-        At = fmaf(wt, s_A[i][dim], At);
-      }
+    for (int i = 0; i < NSUB; ++i) {
+      const float wt = __builtin_amdgcn_exp2f(s_M[i] - Mt);
+      Lt = fmaf(wt, s_L[i], Lt);
+      At = fmaf(wt, s_A[i][dim], At);
     }
-    if (add_new) {
-      float d = dot;
-      if constexpr (WPH > 1) {
-        d = s_dot[sub][0];
+    if (r.add_new) {
+      float d = s_dot[0];
 #pragma unroll
-        for (int i = 1; i < WPH; ++i) d += s_dot[sub][i];
-      }
+      for (int i = 1; i < WPH; ++i) d += s_dot[i];
       const float s_new = d * a.scale_log2e;
       const float m2 = fmaxf(Mt, s_new);
       const float w_old = __builtin_amdgcn_exp2f(Mt - m2), w_new = __builtin_amdgcn_exp2f(s_new - m2);
@@ -1339,9 +1434,7 @@ __global__ __launch_bounds__(256) void k_attn_reduce(const AttnArgs a, int32_t n
     }
     store_elem<E>(a.out, row * HD + dim, Lt > 0.f ? At / Lt : 0.f);
   }
-  // the last workgroups dispatched are the last to end, to within a few of them: those of the last sequence
-  // and one per 16 sequences note the time
-  if (a.clock && threadIdx.x == 0 && (b == (int32_t)gridDim.y - 1 || (blockIdx.x == 0 && (b & 15) == 15)))
+  if (a.clock && threadIdx.x == 0 && (b == (int32_t)gridDim.y - 1 || (hq == 0 && (b & 15) == 15)))
     atomicMax(&a.clock[kClockLayerEnd], wall_clock64());
 }
 
@@ -1466,14 +1559,14 @@ int launch_attn_resolve(const pie_pool* p, const int32_t* d_table, const int32_t
 // done: an event that is to complete with this kernel (it rides on the kernel's own completion signal), or NULL
 template <typename E, int HD>
 static void launch_reduce(const AttnArgs& a, int32_t batch, int32_t n_q_heads, hipStream_t s, hipEvent_t done) {
-  constexpr int NSUB = 256 / HD;
-  // up to eight partitions per sequence: a group of HD threads per query head; beyond, the groups share a head
-  const bool by_head = a.n_parts <= 8 && n_q_heads % NSUB == 0;
-  const dim3 grid(by_head ? n_q_heads / NSUB : n_q_heads, batch);
-  if (by_head)
-    hipExtLaunchKernelGGL((k_attn_reduce<E, HD, true>), grid, dim3(256), 0, s, nullptr, done, 0, a, n_q_heads);
-  else
-    hipExtLaunchKernelGGL((k_attn_reduce<E, HD, false>), grid, dim3(256), 0, s, nullptr, done, 0, a, n_q_heads);
+  if (a.n_parts <= 8) {                           // few partitions per sequence: several heads per workgroup
+    constexpr int HPW = 512 / HD;
+    hipExtLaunchKernelGGL((k_attn_reduce_heads<E, HD>), dim3((n_q_heads + HPW - 1) / HPW, batch), dim3(256), 0, s,
+                          nullptr, done, 0, a, n_q_heads);
+  } else {
+    hipExtLaunchKernelGGL((k_attn_reduce<E, HD>), dim3(n_q_heads, batch), dim3(256), 0, s, nullptr, done, 0, a,
+                          n_q_heads);
+  }
 }
 
 template <typename E, int HD, bool SPLIT, bool VALU = false>
@@ -1570,6 +1663,7 @@ int launch_attn_decode(const pie_pool* p, int32_t layer, const void* d_q, int32_
   a.clock = clock_row;
   a.clock_wg = nullptr;         // set by the launcher of a persistent grid that fits the per-workgroup words
   if ((d_k_new == nullptr) != (d_v_new == nullptr)) return PIE_EINVAL;
+  if (((uintptr_t)d_k_new | (uintptr_t)d_v_new) % 8) return PIE_EINVAL;   // the reduction loads two elements at once
   a.new_k = (const char*)d_k_new;
   a.new_v = (const char*)d_v_new;
   const bool hd128 = c.head_dim == 128;
