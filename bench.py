@@ -33,8 +33,8 @@ LINK_PEAK_GBS = 63.0           # PCIe Gen5 x16, per direction, before protocol o
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="cfg2", choices=["cfg2", "cfg4", "cfg5"])
     ap.add_argument("--layers", type=int, default=None, help="override the number of layers (diagnostics only)")
     ap.add_argument("--ctx-fixed", type=int, default=0, help="diagnostics: give every sequence this context length")
@@ -858,7 +858,7 @@ def main():
     ms_per_step = total_s / args.steps * 1e3
     tokens_per_s = w.batch / (total_s / args.steps)
     prof = layer_profile(dw, streams, none, none)
-    p10, p50, p90 = step_distribution(dw, streams, min(args.steps, 20), none, none)
+    p10, p50, p90 = step_distribution(dw, streams, min(args.steps, 100), none, none)
     assert dw.pool.check_errors() == 0
     k_ms = float(np.mean(prof["kernel"]))
     bytes_layer = dw.kv_bytes_per_layer
