@@ -275,8 +275,9 @@ int pie_attn_stream_probe_sync(pie_pool* pool, int32_t layer, const int32_t* d_b
  * launch on swap_out_stream beside the first layers (compute_stream is ordered after it when the step ends),
  * those of host-homed tails into their staged copies on swap_out_stream once the copy has arrived, and from
  * there layer l's dirty blocks go home at once (the layer only reads them, so append and write-back run beside
- * it; swap_in_stream carries nothing but the copies, back to back).  Behind the last layer, layer 0's blocks are brought in once more for
- * the step that follows (see pie_set_cross_step_prefetch).
+ * it; swap_in_stream carries nothing but the copies, back to back).  Behind the last layer, layer 0's blocks
+ * are brought in once more for the step that follows (see pie_set_cross_step_prefetch).
+ * d_k_new and d_v_new must be 8-byte aligned and stay valid until the step has run.
  * d_q_all, d_out_all: [L][batch][n_q_heads][head_dim]; d_k_new, d_v_new: [L][batch][n_kv_heads][head_dim]
  * (NULL skips the append).  Argument errors are detected before anything is enqueued; a HIP error in the
  * middle (PIE_EHIP) leaves the step partly enqueued. */

@@ -1077,9 +1077,9 @@ static int step_body(pie_pool* p, const StepJob& j) {
     }
     if (n_dirty > 0 && d_k_new) {
       // The attention only reads the staged tail blocks.  So they get the new rows and go home as soon as this
-      // layer's swap-in has completed, beside the layer's computation, not after it: the write-back is then neither something
-      // the host waits for at the layer's end (with the next layer's kernels not yet queued) nor a link in
-      // the chain  layer l ends -> write back -> prefetch layer l + 2 into the same region.
+      // layer's swap-in has completed, beside the layer's computation, not after it: the write-back is then
+      // neither something the host waits for at the layer's end (with the next layer's kernels not yet
+      // queued) nor a link in the chain  layer l ends -> write back -> prefetch layer l + 2 into the region.
       if ((rc = swap_out_impl(p, l, n_dirty, h_dirty, os, mark(p->lev[l].out_start, l, kClockOutStart),
                               mark(p->lev[l].out_end, l, kClockOutEnd), false, job_for(l))))
         return rc;
@@ -1087,7 +1087,8 @@ static int step_body(pie_pool* p, const StepJob& j) {
     }
   }
   // The next step will most likely touch the same host blocks: bring layer 0's in now, behind this step's
-  // last layer, into the region the layer before last has just left.  If anything about those blocks changes first, the copy is repeated.
+  // last layer, into the region the layer before last has just left.  If anything about those blocks changes
+  // first, the copy is repeated.
   if (p->cross_step_prefetch && n_prefetch > 0 && L >= 2) {
     Mark m1;                                     // two marks in turn: the step that uses the copy reads its mark
     p->pre_idx ^= 1;                             // after this step has written the other one
