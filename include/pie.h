@@ -106,7 +106,7 @@ typedef struct {
   float   expansion_simple;     /* 1 / (1 - f): Section 3.1 */
   float   expansion_staged;     /* L / (L (1 - f) + 2 f): Section 3.3's buffer-corrected ratio, block form */
   float   step_ms;              /* first layer's start to last layer's end on the compute stream */
-  float   attn_ms;              /* sum over layers of append + attention time */
+  float   attn_ms;              /* sum over layers of attention + reduction time */
   float   swap_in_ms;           /* sum over layers */
   float   swap_out_ms;
   float   stall_ms;             /* sum over layers of the compute stream's waits for a layer's prefetch */
