@@ -287,6 +287,7 @@ def roofline_of(w, dw, streams, steps, warmup):
     achieved = dw.kv_bytes_per_layer / (k_ms * 1e-3) / 1e9
     traffic, source = traffic_from_profile(f"attn_decode_{w.name}_pmc.txt")
     res = {"tokens_per_s": w.batch / s, "ms_per_step": s * 1e3, "layers": w.n_layers,
+           "attn_partition_tokens": dw.pool.attn_partition(),
            "roofline": {"bound": "hbm", "kernel": "k_attn_decode_mfma", "achieved": achieved, "peak": HBM_PEAK_GBS,
                         "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic, "traffic_source": source,
                         "kernel_ms": k_ms, "algorithmic_bytes_per_launch": dw.kv_bytes_per_layer,
@@ -872,7 +873,8 @@ def main():
                                f"{w.n_kv_heads} kv heads, head_dim {w.head_dim}, block 16, ctx {w.ctx_dist} "
                                f"[{w.ctx_lo},{w.ctx_hi}], all KV GPU-resident",
                    "context_tokens": int(dw.ctx_lens.sum()), "kv_bytes_per_layer": bytes_layer,
-                   "kv_blocks_per_layer": dw.total_blocks, "attn_partition_tokens": args.partition or 512,
+                   "kv_blocks_per_layer": dw.total_blocks, "attn_partition_tokens": dw.pool.attn_partition(),
+                   "attn_partition_chosen_by": "caller" if args.partition else "planning kernel",
                    "t_other_us": args.t_other_us, "layer_weight_bytes": w.layer_weight_bytes,
                    "build_s": round(t_build, 1),
                    # where each part of the named metric ("decode tokens/s & HBM GB/s at X% host-resident KV;

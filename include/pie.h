@@ -191,8 +191,14 @@ int pie_set_host_fraction(pie_pool* pool, float f, int32_t n, const int32_t* ord
 int pie_set_swap_path(pie_pool* pool, int32_t path);
 
 /* Tokens of one sequence handled by one attention workgroup (rounded up to a multiple of 64, clamped to
- * [256, 4096]); longer contexts are split and reduced.  Default 512. */
+ * [256, 4096]); longer contexts are split and reduced.  0, the default: chosen on the device for every batch,
+ * from 512 / 768 / 1024 / 1536 / 2048 / 3072 / 4096, as the largest size that still leaves the persistent decode
+ * grid more than about eight and a half (partition, kv head) units per workgroup (small units even out the
+ * workgroups' different streaming rates, every unit has a fixed cost). */
 int pie_set_attn_partition(pie_pool* pool, int32_t tokens);
+
+/* The size the last attention planning launch used (the one set, or the one chosen).  Waits for the pool. */
+int pie_get_attn_partition_sync(pie_pool* pool, int32_t* out_tokens);
 
 /* 16-bit caches with one query head per kv head (MHA): on != 0 computes the attention's two products on the
  * vector ALU (two-element dot products, fp32 accumulation) instead of the matrix cores, where with a single query

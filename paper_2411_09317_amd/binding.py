@@ -27,7 +27,7 @@ TIMING_OFF, TIMING_EVENTS, TIMING_CLOCK = 0, 1, 2
 SYMBOLS = [
     "pie_pool_bytes_required", "pie_pool_init", "pie_pool_destroy", "pie_block_alloc", "pie_block_free",
     "pie_block_where", "pie_block_staged", "pie_pool_free_count", "pie_block_address", "pie_swap_in", "pie_swap_out",
-    "pie_migrate", "pie_set_host_fraction", "pie_set_swap_path", "pie_set_attn_partition", "pie_set_swap_workgroups",
+    "pie_migrate", "pie_set_host_fraction", "pie_set_swap_path", "pie_set_attn_partition", "pie_get_attn_partition_sync", "pie_set_swap_workgroups",
     "pie_set_layer_compute_us", "pie_set_attn_vector_alu",
     "pie_kv_append", "pie_attn_decode", "pie_attn_decode_static", "pie_attn_stream_probe_sync",
     "pie_step", "pie_set_async_submit", "pie_step_join_sync", "pie_prefetch_list", "pie_set_timing", "pie_set_cross_step_prefetch", "pie_set_host_presence_check", "pie_pool_sync", "pie_get_stats", "pie_get_layer_times",
@@ -235,6 +235,11 @@ class Pool:
 
     def set_attn_partition(self, tokens: int):
         _check(_lib.pie_set_attn_partition(self._h, C.c_int32(tokens)), "set_attn_partition")
+
+    def attn_partition(self) -> int:
+        t = C.c_int32(0)
+        _check(_lib.pie_get_attn_partition_sync(self._h, C.byref(t)), "get_attn_partition_sync")
+        return t.value
 
     def set_swap_workgroups(self, n: int):
         _check(_lib.pie_set_swap_workgroups(self._h, C.c_int32(n)), "set_swap_workgroups")

@@ -159,7 +159,7 @@ struct pie_pool {
 
   // options
   int32_t swap_path = PIE_SWAP_AUTO;
-  int32_t attn_partition = 512;   // tokens per work item (one workgroup)
+  int32_t attn_partition = 0;     // tokens per work item (one workgroup); 0: the planning kernel chooses
   bool attn_valu = false;         // MHA (one query head per kv head): products on the vector ALU, not the matrix cores
   int32_t swap_wgs = 16;          // workgroups of the gather / scatter kernel
   int32_t swap_shape = 0;         // its threads per workgroup * 100 + loads in flight per lane; 0: by transfer size

@@ -606,15 +606,23 @@ __device__ __forceinline__ int32_t clamp_ctx(int32_t ctx, int32_t max_blocks) {
   return ctx > cap ? cap : ctx;
 }
 
+// The item sizes the planning kernel chooses from when none is set: multiples of one pass of a workgroup's waves.
+constexpr int kAutoParts = 7;
+__host__ __device__ constexpr int32_t auto_part(int i) {
+  return i == 0 ? 512 : i == 1 ? 768 : i == 2 ? 1024 : i == 3 ? 1536 : i == 4 ? 2048 : i == 5 ? 3072 : 4096;
+}
+
 // ---- planning: the list of work items ------------------------------------------------------------------
 // items[i] = {sequence | part << 16, context length of the sequence}: item `part` covers the tokens
 // [part * part_tokens, min((part + 1) * part_tokens, context)).  hdr[0] = number of items.  Full items
 // (part_tokens tokens) come first, then one shorter item per sequence whose length is not a multiple of
 // part_tokens (or is <= 0, so that its output is still written), longest first.  With minus = 1 "context" is the
-// context without its last token.  Also zeroes the ticket
+// context without its last token.  hdr[1] = part_tokens: the given one, or with min_units > 0 the one chosen
+// here; every kernel that follows reads it from there.  Also zeroes the ticket
 // counters of all layers and, if a clock table is given, resets its rows and notes the time in the row
 // after the last.
 __global__ __launch_bounds__(256) void k_attn_plan(const int32_t* __restrict__ ctx, int32_t batch, int32_t part_tokens,
+                                                   int32_t min_units, int32_t n_kv_heads,
                                                    int32_t max_blocks, int32_t minus, uint2* __restrict__ items,
                                                    int32_t* __restrict__ hdr, uint32_t* __restrict__ counters,
                                                    int32_t n_counters, uint32_t* __restrict__ err,
@@ -624,15 +632,45 @@ __global__ __launch_bounds__(256) void k_attn_plan(const int32_t* __restrict__ c
   __shared__ int32_t s_ctx[kMaxPlanBatch];  // context length, clamped to [0, what the table can name]
   __shared__ int32_t s_rem[kMaxPlanBatch];   // size of the short item, -1 if none
   __shared__ int32_t s_total_full;
+  __shared__ int32_t s_units[kAutoParts];    // items per candidate item size
+  __shared__ int32_t s_part;
+  if (threadIdx.x < kAutoParts) s_units[threadIdx.x] = 0;
+  __syncthreads();
+  int32_t my_units[kAutoParts] = {};
   for (int32_t b = threadIdx.x; b < batch; b += blockDim.x) {
     const int32_t raw = ctx[b];
     const int32_t full = clamp_ctx(raw, max_blocks);
     if (raw > full) atomicOr(err, PIE_DEVERR_BAD_HANDLE);   // the table cannot name that many blocks
     const int32_t c = full > 0 ? full - minus : full;       // minus = 1: the last token is not read from the cache
+    s_ctx[b] = c > 0 ? c : 0;
+    if (min_units > 0)
+#pragma unroll
+      for (int i = 0; i < kAutoParts; ++i) my_units[i] += c > 0 ? (c + auto_part(i) - 1) / auto_part(i) : 1;
+  }
+  // The item size, when it is not given: the largest candidate that still leaves more than min_units units
+  // (items x kv heads) for the decode kernel's workgroups to share, the smallest candidate if none does.
+  if (min_units > 0) {
+#pragma unroll
+    for (int i = 0; i < kAutoParts; ++i)
+      if (my_units[i]) atomicAdd(&s_units[i], my_units[i]);
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      int32_t pick = auto_part(0);
+      for (int i = 1; i < kAutoParts; ++i)
+        if ((long long)s_units[i] * n_kv_heads > min_units) pick = auto_part(i);
+      s_part = pick;
+    }
+  } else if (threadIdx.x == 0) {
+    s_part = part_tokens;
+  }
+  __syncthreads();
+  part_tokens = s_part;
+  if (threadIdx.x == 0) hdr[1] = part_tokens;
+  for (int32_t b = threadIdx.x; b < batch; b += blockDim.x) {
+    const int32_t c = s_ctx[b];
     const int32_t nf = c > 0 ? c / part_tokens : 0;
     const int32_t rem = c > 0 ? c % part_tokens : 0;
     s_nf[b] = nf;
-    s_ctx[b] = c > 0 ? c : 0;
     s_rem[b] = (rem > 0 || c <= 0) ? rem : -1;
   }
   for (int32_t i = threadIdx.x; i < n_counters; i += blockDim.x) counters[i] = 0;
@@ -683,7 +721,7 @@ struct ResolveArgs {
   const int32_t* map[2];
   int32_t* slots[2];         // NULL to skip a region
   uint32_t* err;
-  int32_t max_blocks, n_handles, n_gpu_blocks, n_slots, blocks_per_item;
+  int32_t max_blocks, n_handles, n_gpu_blocks, n_slots;
   int32_t stage_valid[2];
 };
 
@@ -694,14 +732,15 @@ __global__ __launch_bounds__(64) void k_attn_resolve(const ResolveArgs a) {
   const int32_t b = (int32_t)(rec.x & 0xffffu), part = (int32_t)(rec.x >> 16);
   const int32_t tok1 = (int32_t)rec.y;
   const int32_t jb1 = tok1 > 0 ? (tok1 + kBlockTokens - 1) / kBlockTokens : 0;   // <= max_blocks
-  for (int32_t jj = threadIdx.x; jj < a.blocks_per_item; jj += blockDim.x) {
-    const int32_t j = part * a.blocks_per_item + jj;
+  const int32_t bpi = a.hdr[1] / kBlockTokens;   // blocks per item, as planned
+  for (int32_t jj = threadIdx.x; jj < bpi; jj += blockDim.x) {
+    const int32_t j = part * bpi + jj;
     const bool live = j < jb1;
     const int32_t h = live ? a.table[(size_t)b * a.max_blocks + j] : -1;
 #pragma unroll
     for (int r = 0; r < 2; ++r) {
       if (!a.slots[r]) continue;
-      a.slots[r][(size_t)i * a.blocks_per_item + jj] =
+      a.slots[r][(size_t)i * bpi + jj] =
           live ? resolve_slot(h, a.map[r], a.n_handles, a.n_gpu_blocks, a.n_slots, a.stage_valid[r] != 0, a.err) : -1;
     }
   }
@@ -719,7 +758,8 @@ struct AttnArgs {
   const int32_t* ctx;
   size_t block_bytes;
   float scale_log2e;
-  int32_t max_blocks, n_kv_heads, group, part_tokens, n_parts;
+  int32_t max_blocks, n_kv_heads, group;
+  int32_t n_parts;           // partitions the workspace has room for per (sequence, head); the item size is hdr[1]
   int32_t max_items;         // entries the item list has room for (batch x n_parts)
   unsigned long long* clock;    // this launch's row of the clock table, or NULL
   unsigned long long* clock_wg; // with it: a (first, last moment) pair per workgroup, or NULL (atomics on the row)
@@ -769,7 +809,8 @@ void k_attn_decode_mfma(const AttnArgs a) {
   const uint32_t n_kv = (uint32_t)a.n_kv_heads;
   const uint32_t max_units = (uint32_t)a.max_items * n_kv;        // what the item and slot lists have room for
   const size_t v_off = a.block_bytes / 2;
-  const int32_t bpi = a.part_tokens / kBlockTokens;               // blocks per item, <= 64 * kWaves
+  const int32_t part_tokens = a.hdr[1];                           // the item size the planning kernel noted
+  const int32_t bpi = part_tokens / kBlockTokens;                 // blocks per item, <= 64 * kWaves
   const int32_t my_n = (bpi + kWaves - 1 - wave) / kWaves;        // blocks of an item this wave may own
 
   // Units are handed out by tickets.  A workgroup's first two are static (its index, and its index plus the
@@ -822,8 +863,8 @@ void k_attn_decode_mfma(const AttnArgs a) {
   };
   // blocks of unit (r, u) this wave handles: j = jb0 + wave + kWaves * it, it < n_it (<= 0: nothing)
   auto wave_blocks = [&](const uint2& r) {
-    const int32_t ctx_u = (int32_t)r.y, tok0_u = (int32_t)(r.x >> 16) * a.part_tokens;
-    const int32_t tok1_u = min(ctx_u, tok0_u + a.part_tokens);
+    const int32_t ctx_u = (int32_t)r.y, tok0_u = (int32_t)(r.x >> 16) * part_tokens;
+    const int32_t tok1_u = min(ctx_u, tok0_u + part_tokens);
     const int32_t jb1_u = tok1_u > 0 ? (tok1_u + kBlockTokens - 1) / kBlockTokens : 0;
     return (jb1_u - tok0_u / kBlockTokens - wave + kWaves - 1) / kWaves;
   };
@@ -843,9 +884,9 @@ void k_attn_decode_mfma(const AttnArgs a) {
     const int32_t g = (int32_t)(unit % n_kv);
     const int32_t b = (int32_t)(rec.x & 0xffffu), part = (int32_t)(rec.x >> 16);
     const int32_t ctx_b = (int32_t)rec.y;                          // clamped context length of the sequence
-    const int32_t tok0 = part * a.part_tokens;
-    const int32_t tok1 = min(ctx_b, tok0 + a.part_tokens);         // <= tok0 only for an empty sequence
-    const int32_t np_b = ctx_b > 0 ? (ctx_b + a.part_tokens - 1) / a.part_tokens : 1;   // partitions of the sequence
+    const int32_t tok0 = part * part_tokens;
+    const int32_t tok1 = min(ctx_b, tok0 + part_tokens);         // <= tok0 only for an empty sequence
+    const int32_t np_b = ctx_b > 0 ? (ctx_b + part_tokens - 1) / part_tokens : 1;   // partitions of the sequence
     const int32_t hq0 = g * G;
     const int32_t jb0 = tok0 / kBlockTokens;
     const int32_t n_it = wave_blocks(rec);                         // <= my_n <= 64
@@ -1092,7 +1133,8 @@ __global__ __launch_bounds__(kWaves * 64) void k_stream_probe(const AttnArgs a, 
   const uint32_t n_kv = (uint32_t)a.n_kv_heads;
   const uint32_t n_units = (uint32_t)a.hdr[0] * n_kv;
   const size_t v_off = a.block_bytes / 2;
-  const int32_t bpi = a.part_tokens / kBlockTokens;
+  const int32_t part_tokens = a.hdr[1];
+  const int32_t bpi = part_tokens / kBlockTokens;
   const int32_t my_n = (bpi + kWaves - 1 - wave) / kWaves;
   u32x4 acc = {0, 0, 0, 0};
   uint32_t unit = blockIdx.x;
@@ -1101,8 +1143,8 @@ __global__ __launch_bounds__(kWaves * 64) void k_stream_probe(const AttnArgs a, 
     const uint2 rec = a.items[item];
     int32_t my_slot = -1;
     if (lane < my_n) my_slot = a.slots[(size_t)item * bpi + wave + kWaves * lane];
-    const int32_t ctx_u = (int32_t)rec.y, tok0 = (int32_t)(rec.x >> 16) * a.part_tokens;
-    const int32_t tok1 = min(ctx_u, tok0 + a.part_tokens);
+    const int32_t ctx_u = (int32_t)rec.y, tok0 = (int32_t)(rec.x >> 16) * part_tokens;
+    const int32_t tok1 = min(ctx_u, tok0 + part_tokens);
     const int32_t jb1 = tok1 > 0 ? (tok1 + kBlockTokens - 1) / kBlockTokens : 0;
     const int32_t n_it = (jb1 - tok0 / kBlockTokens - wave + kWaves - 1) / kWaves;
     const size_t head_off = (size_t)(unit % n_kv) * tile_bytes + (size_t)lane * 16;
@@ -1157,13 +1199,14 @@ __global__ __launch_bounds__(kWaves * 64) void k_attn_decode_f32(const AttnArgs 
   const int32_t G = a.group;
   const int32_t n_q_heads = a.n_kv_heads * G;
   const int32_t g = hq / G;
-  const int32_t bpi = a.part_tokens / kBlockTokens;
+  const int32_t part_tokens = a.hdr[1];
+  const int32_t bpi = part_tokens / kBlockTokens;
   const int32_t my_n = (bpi + kWaves - 1 - wave) / kWaves;
   const uint2 rec = a.items[item];
   const int32_t b = (int32_t)(rec.x & 0xffffu), part = (int32_t)(rec.x >> 16);
   const int32_t ctx_b = (int32_t)rec.y;           // clamped context length of the sequence
-  const int32_t tok0 = part * a.part_tokens, tok1 = min(ctx_b, tok0 + a.part_tokens);
-  const int32_t np_b = ctx_b > 0 ? (ctx_b + a.part_tokens - 1) / a.part_tokens : 1;
+  const int32_t tok0 = part * part_tokens, tok1 = min(ctx_b, tok0 + part_tokens);
+  const int32_t np_b = ctx_b > 0 ? (ctx_b + part_tokens - 1) / part_tokens : 1;
   const int32_t jb0 = tok0 / kBlockTokens;
   const int32_t jb1 = tok1 > 0 ? (tok1 + kBlockTokens - 1) / kBlockTokens : 0;
   const int32_t n_it = (jb1 - jb0 - wave + kWaves - 1) / kWaves;
@@ -1280,7 +1323,8 @@ __device__ __forceinline__ ReduceRow reduce_row(const AttnArgs& a, int32_t b) {
   const int32_t full = clamp_ctx(a.ctx[b], a.max_blocks);
   const bool with_new = a.new_k != nullptr;
   const int32_t ctx = with_new && full > 0 ? full - 1 : full;   // the tokens the partitions covered
-  int32_t np = ctx <= 0 ? 1 : (ctx + a.part_tokens - 1) / a.part_tokens;
+  const int32_t part_tokens = a.hdr[1];
+  int32_t np = ctx <= 0 ? 1 : (ctx + part_tokens - 1) / part_tokens;
   if (np > a.n_parts) np = a.n_parts;
   return {np, with_new && full > 0, np <= 1 && !with_new};
 }
@@ -1499,9 +1543,12 @@ static int32_t* plan_slots(const AttnWork& w, int region) {
          (size_t)region * slot_list_ints(w.lay_batch, w.lay_max_blocks);
 }
 
-// item size: a multiple of one pass of the workgroup's waves, at most 64 blocks per wave
+// Item size: a multiple of one pass of the workgroup's waves, at most 64 blocks per wave.  With no size set
+// (attn_partition 0) the planning kernel chooses one of auto_part(); the host then sizes grids and the
+// workspace for the smallest of them, which has the most items.
 static int32_t part_tokens_of(const pie_pool* p) {
   int32_t part = p->attn_partition;
+  if (part <= 0) return auto_part(0);
   const int32_t quantum = kWaves * kBlockTokens;
   if (part < kMinPartTokens) part = kMinPartTokens;
   part = (part + quantum - 1) / quantum * quantum;
@@ -1513,8 +1560,10 @@ int launch_attn_plan(const pie_pool* p, const int32_t* d_ctx, int32_t batch, int
                      bool reset_clock, const AttnWork* work, bool without_last) {
   const AttnWork w = work ? *work : pool_work(p);
   if (batch > kMaxPlanBatch || batch > w.lay_batch || max_blocks > w.lay_max_blocks) return PIE_EINVAL;
-  hipLaunchKernelGGL(k_attn_plan, dim3(1), dim3(256), 0, s, d_ctx, batch, part_tokens_of(p), max_blocks,
-                     without_last ? 1 : 0, plan_items(w),
+  // automatic item size: keep more than about eight and a half units per workgroup of the persistent decode grid
+  const int32_t min_units = p->attn_partition <= 0 ? p->n_cu * 17 : 0;
+  hipLaunchKernelGGL(k_attn_plan, dim3(1), dim3(256), 0, s, d_ctx, batch, part_tokens_of(p), min_units,
+                     p->cfg.n_kv_heads, max_blocks, without_last ? 1 : 0, plan_items(w),
                      plan_hdr(w), plan_counters(w), w.n_counters, p->d_err, reset_clock ? p->d_clock : nullptr);
   PIE_HIP(hipGetLastError());
   return PIE_OK;
@@ -1540,7 +1589,6 @@ int launch_attn_resolve(const pie_pool* p, const int32_t* d_table, const int32_t
   a.n_handles = p->n_handles;
   a.n_gpu_blocks = p->cfg.n_gpu_blocks;
   a.n_slots = p->cfg.n_gpu_blocks + 2 * p->cfg.n_stage_blocks;
-  a.blocks_per_item = part / kBlockTokens;
   a.stage_valid[0] = valid0 ? 1 : 0;
   a.stage_valid[1] = valid1 ? 1 : 0;
   if (view) {                                    // one layer's own handle -> slot map, into the slot list of region 0
@@ -1657,7 +1705,6 @@ int launch_attn_decode(const pie_pool* p, int32_t layer, const void* d_q, int32_
   a.max_blocks = max_blocks;
   a.n_kv_heads = c.n_kv_heads;
   a.group = g;
-  a.part_tokens = part;
   a.n_parts = n_parts;
   a.max_items = batch * n_parts;
   a.clock = clock_row;
@@ -1703,7 +1750,6 @@ int launch_stream_probe(const pie_pool* p, int32_t layer, int32_t max_blocks, in
   a.counter = plan_counters(w) + layer;
   a.block_bytes = p->block_bytes;
   a.n_kv_heads = c.n_kv_heads;
-  a.part_tokens = part;
   const size_t tile_bytes = (size_t)kBlockTokens * c.head_dim * p->elem_bytes;
   uint32_t* sink = p->d_err + 1;                  // a spare word of the error page
   const int grid = p->n_cu * 2;

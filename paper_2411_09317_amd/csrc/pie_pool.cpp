@@ -470,7 +470,7 @@ int pie_pool_init(const pie_config* cfg, void* d_base, size_t d_bytes, void* h_p
   }
   p->h_kv = (char*)h_pinned_base;
   // tuning hooks for experiments; the defaults are what the benchmarks use
-  if (const char* e = std::getenv("PIE_ATTN_PART")) { const int v = std::atoi(e); if (v > 0) p->attn_partition = v; }
+  if (const char* e = std::getenv("PIE_ATTN_PART")) { const int v = std::atoi(e); if (v >= 0) p->attn_partition = v; }
   if (const char* e = std::getenv("PIE_DMA_STREAM_ORDER")) p->dma_stream_order = std::atoi(e) != 0;
   if (const char* e = std::getenv("PIE_SWAP_SHAPE")) { const int v = std::atoi(e); if (v > 0) p->swap_shape = v; }
   if (device) {
@@ -773,9 +773,18 @@ int pie_set_swap_path(pie_pool* p, int32_t path) {
 }
 
 int pie_set_attn_partition(pie_pool* p, int32_t tokens) {
-  if (!p || tokens <= 0) return PIE_EINVAL;
+  if (!p || tokens < 0) return PIE_EINVAL;
   PIE_DRAIN(p);
   p->attn_partition = tokens;
+  return PIE_OK;
+}
+
+int pie_get_attn_partition_sync(pie_pool* p, int32_t* out_tokens) {
+  if (!p || !out_tokens) return PIE_EINVAL;
+  if (!p->device) return PIE_ESTATE;
+  int rc = pie_pool_sync(p);
+  if (rc) return rc;
+  PIE_HIP(hipMemcpy(out_tokens, p->d_plan + 1, sizeof(int32_t), hipMemcpyDeviceToHost));
   return PIE_OK;
 }
 

@@ -97,10 +97,13 @@ def test_partition_size_does_not_change_the_result_beyond_rounding():
     lib, mod, table = GH.make_pools(case, int(case.n_blocks.sum()), 4, 4)
     ref = A.dense_attention(*H.dense_f64(case, 0), case.ctx_lens)
     outs = []
-    for part in (256, 512, 1024, 4096):
+    for part in (256, 512, 1000, 4096, 0):
         lib.set_attn_partition(part)
         outs.append(run_attn(lib, case, table))
         check(outs[-1], ref, w.dtype)
+        # what the kernels used: the size set, rounded up to a multiple of 64; left to the library (0), a batch
+        # this small gets the smallest of the sizes it chooses from
+        assert lib.attn_partition() == {256: 256, 512: 512, 1000: 1024, 4096: 4096, 0: 512}[part]
     lib.close()
 
 

@@ -50,6 +50,19 @@ def oracle_rows(dw, layer, b):
     return A.dense_attention(q[None], [K], [V], np.array([ctx]))[0]
 
 
+def expected_partition(dw, new_token=True):
+    """The item size the planning kernel is documented to choose: the largest of its candidates that leaves more
+    than 17 x (compute units) (partition, kv head) units, the smallest candidate if none does."""
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    ctx = dw.ctx_lens.astype(np.int64) - (1 if new_token else 0)
+    pick = 512
+    for p in (768, 1024, 1536, 2048, 3072, 4096):
+        units = int(np.maximum(1, -(-ctx // p)).sum()) * dw.w.n_kv_heads
+        if units > 17 * cus:
+            pick = p
+    return pick
+
+
 def run_steps(dw, pf, dirty, n=1):
     streams = (torch.cuda.Stream(), torch.cuda.Stream(), torch.cuda.Stream())
     for _ in range(n):
@@ -143,6 +156,7 @@ def test_llama2_7b_shape_all_resident_then_thirty_percent_on_the_host():
     dw = WL.build(I.CONFIGS["cfg2"], host_capacity_fraction=0.32)
     try:
         run_steps(dw, none, none, n=2)
+        assert dw.pool.attn_partition() == expected_partition(dw)
         samples = sample_pairs(dw, 6, 0)
         check_samples(dw, samples)
         resident = dw.out.clone()
@@ -175,6 +189,7 @@ def test_llama3_8b_shape_gqa_bf16_all_resident_then_ten_percent_on_the_host():
     dw = WL.build(I.CONFIGS["cfg4"], host_capacity_fraction=0.12)
     try:
         run_steps(dw, none, none, n=2)
+        assert dw.pool.attn_partition() == expected_partition(dw)
         samples = sample_pairs(dw, 6, 1)
         check_samples(dw, samples)
         resident = dw.out.clone()
@@ -202,6 +217,7 @@ def test_70b_shape_long_context_per_layer_shape_on_four_layers():
     dw = WL.build(I.CONFIGS["cfg5"], n_layers=4, host_capacity_fraction=0.225)
     try:
         run_steps(dw, none, none, n=1)
+        assert dw.pool.attn_partition() == expected_partition(dw) > 512
         check_samples(dw, [(0, 0), (3, 17), (2, 31)])
         resident = dw.out.clone()
         hs = WL.per_sequence_host_order(dw, 0.215)
