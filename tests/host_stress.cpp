@@ -62,6 +62,11 @@ static void stress_pool(int iters) {
         REQUIRE(rc == PIE_OK || rc == PIE_ESTATE);
         rc = pie_set_swap_workgroups(p, ri(-1, 1030));
         REQUIRE(rc == PIE_OK || rc == PIE_EINVAL);
+        const int tokens = ri(-2, 5000);
+        REQUIRE(pie_set_attn_partition(p, tokens) == (tokens < 0 ? PIE_EINVAL : PIE_OK));
+        int32_t used = -7;
+        REQUIRE(pie_get_attn_partition_sync(p, &used) == PIE_ESTATE && used == -7);   // no device: nothing planned
+        REQUIRE(pie_get_attn_partition_sync(p, nullptr) == PIE_EINVAL);
         break;
       }
     }
